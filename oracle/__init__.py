@@ -1,0 +1,164 @@
+"""fp64 CPU oracle for the five image stages.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around ``hb_oracle.c`` (plain C loops, double precision).
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package; the HIP library and its Python binding
+never do, and this package imports nothing from them.
+
+fp16 arrays are ``numpy.uint16`` bit patterns; results are ``numpy.float64``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hb_oracle.c")
+_LIB = os.path.join(_HERE, "libhb_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile hb_oracle.c with gcc (a second or two)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        i32p = ctypes.POINTER(ctypes.c_int)
+        I, Lg = ctypes.c_int, ctypes.c_long
+        L.hbo_half_to_double.argtypes = [ctypes.c_uint16]
+        L.hbo_half_to_double.restype = ctypes.c_double
+        L.hbo_num_threads.restype = I
+        L.hbo_set_num_threads.argtypes = [I]
+        L.hbo_fir1d.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I]
+        L.hbo_sepblur.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, u16p, I, I]
+        L.hbo_sat2d.argtypes = [u16p, f64p, I, I, Lg, Lg]
+        L.hbo_conv3x3.argtypes = [u16p, u16p, f64p, I, I, I, I, I]
+        L.hbo_conv3x3_rows.argtypes = [u16p, u16p, f64p, I, I, I, I, I, I, I]
+        L.hbo_conv3x3_points.argtypes = [u16p, u16p, f64p, I, I, I, I, I, Lg, i32p, i32p, i32p]
+        L.hbo_pyr_level.argtypes = [u16p, f64p, f64p, I, I, Lg, Lg, Lg]
+        for f in (L.hbo_set_num_threads, L.hbo_fir1d, L.hbo_sepblur, L.hbo_sat2d, L.hbo_conv3x3,
+                  L.hbo_conv3x3_rows, L.hbo_conv3x3_points, L.hbo_pyr_level):
+            f.restype = None
+        _lib = L
+    return _lib
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
+
+
+def _f64(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def num_threads() -> int:
+    return int(_load().hbo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().hbo_set_num_threads(int(n))
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().hbo_half_to_double(int(bits)))
+
+
+def fir1d(img, taps, anchor):
+    """out[y][x] = sum_r k[r] in[y][clampW(x + r - anchor)]  (Sec. V-A 1-D form)."""
+    img, pi = _u16(img)
+    taps, pt = _u16(taps)
+    H, W = img.shape
+    out = np.empty((H, W), dtype=np.float64)
+    _load().hbo_fir1d(pi, _f64(out), H, W, W, W, pt, len(taps), int(anchor))
+    return out
+
+
+def sepblur(img, taps_x, anchor_x, taps_y, anchor_y):
+    """Row FIR then column FIR, clamp-to-edge, fp64 intermediate."""
+    img, pi = _u16(img)
+    tx, ptx = _u16(taps_x)
+    ty, pty = _u16(taps_y)
+    H, W = img.shape
+    out = np.empty((H, W), dtype=np.float64)
+    _load().hbo_sepblur(pi, _f64(out), H, W, W, W, ptx, len(tx), int(anchor_x),
+                        pty, len(ty), int(anchor_y))
+    return out
+
+
+def sat2d(img):
+    """Inclusive 2-D prefix sum."""
+    img, pi = _u16(img)
+    H, W = img.shape
+    out = np.empty((H, W), dtype=np.float64)
+    _load().hbo_sat2d(pi, _f64(out), H, W, W, W)
+    return out
+
+
+def conv3x3(x_nhwc, w_hwio):
+    """3x3, zero pad 1, stride 1, NHWC x HWIO -> NHWC (fp64, unrounded)."""
+    x, px = _u16(x_nhwc)
+    w, pw = _u16(w_hwio)
+    N, H, W, Ci = x.shape
+    assert w.shape[:3] == (3, 3, Ci)
+    Co = w.shape[3]
+    out = np.empty((N, H, W, Co), dtype=np.float64)
+    _load().hbo_conv3x3(px, pw, _f64(out), N, H, W, Ci, Co)
+    return out
+
+
+def conv3x3_rows(x_nhwc, w_hwio, y0, y1):
+    """Output rows y0..y1-1 only, returned as an (N, y1-y0, W, Cout) array."""
+    x, px = _u16(x_nhwc)
+    w, pw = _u16(w_hwio)
+    N, H, W, Ci = x.shape
+    Co = w.shape[3]
+    assert N == 1, "row-band variant is used on single images"
+    full = np.empty((N, H, W, Co), dtype=np.float64)   # virtual memory; only the band is touched
+    _load().hbo_conv3x3_rows(px, pw, _f64(full), N, H, W, Ci, Co, int(y0), int(y1))
+    return full[:, y0:y1].copy()
+
+
+def conv3x3_points(x_nhwc, w_hwio, ns, ys, xs):
+    """All Cout channels at the listed (n, y, x) positions -> (npts, Cout)."""
+    x, px = _u16(x_nhwc)
+    w, pw = _u16(w_hwio)
+    N, H, W, Ci = x.shape
+    Co = w.shape[3]
+    ns = np.ascontiguousarray(ns, dtype=np.int32)
+    ys = np.ascontiguousarray(ys, dtype=np.int32)
+    xs = np.ascontiguousarray(xs, dtype=np.int32)
+    out = np.empty((len(ys), Co), dtype=np.float64)
+    i32p = ctypes.POINTER(ctypes.c_int)
+    _load().hbo_conv3x3_points(px, pw, _f64(out), N, H, W, Ci, Co, len(ys),
+                               ns.ctypes.data_as(i32p), ys.ctypes.data_as(i32p),
+                               xs.ctypes.data_as(i32p))
+    return out
+
+
+def pyr_level(img, want_down: bool = False):
+    """Residual of one Laplacian level with the [1,4,6,4,1]/16 kernel (and D if asked)."""
+    img, pi = _u16(img)
+    H, W = img.shape
+    assert H % 2 == 0 and W % 2 == 0
+    res = np.empty((H, W), dtype=np.float64)
+    down = np.empty((H // 2, W // 2), dtype=np.float64) if want_down else None
+    _load().hbo_pyr_level(pi, _f64(res), _f64(down) if want_down else None,
+                          H, W, W, W, W // 2)
+    return (res, down) if want_down else res
