@@ -1,0 +1,169 @@
+/*
+ * hb -- five image-processing stages recast as dense products with fixed
+ * Toeplitz / strided-Toeplitz / phase / triangular coefficient matrices and run
+ * on the MI355X (gfx950) matrix units, after "Pushing Tensor Accelerators
+ * beyond MatMul in a User-Schedulable Language" (Sec. V-A, V-B).
+ *
+ * C ABI.  Plain pointers and sizes only.
+ *
+ * Common conventions
+ * ------------------
+ *  - hb_half is an IEEE binary16 bit pattern.
+ *  - Every `in`, `out`, `residual`, `down`, `w`, `workspace` pointer is a DEVICE
+ *    pointer owned by the caller.  `taps*_host` pointers are HOST pointers; they
+ *    are read during the call and travel to the GPU inside the kernel arguments,
+ *    so the caller may free or change them as soon as the call returns.
+ *  - Single-channel images are row-major; pitches are in ELEMENTS (not bytes) and
+ *    must be >= the width.  Any H, W >= 1 is computed correctly.  The vectorised
+ *    path needs 16-byte aligned base pointers, input pitches that are multiples of
+ *    8 and output pitches that are multiples of 4; other layouts take a slower
+ *    element-wise path inside the same kernels.
+ *  - Orientation is correlation, as the paper prints it: O(x) = sum_r I(x + r) K(r).
+ *    `anchor` shifts the window, tap r reads x + r - anchor; anchor = 0 is the
+ *    paper's formula verbatim.  Output has the size of the input; out-of-range
+ *    reads clamp the INPUT index to the edge (zero padding for hb_conv3x3).
+ *  - Arithmetic: fp16 operands, fp32 accumulation on the matrix units.
+ *  - `stream` is a hipStream_t (passed as void* so that this header needs no HIP
+ *    include).  All work is enqueued on it; no call synchronises, allocates, frees
+ *    or keeps a pointer.  Input and output buffers must not overlap.
+ *  - Errors: the return code only.  Arguments are validated before any HIP call
+ *    (HB_ERR_INVALID_ARG / HB_ERR_UNSUPPORTED / HB_ERR_WORKSPACE); a launch failure
+ *    reported by the runtime gives HB_ERR_HIP.  Faults inside a kernel surface at
+ *    the caller's next synchronisation, as for any asynchronous launch.
+ *  - Thread safety: the library keeps no mutable global state; calls on different
+ *    streams may run concurrently provided their buffers (and SAT workspaces) are
+ *    distinct.
+ *  - Every stage has a `_valu` twin with the same signature and results that uses
+ *    only vector-ALU FMAs (no MFMA): the ablation that shows what the matrix units
+ *    buy.
+ */
+#ifndef HB_H
+#define HB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HB_OK = 0,
+    HB_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, pitch < width, bad taps/anchor ... */
+    HB_ERR_UNSUPPORTED = 2,   /* valid request outside what the kernels implement */
+    HB_ERR_WORKSPACE = 3,     /* workspace missing, misaligned or too small */
+    HB_ERR_HIP = 4            /* the HIP runtime rejected a launch */
+} hb_status;
+
+typedef uint16_t hb_half;
+typedef void *hb_stream;      /* hipStream_t */
+
+#define HB_MAX_TAPS 64
+
+/* Human-readable name of a status code (static storage). */
+const char *hb_status_string(hb_status s);
+
+/*
+ * Row-wise 1-D FIR (Sec. V-A, 1-D convolution as a product with the Toeplitz
+ * matrix A_K(x, y) = K(y - x)):
+ *     out[y][x] = sum_{r < ntaps} taps[r] * in[y][clampW(x + r - anchor)]
+ * in: H x W fp16, out: H x W fp32.  1 <= ntaps <= HB_MAX_TAPS, 0 <= anchor < ntaps.
+ */
+hb_status hb_fir1d(const hb_half *in, float *out, int H, int W,
+                   int64_t in_pitch, int64_t out_pitch,
+                   const hb_half *taps_host, int ntaps, int anchor, hb_stream stream);
+hb_status hb_fir1d_valu(const hb_half *in, float *out, int H, int W,
+                        int64_t in_pitch, int64_t out_pitch,
+                        const hb_half *taps_host, int ntaps, int anchor, hb_stream stream);
+
+/*
+ * Separable 2-D blur (Sec. V-A, the 2-D form with K(rx, ry) = kx[rx] ky[ry]; the
+ * second axis is a second Toeplitz product with the coefficient matrix on the
+ * left):
+ *     tmp[y][x] = sum_r taps_x[r] * in[y][clampW(x + r - anchor_x)]    (rounded to fp16)
+ *     out[y][x] = sum_r taps_y[r] * tmp[clampH(y + r - anchor_y)][x]
+ * in: H x W fp16, out: H x W fp32; tmp never leaves the chip.
+ */
+hb_status hb_sepblur(const hb_half *in, float *out, int H, int W,
+                     int64_t in_pitch, int64_t out_pitch,
+                     const hb_half *taps_x_host, int ntaps_x, int anchor_x,
+                     const hb_half *taps_y_host, int ntaps_y, int anchor_y, hb_stream stream);
+hb_status hb_sepblur_valu(const hb_half *in, float *out, int H, int W,
+                          int64_t in_pitch, int64_t out_pitch,
+                          const hb_half *taps_x_host, int ntaps_x, int anchor_x,
+                          const hb_half *taps_y_host, int ntaps_y, int anchor_y, hb_stream stream);
+
+/*
+ * Summed-area table (inclusive prefix sum over rows and columns; a product
+ * L * X * U with triangular all-ones matrices per tile plus inter-tile carries --
+ * the tile-then-fix-up structure of Sec. V-D applied to a first-order recursion):
+ *     out[i][j] = sum_{y <= i} sum_{x <= j} in[y][x]
+ * in: H x W fp16, out: H x W fp32.  `workspace` is device scratch of at least
+ * hb_sat2d_workspace_size(H, W) bytes, 256-byte aligned; its contents on entry do
+ * not matter and are undefined on exit.  Two calls that run concurrently need
+ * two workspaces.
+ */
+size_t hb_sat2d_workspace_size(int H, int W);
+hb_status hb_sat2d(const hb_half *in, float *out, int H, int W,
+                   int64_t in_pitch, int64_t out_pitch,
+                   void *workspace, size_t workspace_bytes, hb_stream stream);
+hb_status hb_sat2d_valu(const hb_half *in, float *out, int H, int W,
+                        int64_t in_pitch, int64_t out_pitch,
+                        void *workspace, size_t workspace_bytes, hb_stream stream);
+
+/*
+ * Multi-channel 3x3 convolution, stride 1, zero padding 1 (Sec. V-A 2-D form summed
+ * over input channels; the conv layer of Sec. IV without bias and activation), as an
+ * implicit GEMM with M = pixels, N = Cout, K = 9 * Cin:
+ *     out[n][y][x][co] = sum_{ky,kx < 3} sum_ci in[n][y+ky-1][x+kx-1][ci] * w[ky][kx][ci][co]
+ * in: N x H x W x Cin fp16 (NHWC, dense), w: 3 x 3 x Cin x Cout fp16 (HWIO, dense),
+ * out: N x H x W x Cout fp16 (fp32 accumulator rounded to nearest even).
+ * Cin and Cout must both be 64 (HB_ERR_UNSUPPORTED otherwise); pointers 16-byte aligned.
+ */
+hb_status hb_conv3x3(const hb_half *in_nhwc, const hb_half *w_hwio, hb_half *out_nhwc,
+                     int N, int H, int W, int Cin, int Cout, hb_stream stream);
+hb_status hb_conv3x3_valu(const hb_half *in_nhwc, const hb_half *w_hwio, hb_half *out_nhwc,
+                          int N, int H, int W, int Cin, int Cout, hb_stream stream);
+
+/*
+ * One Laplacian-pyramid level with the fixed kernel w = [1,4,6,4,1]/16 (Sec. V-B:
+ * 2x downsample as a product with A_down(x, y) = K(y - 2x), 2x upsample as a
+ * two-phase filter K_phase(x, dx) = K(2x + dx) whose phases are interleaved before
+ * the store):
+ *     D[m][n]  = sum_{i,j=-2..2} w[i] w[j] in[clampH(2m+i)][clampW(2n+j)]      (H/2 x W/2, fp16 on chip)
+ *     per axis:  U[2n] = (D[c(n-1)] + 6 D[n] + D[c(n+1)]) / 8,  U[2n+1] = (D[n] + D[c(n+1)]) / 2
+ *                (c clamps the D index to its extent), along x then along y
+ *     residual = in - U                                                        (H x W, fp32)
+ * H and W must be even.  `down_or_null`, when not null, receives D rounded to fp16
+ * (H/2 x W/2, pitch down_pitch); pass NULL (and any pitch) to skip it.
+ */
+hb_status hb_pyr_level(const hb_half *in, float *residual, hb_half *down_or_null,
+                       int H, int W, int64_t in_pitch, int64_t res_pitch, int64_t down_pitch,
+                       hb_stream stream);
+hb_status hb_pyr_level_valu(const hb_half *in, float *residual, hb_half *down_or_null,
+                            int H, int W, int64_t in_pitch, int64_t res_pitch, int64_t down_pitch,
+                            hb_stream stream);
+
+/*
+ * Measurement helper, not a stage: out[i] = (float) in[i] for n elements with 16-byte
+ * vector accesses.  It moves the same 2 B in + 4 B out per element as the streaming
+ * stages and serves as the achievable-bandwidth reference.  n >= 1; pointers 16-byte
+ * aligned.
+ */
+hb_status hb_copy_f16_f32(const hb_half *in, float *out, int64_t n, hb_stream stream);
+
+/*
+ * Self-check helper, not a stage: runs one v_mfma_f32_16x16x32_f16 (which = 0),
+ * one v_mfma_f32_16x16x16_f16 (which = 1), one v_mfma_f32_32x32x16_f16 (which = 2) or
+ * one v_mfma_f32_16x16x4_f32 (which = 3) on dense row-major operands A (M x K) and
+ * B (K x N) gathered through the operand-to-lane maps the kernels assume, and
+ * scatters the accumulator to row-major D (M x N, fp32).  A test multiplies random
+ * matrices and compares with a host product, which checks those maps.  A and B are
+ * fp16 for which 0..2 and fp32 for which 3.
+ */
+hb_status hb_mfma_probe(int which, const void *A, const void *B, float *D, hb_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HB_H */

@@ -1,0 +1,108 @@
+// Device-side building blocks shared by the gfx950 kernels: vector types, MFMA
+// wrappers with their operand-to-lane maps, edge-aware row loads and stores.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hb {
+
+typedef _Float16 half_t;
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------
+// Operand-to-lane maps on a 64-lane wave (lane = 16*g + c for the 16-wide shapes).
+//
+// v_mfma_f32_16x16x32_f16   D[16x16] += A[16x32] * B[32x16]
+//   A: lane (c, g) holds A[c][8g .. 8g+7]        (8 halves)
+//   B: lane (c, g) holds B[8g .. 8g+7][c]        (8 halves)
+//   D: lane (c, g) holds D[4g .. 4g+3][c]        (4 floats)
+// v_mfma_f32_16x16x16_f16   D[16x16] += A[16x16] * B[16x16]
+//   A: lane (c, g) holds A[c][4g .. 4g+3];  B: lane (c, g) holds B[4g .. 4g+3][c];  D as above
+// v_mfma_f32_16x16x4_f32    D[16x16] += A[16x4] * B[4x16]
+//   A: lane (c, g) holds A[c][g];  B: lane (c, g) holds B[g][c];  D as above
+// v_mfma_f32_32x32x16_f16   D[32x32] += A[32x16] * B[16x32]      (lane = 32*h + c)
+//   A: lane (c, h) holds A[c][8h .. 8h+7];  B: lane (c, h) holds B[8h .. 8h+7][c]
+//   D: lane (c, h) holds D[8q + 4h + r][c] in register 4q + r  (q, r = 0..3)
+//
+// Because a D fragment holds, per lane, a run of the ROW index for a fixed column,
+// a D fragment rounded to fp16 is already a valid A or B fragment of a following
+// product that contracts over that row index: no transpose, no LDS round trip.
+// Two stacked 16-row D fragments t = 0, 1 form one K = 32 operand whose k-slot
+// 8g + i stands for row 16*(i/4) + 4g + (i%4); the coefficient operand is built
+// with the same slot order (see krow32 below), which leaves the sum unchanged.
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ floatx4 mfma16x16x32(half8 a, half8 b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ floatx4 mfma16x16x16(half4 a, half4 b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ floatx4 mfma16x16x4f32(float a, float b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ floatx16 mfma32x32x16(half8 a, half8 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+// Row (within a 32-row window made of two stacked 16-row D fragments) that k-slot
+// 8g + i of a chained K = 32 operand stands for.
+__device__ __forceinline__ int krow32(int g, int i) { return 16 * (i >> 2) + 4 * g + (i & 3); }
+
+// Two D fragments (rows 0..15 and 16..31 of a window), rounded to fp16 (RNE), as
+// one K = 32 operand in the slot order of krow32.
+__device__ __forceinline__ half8 chain2(floatx4 lo, floatx4 hi) {
+    half8 r;
+    r[0] = (half_t)lo[0]; r[1] = (half_t)lo[1]; r[2] = (half_t)lo[2]; r[3] = (half_t)lo[3];
+    r[4] = (half_t)hi[0]; r[5] = (half_t)hi[1]; r[6] = (half_t)hi[2]; r[7] = (half_t)hi[3];
+    return r;
+}
+__device__ __forceinline__ half4 to_half4(floatx4 v) {
+    half4 r;
+    r[0] = (half_t)v[0]; r[1] = (half_t)v[1]; r[2] = (half_t)v[2]; r[3] = (half_t)v[3];
+    return r;
+}
+__device__ __forceinline__ half8 join(half4 lo, half4 hi) {
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// Eight consecutive pixels row[xs .. xs+7] with the column index clamped to [0, W-1].
+// One 16-byte load when the run is inside the row and the layout allows it.
+__device__ __forceinline__ half8 load8_clamp(const half_t* __restrict__ row, int xs, int W, bool vec_ok) {
+    if (vec_ok && xs >= 0 && xs + 8 <= W) {
+        return *reinterpret_cast<const half8*>(row + xs);
+    }
+    half8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = row[clampi(xs + i, 0, W - 1)];
+    return r;
+}
+
+// Four consecutive pixels row[xs .. xs+3], clamped like load8_clamp.
+__device__ __forceinline__ half4 load4_clamp(const half_t* __restrict__ row, int xs, int W, bool vec_ok) {
+    if (vec_ok && xs >= 0 && xs + 4 <= W) {
+        return *reinterpret_cast<const half4*>(row + xs);
+    }
+    half4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = row[clampi(xs + i, 0, W - 1)];
+    return r;
+}
+
+// Store four consecutive floats at row[x .. x+3], dropping columns >= W.
+__device__ __forceinline__ void store4_mask(float* __restrict__ row, int x, int W, floatx4 v, bool vec_ok) {
+    if (vec_ok && x + 4 <= W) {
+        *reinterpret_cast<floatx4*>(row + x) = v;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (x + i < W) row[x + i] = v[i];
+    }
+}
+
+}  // namespace hb

@@ -1,0 +1,71 @@
+"""Boundary checks that need no GPU: the library loads, exports every declared
+symbol, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2512_02371_amd import hb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hb.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return hb.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(os.path.join(ROOT, "include", "hb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(hb_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(hb.SYMBOLS)
+    for s in declared:
+        assert hasattr(lib, s), s
+
+
+def test_status_strings(lib):
+    assert hb.status_string(0) == "HB_OK"
+    assert hb.status_string(1) == "HB_ERR_INVALID_ARG"
+    assert hb.status_string(3) == "HB_ERR_WORKSPACE"
+
+
+FAKE = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+TAPS = np.zeros(8, dtype=np.uint16).ctypes.data_as(ctypes.c_void_p)
+_keep = np.zeros(8, dtype=np.uint16)
+TAPS = _keep.ctypes.data_as(ctypes.c_void_p)
+
+
+@pytest.mark.parametrize("fn", ["hb_fir1d", "hb_fir1d_valu"])
+def test_fir_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    ok = dict(i=FAKE, o=FAKE, H=16, W=16, ip=16, op=16, t=TAPS, n=8, a=3)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["H"], p["W"], p["ip"], p["op"], p["t"], p["n"], p["a"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(t=None) == hb.HB_ERR_INVALID_ARG
+    assert call(H=0) == hb.HB_ERR_INVALID_ARG
+    assert call(W=-1) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=15) == hb.HB_ERR_INVALID_ARG
+    assert call(op=8) == hb.HB_ERR_INVALID_ARG
+    assert call(n=0) == hb.HB_ERR_INVALID_ARG
+    assert call(n=65) == hb.HB_ERR_INVALID_ARG
+    assert call(a=-1) == hb.HB_ERR_INVALID_ARG
+    assert call(a=8) == hb.HB_ERR_INVALID_ARG
+    assert call(i=ctypes.c_void_p(0x1001)) == hb.HB_ERR_INVALID_ARG
+
+
+def test_copy_and_probe_validation(lib):
+    assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
+    assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
+    assert lib.hb_copy_f16_f32(ctypes.c_void_p(0x1004), FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
+    assert lib.hb_mfma_probe(4, FAKE, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
+    assert lib.hb_mfma_probe(0, None, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
