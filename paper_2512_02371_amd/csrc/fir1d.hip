@@ -6,17 +6,23 @@
 // product by stacking overlapped segments of ONE row (Eq. 1).  An image already
 // has the second dimension: 16 image rows are the 16 independent vectors, so the
 // image operand is read straight from memory in its natural layout (each lane: 8
-// consecutive pixels of one row, one 16-byte load) and no overlapped view has to
-// be staged.  We compute the transposed tile
-//     D'[m][n] = sum_k A[m][k] * P[k][n],   m = output column in a 16-wide tile,
+// consecutive pixels of one row, one 16-byte load at any pixel offset) and no
+// overlapped view has to be staged.  For a 16-column output tile starting at x0 the
+// window is the 32*NK pixels from x0 - anchor - e on (e = anchor & 1 keeps the window
+// on an even pixel, i.e. dword aligned: 16-byte loads at odd pixel offsets run at a
+// fraction of the rate), and we compute the transposed tile
+//     D'[m][n] = sum_k A[m][k] * P[k][n],   m = output column in the tile,
 //                                            n = image row in a 16-row group,
-//                                            k = pixel inside an aligned 32-pixel block,
-// with A[m][k] = taps[32*delta + k - (16*par + m) + anchor] (zero outside the taps),
-// one A fragment per (half-block par, neighbouring block delta), built once per
-// wave.  In D' a lane owns four consecutive output columns of one row, so the
-// result leaves with one 16-byte store per lane.
+//                                            k = pixel in the window,
+// with A[m][k] = taps[k - m - e] (zero outside the taps): A_K itself, built once per
+// wave from a zero-padded tap table.  In D' a lane owns four consecutive output
+// columns of one row, so the result leaves with one 16-byte store per lane.
 #include "hb_device.hpp"
 #include "hb_host.hpp"
+
+#ifndef HB_FIR_TILES
+#define HB_FIR_TILES 4        // 16-column tiles per wave task
+#endif
 
 namespace hb {
 
@@ -26,10 +32,8 @@ struct FirArgs {
     int H, W;
     int64_t in_pitch, out_pitch;
     int T, anchor;
-    int dmin;            // first neighbouring block (relative) that a 32-column output block reads
-    int nct;             // 64-column tiles per row
+    int nct;             // column tasks per row group
     int ntasks;          // (16-row groups) x nct
-    int vec_in, vec_out; // layouts allow 16-byte accesses
     Taps taps;
 };
 
@@ -37,51 +41,64 @@ __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
     return __builtin_bit_cast(half_t, b);
 }
 
-template <int ND>
+template <int NK, bool STREAM>
 __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
-    __shared__ half_t s_taps[HB_MAX_TAPS];
-    if (threadIdx.x < HB_MAX_TAPS) s_taps[threadIdx.x] = tap_from_bits(p.taps.v[threadIdx.x]);
+    __shared__ half_t s_tab[kTapLen];
+    fill_tap_table(s_tab, p.taps.v, p.T);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
 
-    // Toeplitz fragments, A-operand layout: lane (c, g) holds A[c][8g .. 8g+7].
-    half8 coef[2][ND];
+    // Toeplitz fragments, A-operand layout: lane (c, g) holds A[c][32kk + 8g + i] = taps[32kk + 8g + i - c - e].
+    const int e = p.anchor & 1;
+    const int aw = p.anchor + e;              // window start, left of the tile
+    half8 coef[NK];
 #pragma unroll
-    for (int par = 0; par < 2; ++par)
-#pragma unroll
-        for (int d = 0; d < ND; ++d)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int t = 32 * (p.dmin + d) + 8 * g + i - (16 * par + c) + p.anchor;
-                coef[par][d][i] = (t >= 0 && t < p.T) ? s_taps[t] : (half_t)0;
-            }
+    for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(s_tab, 32 * kk + 8 * g - c - e);
 
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const uint32_t lane_in = (uint32_t)c * (uint32_t)p.in_pitch + 8u * g;
+    const uint32_t lane_out = (uint32_t)c * (uint32_t)p.out_pitch + 4u * g;
+
+    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int task = wave; task < p.ntasks; task += nwaves) {
         const int rg = task / p.nct, ct = task - rg * p.nct;
-        const int y = 16 * rg + c;
-        const half_t* row = p.in + (int64_t)min(y, p.H - 1) * p.in_pitch;
-        const int x0 = 64 * ct;
-
-        half8 blk[ND + 1];
+        const int y0 = 16 * rg, x0 = 16 * HB_FIR_TILES * ct;
+        const bool interior = (y0 + 16 <= p.H) && (x0 - aw >= 0) &&
+                              (x0 + 16 * (HB_FIR_TILES - 1) - aw + 32 * NK <= p.W) &&
+                              (x0 + 16 * HB_FIR_TILES <= p.W);
+        if (interior) {
+            // whole task inside the image: uniform bases, 32-bit lane offsets, no masks
+            const half_t* src = p.in + (int64_t)y0 * p.in_pitch + (x0 - aw);
+            float* dst = p.out + (int64_t)y0 * p.out_pitch + x0;
+            const uint32_t bin = 2u * lane_in, bout = 4u * lane_out;
+            half8 win[HB_FIR_TILES][NK];
 #pragma unroll
-        for (int j = 0; j <= ND; ++j)
-            blk[j] = load8_clamp(row, x0 + 32 * (p.dmin + j) + 8 * g, p.W, p.vec_in);
-
-        float* orow = p.out + (int64_t)y * p.out_pitch;
+            for (int j = 0; j < HB_FIR_TILES; ++j)
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
+                for (int kk = 0; kk < NK; ++kk)
+                    win[j][kk] = ldg8(src, bin + 2u * (16u * j + 32u * kk));
 #pragma unroll
-            for (int par = 0; par < 2; ++par) {
+            for (int j = 0; j < HB_FIR_TILES; ++j) {
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int d = 0; d < ND; ++d) acc = mfma16x16x32(coef[par][d], blk[tb + d], acc);
-                const int xo = x0 + 32 * tb + 16 * par + 4 * g;
-                if (y < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc, p.vec_out);
+                for (int kk = 0; kk < NK; ++kk) acc = mfma16x16x32(coef[kk], win[j][kk], acc);
+                stg4<STREAM>(dst, bout + 64u * j, acc);
             }
+        } else {
+            const int y = y0 + c;
+            const half_t* row = p.in + (int64_t)min(y, p.H - 1) * p.in_pitch;
+            float* orow = p.out + (int64_t)y * p.out_pitch;
+            for (int j = 0; j < HB_FIR_TILES; ++j) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk)
+                    acc = mfma16x16x32(coef[kk], load8_clamp(row, x0 + 16 * j - aw + 32 * kk + 8 * g, p.W), acc);
+                const int xo = x0 + 16 * j + 4 * g;
+                if (y < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc);
+            }
+        }
     }
 }
 
@@ -104,7 +121,7 @@ __global__ void __launch_bounds__(256) fir1d_valu_kernel(FirArgs p) {
     for (int idx = threadIdx.x; idx < 16 * nch; idx += 256) {
         const int r = idx / nch, ch = idx - r * nch;
         const half_t* row = p.in + (int64_t)min(16 * rg + r, p.H - 1) * p.in_pitch;
-        half8 v = load8_clamp(row, x0 - lead + 8 * ch, p.W, p.vec_in);
+        half8 v = load8_clamp(row, x0 - lead + 8 * ch, p.W);
         *reinterpret_cast<half8*>(&s_px[r * kValuPitch + 8 * ch]) = v;
     }
     __syncthreads();
@@ -128,7 +145,7 @@ __global__ void __launch_bounds__(256) fir1d_valu_kernel(FirArgs p) {
                 if (t >= 0 && t < p.T) acc[q] = fmaf(s_k[t], v, acc[q]);
             }
         }
-        store4_mask(orow, x0 + xl, p.W, acc, p.vec_out);
+        store4_mask(orow, x0 + xl, p.W, acc);
     }
 }
 
@@ -147,11 +164,8 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
     a.out_pitch = out_pitch;
     a.T = ntaps;
     a.anchor = anchor;
-    a.dmin = floor_div(-anchor, 32);
-    a.nct = ceil_div(W, 64);
+    a.nct = ceil_div(W, 16 * HB_FIR_TILES);
     a.ntasks = ceil_div(H, 16) * a.nct;
-    a.vec_in = aligned_to(in, 16) && (in_pitch % 8 == 0);
-    a.vec_out = aligned_to(out, 16) && (out_pitch % 4 == 0);
     a.taps = pack_taps(taps_host, ntaps);
     return HB_OK;
 }
@@ -165,17 +179,21 @@ extern "C" hb_status hb_fir1d(const hb_half* in, float* out, int H, int W,
     FirArgs a;
     hb_status s = fir1d_prepare(a, in, out, H, W, in_pitch, out_pitch, taps_host, ntaps, anchor);
     if (s != HB_OK) return s;
-    // blocks dmin .. dmax (relative) hold the pixels a 32-column output block reads
-    const int dmax = floor_div(31 - anchor + ntaps - 1, 32);
-    const int nd = dmax - a.dmin + 1;
+    // a 16-column tile reads the 16 + ntaps - 1 pixels from x0 - anchor on (one more when the
+    // window is moved to an even pixel): NK windows of 32
+    const int nk = ceil_div(15 + ntaps + (anchor & 1), 32);
     const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    switch (nd) {
-        case 1: hipLaunchKernelGGL(fir1d_mfma_kernel<1>, dim3(blocks), dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL(fir1d_mfma_kernel<2>, dim3(blocks), dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL(fir1d_mfma_kernel<3>, dim3(blocks), dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL(fir1d_mfma_kernel<4>, dim3(blocks), dim3(256), 0, st, a); break;
-        default: return HB_ERR_UNSUPPORTED;
+    const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
+    if (nk < 1 || nk > 3) return HB_ERR_UNSUPPORTED;
+    if (ss) {
+        if (nk == 1) hipLaunchKernelGGL((fir1d_mfma_kernel<1, true>), dim3(blocks), dim3(256), 0, st, a);
+        if (nk == 2) hipLaunchKernelGGL((fir1d_mfma_kernel<2, true>), dim3(blocks), dim3(256), 0, st, a);
+        if (nk == 3) hipLaunchKernelGGL((fir1d_mfma_kernel<3, true>), dim3(blocks), dim3(256), 0, st, a);
+    } else {
+        if (nk == 1) hipLaunchKernelGGL((fir1d_mfma_kernel<1, false>), dim3(blocks), dim3(256), 0, st, a);
+        if (nk == 2) hipLaunchKernelGGL((fir1d_mfma_kernel<2, false>), dim3(blocks), dim3(256), 0, st, a);
+        if (nk == 3) hipLaunchKernelGGL((fir1d_mfma_kernel<3, false>), dim3(blocks), dim3(256), 0, st, a);
     }
     return launch_status();
 }

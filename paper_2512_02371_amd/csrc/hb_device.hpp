@@ -71,11 +71,17 @@ __device__ __forceinline__ half8 join(half4 lo, half4 hi) {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// Vector types with element alignment only: gfx950 under HSA runs with unaligned
+// access enabled, so a 16-byte access needs no more than the alignment of its elements.
+typedef half8 half8_u __attribute__((aligned(2)));
+typedef half4 half4_u __attribute__((aligned(2)));
+typedef floatx4 floatx4_u __attribute__((aligned(4)));
+
 // Eight consecutive pixels row[xs .. xs+7] with the column index clamped to [0, W-1].
-// One 16-byte load when the run is inside the row and the layout allows it.
-__device__ __forceinline__ half8 load8_clamp(const half_t* __restrict__ row, int xs, int W, bool vec_ok) {
-    if (vec_ok && xs >= 0 && xs + 8 <= W) {
-        return *reinterpret_cast<const half8*>(row + xs);
+// One 16-byte load (any 2-byte aligned address) when the run lies inside the row.
+__device__ __forceinline__ half8 load8_clamp(const half_t* __restrict__ row, int xs, int W) {
+    if (xs >= 0 && xs + 8 <= W) {
+        return *reinterpret_cast<const half8_u*>(row + xs);
     }
     half8 r;
 #pragma unroll
@@ -84,9 +90,9 @@ __device__ __forceinline__ half8 load8_clamp(const half_t* __restrict__ row, int
 }
 
 // Four consecutive pixels row[xs .. xs+3], clamped like load8_clamp.
-__device__ __forceinline__ half4 load4_clamp(const half_t* __restrict__ row, int xs, int W, bool vec_ok) {
-    if (vec_ok && xs >= 0 && xs + 4 <= W) {
-        return *reinterpret_cast<const half4*>(row + xs);
+__device__ __forceinline__ half4 load4_clamp(const half_t* __restrict__ row, int xs, int W) {
+    if (xs >= 0 && xs + 4 <= W) {
+        return *reinterpret_cast<const half4_u*>(row + xs);
     }
     half4 r;
 #pragma unroll
@@ -95,14 +101,49 @@ __device__ __forceinline__ half4 load4_clamp(const half_t* __restrict__ row, int
 }
 
 // Store four consecutive floats at row[x .. x+3], dropping columns >= W.
-__device__ __forceinline__ void store4_mask(float* __restrict__ row, int x, int W, floatx4 v, bool vec_ok) {
-    if (vec_ok && x + 4 <= W) {
-        *reinterpret_cast<floatx4*>(row + x) = v;
+__device__ __forceinline__ void store4_mask(float* __restrict__ row, int x, int W, floatx4 v) {
+    if (x + 4 <= W) {
+        *reinterpret_cast<floatx4_u*>(row + x) = v;
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if (x + i < W) row[x + i] = v[i];
     }
+}
+
+// Accesses through a wave-uniform base plus a 32-bit per-lane BYTE offset: the form the
+// hardware addresses with a scalar base register and one vector offset register.
+__device__ __forceinline__ half8 ldg8(const half_t* base, uint32_t byte_off) {
+    return *reinterpret_cast<const half8_u*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ half4 ldg4(const half_t* base, uint32_t byte_off) {
+    return *reinterpret_cast<const half4_u*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+// Output stores.  STREAM = true marks the lines non-temporal (written once, not read back
+// by the kernel): faster while the output of one call is small against the 256 MB
+// memory-side cache, slower beyond it, so the host picks per call.
+template <bool STREAM>
+__device__ __forceinline__ void stg4(float* base, uint32_t byte_off, floatx4 v) {
+    floatx4_u* q = reinterpret_cast<floatx4_u*>(reinterpret_cast<char*>(base) + byte_off);
+    if (STREAM) __builtin_nontemporal_store(v, q); else *q = v;
+}
+// Outputs up to this many bytes per call are written with streaming stores.
+constexpr int64_t kStreamStoreMaxBytes = (int64_t)128 << 20;
+
+// Zero-padded tap table in LDS: entry kTapPad + t holds taps[t] for 0 <= t < ntaps and
+// zero for every other t in [-kTapPad, kTapLen - kTapPad).  A Toeplitz fragment is then
+// eight consecutive entries, fetched with one (unaligned) 16-byte LDS read.
+constexpr int kTapPad = 16;
+constexpr int kTapLen = 16 + 64 + 48;
+
+__device__ __forceinline__ void fill_tap_table(half_t* tab, const uint16_t* taps_bits, int ntaps) {
+    for (int i = threadIdx.x; i < kTapLen; i += blockDim.x) {
+        const int t = i - kTapPad;
+        tab[i] = (t >= 0 && t < ntaps) ? __builtin_bit_cast(half_t, taps_bits[t]) : (half_t)0;
+    }
+}
+__device__ __forceinline__ half8 tap_run(const half_t* tab, int t0) {
+    return *reinterpret_cast<const half8_u*>(tab + kTapPad + t0);
 }
 
 }  // namespace hb

@@ -14,10 +14,11 @@ struct Taps {
     uint16_t v[HB_MAX_TAPS];
 };
 
-// MI355X: 256 compute units, 4 SIMDs each.  Streaming kernels launch at most this
-// many 256-thread workgroups and let every wave walk a strided list of tasks.
+// MI355X: 256 compute units, 4 SIMDs each.  Streaming kernels launch one short-lived
+// wave per task (the dispatcher keeps the memory pipes fed best that way); beyond this
+// many 256-thread workgroups every wave walks a strided list of tasks instead.
 constexpr int kNumCU = 256;
-constexpr int kMaxStreamBlocks = kNumCU * 8;
+constexpr int kMaxStreamBlocks = 1 << 20;
 
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -27,9 +28,8 @@ inline hb_status check_image(const void* in, const void* out, int H, int W,
     if (H < 1 || W < 1) return HB_ERR_INVALID_ARG;
     if (in_pitch < W || out_pitch < W) return HB_ERR_INVALID_ARG;
     if (!aligned_to(in, 2) || !aligned_to(out, 4)) return HB_ERR_INVALID_ARG;
-    // rows are addressed with 32-bit element offsets inside a row and 64-bit row bases
-    if ((int64_t)H * in_pitch > ((int64_t)1 << 40) || (int64_t)H * out_pitch > ((int64_t)1 << 40))
-        return HB_ERR_UNSUPPORTED;
+    // lanes address a 16-row group with 32-bit byte offsets from a 64-bit group base
+    if (in_pitch > ((int64_t)1 << 26) || out_pitch > ((int64_t)1 << 26)) return HB_ERR_UNSUPPORTED;
     return HB_OK;
 }
 

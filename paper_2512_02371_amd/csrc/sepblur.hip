@@ -1,10 +1,11 @@
 // hb_sepblur: separable 2-D blur as two chained Toeplitz products per tile
 // (Sec. V-A), and its vector-ALU twin.
 //
-// MFMA formulation.  A wave owns a 64-column strip and walks down it in steps of
-// 16 rows.
+// MFMA formulation.  A wave owns a strip of HB_SEP_TILES 16-column tiles and walks
+// down it in steps of 16 rows.
 //   row pass     T1[m][n] = sum_k P[m][k] * Bx[k][n]     m = image row, n = column, k = pixel
-//                Bx[k][n] = taps_x[32*delta + k - (16*par + n) + anchor_x]
+//                P = the 32*NKX pixels from x0 - ax - e on (e = ax & 1: even, dword-aligned
+//                window start),   Bx[k][n] = taps_x[k - n - e]
 //   column pass  O'[m][n] = sum_k T1h[m][k] * By[k][n]   m = column, n = output row, k = window row
 //                By[k][n] = taps_y[window_row(k) - n]
 // The row-pass accumulator holds, per lane, four consecutive ROWS of one column,
@@ -21,9 +22,17 @@
 // consecutive tiles and produces one new tile.  Rows outside the image repeat the
 // edge row: clamping the image row index at the load is the same as clamping the
 // index of the row-filtered intermediate, because the row pass treats rows
-// independently.
+// independently.  The pixels of the next row tile are requested before the current
+// one is multiplied, so a wave always has one tile of loads in flight.
 #include "hb_device.hpp"
 #include "hb_host.hpp"
+
+#ifndef HB_SEP_TILES
+#define HB_SEP_TILES 4        // 16-column tiles per wave strip
+#endif
+#ifndef HB_SEP_WAVES
+#define HB_SEP_WAVES 4096     // aim for about this many wave tasks per launch
+#endif
 
 namespace hb {
 
@@ -33,101 +42,136 @@ struct SepArgs {
     int H, W;
     int64_t in_pitch, out_pitch;
     int Tx, ax, Ty, ay;
-    int dmin;          // first neighbouring 32-pixel block a 32-column output block reads
-    int nct;           // 64-column strips
+    int nct;           // strips
     int steps;         // 16-row steps per task
     int nseg;          // row segments per strip
     int ntasks;        // nct * nseg
-    int vec_in, vec_out;
     Taps tx, ty;
 };
 
 __device__ __forceinline__ half_t sep_tap(uint16_t b) { return __builtin_bit_cast(half_t, b); }
 
-template <int ND, int NT>
+// One task: a strip of NW tiles, nsteps output steps.  XIN = every window of the strip
+// lies inside the row and every tile is full (no column clamp, no store mask).
+template <int NKX, int NT, bool XIN, bool STREAM>
+__device__ __forceinline__ void sep_task(const SepArgs& p, const half8 (&coefx)[NKX],
+                                         const half8 (&coefy)[(NT + 1) / 2],
+                                         int x0, int Y0, int nsteps, int xw, int c, int g) {
+    constexpr int NK = (NT + 1) / 2;
+    constexpr int NW = HB_SEP_TILES;
+    const int ntiles = nsteps + NT - 1;
+    const half_t* src = p.in + (x0 - xw);                 // uniform; lanes add row * pitch + 8g
+    float* dst = p.out + x0;
+
+    half4 hist[NT][NW];                                   // row-filtered tiles q .. q+NT-1
+#pragma unroll
+    for (int q = 0; q < NT; ++q)
+#pragma unroll
+        for (int w = 0; w < NW; ++w) hist[q][w] = half4{0, 0, 0, 0};
+
+    auto load_tile = [&](int q, half8 (&dstw)[NW][NKX]) {
+        // tile q covers image rows Y0 - ay + 16 q + (0..15), clamped to the image
+        const int yr = clampi(Y0 - p.ay + 16 * q + c, 0, p.H - 1);
+        if (XIN) {
+            const uint32_t off = ((uint32_t)yr * (uint32_t)p.in_pitch + 8u * g) * 2u;
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int kk = 0; kk < NKX; ++kk) dstw[w][kk] = ldg8(src, off + 2u * (16u * w + 32u * kk));
+        } else {
+            const half_t* row = p.in + (int64_t)yr * p.in_pitch;
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int kk = 0; kk < NKX; ++kk)
+                    dstw[w][kk] = load8_clamp(row, x0 + 16 * w - xw + 32 * kk + 8 * g, p.W);
+        }
+    };
+
+    half8 cur[NW][NKX], nxt[NW][NKX];
+    load_tile(0, cur);
+    for (int q = 0; q < ntiles; ++q) {
+        if (q + 1 < ntiles) load_tile(q + 1, nxt);
+#pragma unroll
+        for (int u = 0; u < NT - 1; ++u)
+#pragma unroll
+            for (int w = 0; w < NW; ++w) hist[u][w] = hist[u + 1][w];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < NKX; ++kk) acc = mfma16x16x32(cur[w][kk], coefx[kk], acc);
+            hist[NT - 1][w] = to_half4(acc);
+        }
+        const int s = q - (NT - 1);                       // output step completed by this tile
+        if (s >= 0) {
+            const int yo = Y0 + 16 * s + c;
+            floatx4 acc[NW];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < NK; ++j) {
+                    const half4 lo = hist[2 * j][w];
+                    const half4 hi = (2 * j + 1 < NT) ? hist[2 * j + 1][w] : half4{0, 0, 0, 0};
+                    acc[w] = mfma16x16x32(join(lo, hi), coefy[j], acc[w]);
+                }
+            }
+            if (XIN) {
+                if (yo < p.H) {
+                    const uint32_t off = ((uint32_t)yo * (uint32_t)p.out_pitch + 4u * g) * 4u;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
+                }
+            } else {
+                float* orow = p.out + (int64_t)yo * p.out_pitch;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const int xo = x0 + 16 * w + 4 * g;
+                    if (yo < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc[w]);
+                }
+            }
+        }
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+#pragma unroll
+            for (int kk = 0; kk < NKX; ++kk) cur[w][kk] = nxt[w][kk];
+    }
+}
+
+template <int NKX, int NT, bool STREAM>
 __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
     constexpr int NK = (NT + 1) / 2;          // K = 32 chunks of the column pass
-    __shared__ half_t s_tx[HB_MAX_TAPS], s_ty[HB_MAX_TAPS];
-    if (threadIdx.x < HB_MAX_TAPS) {
-        s_tx[threadIdx.x] = sep_tap(p.tx.v[threadIdx.x]);
-        s_ty[threadIdx.x] = sep_tap(p.ty.v[threadIdx.x]);
-    }
+    constexpr int NW = HB_SEP_TILES;
+    __shared__ half_t s_tx[kTapLen], s_ty[kTapLen];
+    fill_tap_table(s_tx, p.tx.v, p.Tx);
+    fill_tap_table(s_ty, p.ty.v, p.Ty);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
 
-    half8 coefx[2][ND];                       // B operand of the row pass
+    const int e = p.ax & 1;
+    const int xw = p.ax + e;                  // window start, left of the tile
+    half8 coefx[NKX];                         // B operand of the row pass: Bx[32kk + 8g + i][c]
 #pragma unroll
-    for (int par = 0; par < 2; ++par)
-#pragma unroll
-        for (int d = 0; d < ND; ++d)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int t = 32 * (p.dmin + d) + 8 * g + i - (16 * par + c) + p.ax;
-                coefx[par][d][i] = (t >= 0 && t < p.Tx) ? s_tx[t] : (half_t)0;
-            }
+    for (int kk = 0; kk < NKX; ++kk) coefx[kk] = tap_run(s_tx, 32 * kk + 8 * g - c - e);
     half8 coefy[NK];                          // B operand of the column pass, chained slot order
 #pragma unroll
     for (int j = 0; j < NK; ++j)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int t = 32 * j + krow32(g, i) - c;
-            coefy[j][i] = (t >= 0 && t < p.Ty) ? s_ty[t] : (half_t)0;
-        }
+        for (int i = 0; i < 8; ++i) coefy[j][i] = s_ty[kTapPad + 32 * j + krow32(g, i) - c];
 
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int task = wave; task < p.ntasks; task += nwaves) {
         const int seg = task / p.nct, ct = task - seg * p.nct;
-        const int x0 = 64 * ct;
+        const int x0 = 16 * NW * ct;
         const int Y0 = seg * p.steps * 16;
         const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
-
-        half4 hist[NT][4];                    // row-filtered tiles q .. q+NT-1, four 16-column tiles each
-#pragma unroll
-        for (int q = 0; q < NT; ++q)
-#pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) hist[q][t4] = half4{0, 0, 0, 0};
-
-        // tile q covers image rows Y0 - ay + 16 q + (0..15)
-        for (int q = 0; q < nsteps + NT - 1; ++q) {
-            const int yr = clampi(Y0 - p.ay + 16 * q + c, 0, p.H - 1);
-            const half_t* row = p.in + (int64_t)yr * p.in_pitch;
-            half8 blk[ND + 1];
-#pragma unroll
-            for (int j = 0; j <= ND; ++j)
-                blk[j] = load8_clamp(row, x0 + 32 * (p.dmin + j) + 8 * g, p.W, p.vec_in);
-#pragma unroll
-            for (int u = 0; u < NT - 1; ++u)
-#pragma unroll
-                for (int t4 = 0; t4 < 4; ++t4) hist[u][t4] = hist[u + 1][t4];
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int par = 0; par < 2; ++par) {
-                    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int d = 0; d < ND; ++d) acc = mfma16x16x32(blk[tb + d], coefx[par][d], acc);
-                    hist[NT - 1][2 * tb + par] = to_half4(acc);
-                }
-            const int s = q - (NT - 1);       // output step completed by this tile
-            if (s < 0) continue;
-            const int yo = Y0 + 16 * s + c;
-            float* orow = p.out + (int64_t)yo * p.out_pitch;
-#pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < NK; ++j) {
-                    const half4 lo = hist[2 * j][t4];
-                    const half4 hi = (2 * j + 1 < NT) ? hist[2 * j + 1][t4] : half4{0, 0, 0, 0};
-                    acc = mfma16x16x32(join(lo, hi), coefy[j], acc);
-                }
-                const int xo = x0 + 16 * t4 + 4 * g;
-                if (yo < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc, p.vec_out);
-            }
-        }
+        const bool xin = (x0 - xw >= 0) && (x0 + 16 * (NW - 1) - xw + 32 * NKX <= p.W) && (x0 + 16 * NW <= p.W);
+        if (xin) sep_task<NKX, NT, true, STREAM>(p, coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        else sep_task<NKX, NT, false, STREAM>(p, coefx, coefy, x0, Y0, nsteps, xw, c, g);
     }
 }
 
@@ -157,7 +201,7 @@ __global__ void __launch_bounds__(256) sepblur_valu_kernel(SepArgs p) {
         const int r = idx / nch, ch = idx - r * nch;
         const half_t* row = p.in + (int64_t)clampi(y0 - p.ay + r, 0, p.H - 1) * p.in_pitch;
         *reinterpret_cast<half8*>(&s_px[r * kVPxPitch + 8 * ch]) =
-            load8_clamp(row, x0 - lead + 8 * ch, p.W, p.vec_in);
+            load8_clamp(row, x0 - lead + 8 * ch, p.W);
     }
     __syncthreads();
     const int off = lead - p.ax;
@@ -187,7 +231,7 @@ __global__ void __launch_bounds__(256) sepblur_valu_kernel(SepArgs p) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) acc[q] = fmaf(k, (float)v[q], acc[q]);
         }
-        store4_mask(p.out + (int64_t)y * p.out_pitch, x, p.W, acc, p.vec_out);
+        store4_mask(p.out + (int64_t)y * p.out_pitch, x, p.W, acc);
     }
 }
 
@@ -208,31 +252,33 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
     a.ax = ax;
     a.Ty = nty;
     a.ay = ay;
-    a.dmin = floor_div(-ax, 32);
-    a.nct = ceil_div(W, 64);
+    a.nct = ceil_div(W, 16 * HB_SEP_TILES);
     const int rowsteps = ceil_div(H, 16);
     // enough tasks to fill the chip, few enough that the (NT-1)-tile warm-up stays small
-    int steps = (int)(((int64_t)rowsteps * a.nct) / 4096);
-    steps = steps < 1 ? 1 : (steps > 16 ? 16 : steps);
+    int steps = (int)(((int64_t)rowsteps * a.nct) / HB_SEP_WAVES);
+    steps = steps < 1 ? 1 : (steps > 64 ? 64 : steps);
     a.steps = steps;
     a.nseg = ceil_div(rowsteps, steps);
     a.ntasks = a.nct * a.nseg;
-    a.vec_in = aligned_to(in, 16) && (in_pitch % 8 == 0);
-    a.vec_out = aligned_to(out, 16) && (out_pitch % 4 == 0);
     a.tx = pack_taps(tx, ntx);
     a.ty = pack_taps(ty, nty);
     return HB_OK;
 }
 
-template <int ND>
+template <int NKX, bool STREAM>
 static void sep_launch_nt(int nt, int blocks, hipStream_t st, const SepArgs& a) {
     switch (nt) {
-        case 1: hipLaunchKernelGGL((sepblur_mfma_kernel<ND, 1>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((sepblur_mfma_kernel<ND, 2>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((sepblur_mfma_kernel<ND, 3>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((sepblur_mfma_kernel<ND, 4>), dim3(blocks), dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((sepblur_mfma_kernel<ND, 5>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 1, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 2, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 3, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 4, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 5, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
     }
+}
+template <int NKX>
+static void sep_launch(bool stream_stores, int nt, int blocks, hipStream_t st, const SepArgs& a) {
+    if (stream_stores) sep_launch_nt<NKX, true>(nt, blocks, st, a);
+    else sep_launch_nt<NKX, false>(nt, blocks, st, a);
 }
 
 }  // namespace hb
@@ -246,16 +292,15 @@ extern "C" hb_status hb_sepblur(const hb_half* in, float* out, int H, int W,
     hb_status s = sep_prepare(a, in, out, H, W, in_pitch, out_pitch, taps_x_host, ntaps_x, anchor_x,
                               taps_y_host, ntaps_y, anchor_y);
     if (s != HB_OK) return s;
-    const int dmax = floor_div(31 - anchor_x + ntaps_x - 1, 32);
-    const int nd = dmax - a.dmin + 1;
+    const int nkx = ceil_div(15 + ntaps_x + (anchor_x & 1), 32);
     const int nt = (ntaps_y + 30) / 16;
     const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    switch (nd) {
-        case 1: sep_launch_nt<1>(nt, blocks, st, a); break;
-        case 2: sep_launch_nt<2>(nt, blocks, st, a); break;
-        case 3: sep_launch_nt<3>(nt, blocks, st, a); break;
-        case 4: sep_launch_nt<4>(nt, blocks, st, a); break;
+    const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
+    switch (nkx) {
+        case 1: sep_launch<1>(ss, nt, blocks, st, a); break;
+        case 2: sep_launch<2>(ss, nt, blocks, st, a); break;
+        case 3: sep_launch<3>(ss, nt, blocks, st, a); break;
         default: return HB_ERR_UNSUPPORTED;
     }
     return launch_status();
