@@ -44,7 +44,9 @@ __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
 template <int NK, bool STREAM>
 __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     __shared__ half_t s_tab[kTapLen];
+    __shared__ FoldTables s_fold;
     fill_tap_table(s_tab, p.taps.v, p.T);
+    fill_fold_tables(s_fold, p.taps.v, p.T);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -57,8 +59,9 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(s_tab, 32 * kk + 8 * g - c - e);
 
-    const uint32_t lane_in = (uint32_t)c * (uint32_t)p.in_pitch + 8u * g;
-    const uint32_t lane_out = (uint32_t)c * (uint32_t)p.out_pitch + 4u * g;
+    const uint32_t bin = 2u * ((uint32_t)c * (uint32_t)p.in_pitch + 8u * g);
+    const uint32_t bout = 4u * ((uint32_t)c * (uint32_t)p.out_pitch + 4u * g);
+    const int wmax = p.W - 32 * NK;           // last window start that stays inside the row
 
     const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
@@ -72,13 +75,11 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
             // whole task inside the image: uniform bases, 32-bit lane offsets, no masks
             const half_t* src = p.in + (int64_t)y0 * p.in_pitch + (x0 - aw);
             float* dst = p.out + (int64_t)y0 * p.out_pitch + x0;
-            const uint32_t bin = 2u * lane_in, bout = 4u * lane_out;
             half8 win[HB_FIR_TILES][NK];
 #pragma unroll
             for (int j = 0; j < HB_FIR_TILES; ++j)
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk)
-                    win[j][kk] = ldg8(src, bin + 2u * (16u * j + 32u * kk));
+                for (int kk = 0; kk < NK; ++kk) win[j][kk] = ldg8(src, bin + 2u * (16u * j + 32u * kk));
 #pragma unroll
             for (int j = 0; j < HB_FIR_TILES; ++j) {
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -87,16 +88,32 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
                 stg4<STREAM>(dst, bout + 64u * j, acc);
             }
         } else {
+            // border task, tile by tile: the window is moved inside the row and the clamp
+            // is folded into the fragment; rows past the image repeat the last one
             const int y = y0 + c;
             const half_t* row = p.in + (int64_t)min(y, p.H - 1) * p.in_pitch;
             float* orow = p.out + (int64_t)y * p.out_pitch;
+#pragma unroll 1
             for (int j = 0; j < HB_FIR_TILES; ++j) {
+                const int xt = x0 + 16 * j;
+                if (xt >= p.W) break;
+                const int ws = clampi(xt - aw, 0, wmax);
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                if (ws == xt - aw && xt + 16 <= p.W) {
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk)
-                    acc = mfma16x16x32(coef[kk], load8_clamp(row, x0 + 16 * j - aw + 32 * kk + 8 * g, p.W), acc);
-                const int xo = x0 + 16 * j + 4 * g;
-                if (y < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc);
+                    for (int kk = 0; kk < NK; ++kk)
+                        acc = mfma16x16x32(coef[kk], *reinterpret_cast<const half8_u*>(row + ws + 32 * kk + 8 * g), acc);
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) {
+                        half8 hi, lo;
+                        folded_fragment(s_fold, p.T, p.anchor, p.W, xt, ws, kk, c, g, hi, lo);
+                        const half8 px = *reinterpret_cast<const half8_u*>(row + ws + 32 * kk + 8 * g);
+                        acc = mfma16x16x32(hi, px, acc);
+                        acc = mfma16x16x32(lo, px, acc);
+                    }
+                }
+                if (y < p.H) store4_mask(orow, xt + 4 * g, p.W, acc);
             }
         }
     }
@@ -172,6 +189,10 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
 
 }  // namespace hb
 
+extern "C" hb_status hb_fir1d_valu(const hb_half* in, float* out, int H, int W,
+                                   int64_t in_pitch, int64_t out_pitch,
+                                   const hb_half* taps_host, int ntaps, int anchor, hb_stream stream);
+
 extern "C" hb_status hb_fir1d(const hb_half* in, float* out, int H, int W,
                               int64_t in_pitch, int64_t out_pitch,
                               const hb_half* taps_host, int ntaps, int anchor, hb_stream stream) {
@@ -182,6 +203,8 @@ extern "C" hb_status hb_fir1d(const hb_half* in, float* out, int H, int W,
     // a 16-column tile reads the 16 + ntaps - 1 pixels from x0 - anchor on (one more when the
     // window is moved to an even pixel): NK windows of 32
     const int nk = ceil_div(15 + ntaps + (anchor & 1), 32);
+    if (W < 32 * nk)   // narrower than one window of the matrix formulation: vector-ALU kernel
+        return hb_fir1d_valu(in, out, H, W, in_pitch, out_pitch, taps_host, ntaps, anchor, stream);
     const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;

@@ -146,4 +146,54 @@ __device__ __forceinline__ half8 tap_run(const half_t* tab, int t0) {
     return *reinterpret_cast<const half8_u*>(tab + kTapPad + t0);
 }
 
+
+// ---------------------------------------------------------------------------
+// Clamp-to-edge folded into the coefficient matrix.
+//
+// Clamping the input index is linear in the pixels: every tap that would read left of
+// pixel 0 reads pixel 0 instead, so its weight moves onto the matrix row of pixel 0 (and
+// likewise for the last pixel).  A border tile therefore keeps the in-bounds, aligned
+// 16-byte window loads of an interior tile (the window is shifted to lie inside the row)
+// and only swaps the Toeplitz fragment for a folded one built from absolute indices.
+// Sums of fp16 taps are not fp16 numbers, so a folded fragment is carried as hi + lo
+// (two products), which keeps the border as accurate as the interior.
+//
+// Tables in LDS: kf[t] = taps as fp32 (t < ntaps), pfx[i] = sum of taps t < i (i <= ntaps).
+struct FoldTables {
+    float kf[64];
+    float pfx[65];
+};
+__device__ __forceinline__ void fill_fold_tables(FoldTables& ft, const uint16_t* taps_bits, int ntaps) {
+    for (int i = threadIdx.x; i <= 64; i += blockDim.x) {
+        float s = 0.f;
+        for (int t = 0; t < i && t < ntaps; ++t) s += (float)__builtin_bit_cast(half_t, taps_bits[t]);
+        ft.pfx[i] = s;
+        if (i < 64) ft.kf[i] = i < ntaps ? (float)__builtin_bit_cast(half_t, taps_bits[i]) : 0.f;
+    }
+}
+// Weight of pixel u in output x: sum of taps[t] over t with clamp(x + t - anchor, 0, n-1) == u.
+__device__ __forceinline__ float folded_tap(const FoldTables& ft, int ntaps, int anchor, int n, int x, int u) {
+    float v = 0.f;
+    const int t = u - x + anchor;
+    if (t >= 0 && t < ntaps) v = ft.kf[t];
+    if (u == 0) v += ft.pfx[clampi(anchor - x, 0, ntaps)];                 // taps that read left of 0
+    if (u == n - 1) {
+        const int t0 = clampi(n - x + anchor, 0, ntaps);                   // first tap that reads past n-1
+        v += ft.pfx[ntaps] - ft.pfx[t0];
+    }
+    return v;
+}
+// Folded fragment (natural slot order: slot 8g + i = window pixel 32*kk + 8g + i) for the 16
+// outputs xbase + c and the window starting at absolute pixel ws.
+__device__ __forceinline__ void folded_fragment(const FoldTables& ft, int ntaps, int anchor, int n,
+                                                int xbase, int ws, int kk, int c, int g,
+                                                half8& hi, half8& lo) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float v = folded_tap(ft, ntaps, anchor, n, xbase + c, ws + 32 * kk + 8 * g + i);
+        hi[i] = (half_t)v;
+        lo[i] = (half_t)(v - (float)hi[i]);
+    }
+}
+
 }  // namespace hb

@@ -20,6 +20,26 @@ struct Taps {
 constexpr int kNumCU = 256;
 constexpr int kMaxStreamBlocks = 1 << 20;
 
+// Tasks form an nct x nseg grid.  Those in the rectangle [c0, c1) x [s0, s1) touch no image
+// border and take a lean code path (plain loads, unmasked stores); the others take a
+// border-aware path that is written for small register use rather than speed, so that it
+// does not lower the occupancy of the kernel that holds both.
+struct TaskGrid {
+    int nct, nseg;
+    int c0, c1, s0, s1;
+    __host__ __device__ int count() const { return nct * nseg; }
+    __device__ bool interior(int seg, int ct) const { return ct >= c0 && ct < c1 && seg >= s0 && seg < s1; }
+};
+
+// Interior range [lo, hi) of the n task indices t whose footprint
+// [t*step - before, t*step + after) lies inside [0, extent); lo = hi = 0 when empty.
+inline void interior_range(int n, int step, int before, int after, int extent, int& lo, int& hi) {
+    lo = before <= 0 ? 0 : (before + step - 1) / step;
+    hi = extent - after < 0 ? 0 : (extent - after) / step + 1;
+    if (hi > n) hi = n;
+    if (hi <= lo) lo = hi = 0;
+}
+
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 inline hb_status check_image(const void* in, const void* out, int H, int W,

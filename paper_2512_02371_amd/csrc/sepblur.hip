@@ -42,24 +42,46 @@ struct SepArgs {
     int H, W;
     int64_t in_pitch, out_pitch;
     int Tx, ax, Ty, ay;
-    int nct;           // strips
     int steps;         // 16-row steps per task
-    int nseg;          // row segments per strip
-    int ntasks;        // nct * nseg
+    TaskGrid grid;     // strips x row segments
     Taps tx, ty;
 };
 
 __device__ __forceinline__ half_t sep_tap(uint16_t b) { return __builtin_bit_cast(half_t, b); }
 
 // One task: a strip of NW tiles, nsteps output steps.  XIN = every window of the strip
-// lies inside the row and every tile is full (no column clamp, no store mask).
-template <int NKX, int NT, bool XIN, bool STREAM>
-__device__ __forceinline__ void sep_task(const SepArgs& p, const half8 (&coefx)[NKX],
+// lies inside the row and every tile is full: plain Toeplitz fragment, no store mask.
+// Otherwise each tile's window is moved inside the row and the column clamp is folded
+// into a per-tile hi + lo fragment.
+template <int NKX, int NT, int NW, bool XIN, bool STREAM>
+__device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fold, const half8 (&coefx)[NKX],
                                          const half8 (&coefy)[(NT + 1) / 2],
                                          int x0, int Y0, int nsteps, int xw, int c, int g) {
     constexpr int NK = (NT + 1) / 2;
-    constexpr int NW = HB_SEP_TILES;
     const int ntiles = nsteps + NT - 1;
+
+    // border strips: per-tile window start (absolute pixel, inside the row) and folded fragments
+    int wsh[NW];
+    half8 fh[XIN ? 1 : NW][NKX], fl[XIN ? 1 : NW][NKX];
+    if (!XIN) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const int xt = x0 + 16 * w;
+            const int ws = clampi(xt - xw, 0, p.W - 32 * NKX);
+            wsh[w] = ws;
+#pragma unroll
+            for (int kk = 0; kk < NKX; ++kk) {
+                if (ws == xt - xw && xt + 16 <= p.W) {
+                    fh[w][kk] = coefx[kk];
+                    fl[w][kk] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+                } else if (xt < p.W) {
+                    folded_fragment(fold, p.Tx, p.ax, p.W, xt, ws, kk, c, g, fh[w][kk], fl[w][kk]);
+                } else {
+                    fh[w][kk] = fl[w][kk] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+                }
+            }
+        }
+    }
     const half_t* src = p.in + (x0 - xw);                 // uniform; lanes add row * pitch + 8g
     float* dst = p.out + x0;
 
@@ -79,19 +101,19 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const half8 (&coefx)[
 #pragma unroll
                 for (int kk = 0; kk < NKX; ++kk) dstw[w][kk] = ldg8(src, off + 2u * (16u * w + 32u * kk));
         } else {
-            const half_t* row = p.in + (int64_t)yr * p.in_pitch;
+            const half_t* row = p.in + (int64_t)yr * p.in_pitch + 8 * g;
 #pragma unroll
             for (int w = 0; w < NW; ++w)
 #pragma unroll
                 for (int kk = 0; kk < NKX; ++kk)
-                    dstw[w][kk] = load8_clamp(row, x0 + 16 * w - xw + 32 * kk + 8 * g, p.W);
+                    dstw[w][kk] = *reinterpret_cast<const half8_u*>(row + wsh[w] + 32 * kk);
         }
     };
 
     half8 cur[NW][NKX], nxt[NW][NKX];
     load_tile(0, cur);
     for (int q = 0; q < ntiles; ++q) {
-        if (q + 1 < ntiles) load_tile(q + 1, nxt);
+        if (q + 1 < ntiles) load_tile(q + 1, nxt);        // next row tile in flight while this one is multiplied
 #pragma unroll
         for (int u = 0; u < NT - 1; ++u)
 #pragma unroll
@@ -100,7 +122,14 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const half8 (&coefx)[
         for (int w = 0; w < NW; ++w) {
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < NKX; ++kk) acc = mfma16x16x32(cur[w][kk], coefx[kk], acc);
+            for (int kk = 0; kk < NKX; ++kk) {
+                if (XIN) {
+                    acc = mfma16x16x32(cur[w][kk], coefx[kk], acc);
+                } else {
+                    acc = mfma16x16x32(cur[w][kk], fh[w][kk], acc);
+                    acc = mfma16x16x32(cur[w][kk], fl[w][kk], acc);
+                }
+            }
             hist[NT - 1][w] = to_half4(acc);
         }
         const int s = q - (NT - 1);                       // output step completed by this tile
@@ -117,18 +146,18 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const half8 (&coefx)[
                     acc[w] = mfma16x16x32(join(lo, hi), coefy[j], acc[w]);
                 }
             }
-            if (XIN) {
-                if (yo < p.H) {
+            if (yo < p.H) {
+                if (XIN) {
                     const uint32_t off = ((uint32_t)yo * (uint32_t)p.out_pitch + 4u * g) * 4u;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
-                }
-            } else {
-                float* orow = p.out + (int64_t)yo * p.out_pitch;
+                } else {
+                    float* orow = p.out + (int64_t)yo * p.out_pitch;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) {
-                    const int xo = x0 + 16 * w + 4 * g;
-                    if (yo < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc[w]);
+                    for (int w = 0; w < NW; ++w) {
+                        const int xo = x0 + 16 * w + 4 * g;
+                        if (xo < p.W) store4_mask(orow, xo, p.W, acc[w]);
+                    }
                 }
             }
         }
@@ -144,8 +173,10 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
     constexpr int NK = (NT + 1) / 2;          // K = 32 chunks of the column pass
     constexpr int NW = HB_SEP_TILES;
     __shared__ half_t s_tx[kTapLen], s_ty[kTapLen];
+    __shared__ FoldTables s_fold;
     fill_tap_table(s_tx, p.tx.v, p.Tx);
     fill_tap_table(s_ty, p.ty.v, p.Ty);
+    fill_fold_tables(s_fold, p.tx.v, p.Tx);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -164,14 +195,14 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
 
     const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    for (int task = wave; task < p.ntasks; task += nwaves) {
-        const int seg = task / p.nct, ct = task - seg * p.nct;
+    const int ntasks = p.grid.count();
+    for (int task = wave; task < ntasks; task += nwaves) {
+        const int seg = task / p.grid.nct, ct = task - seg * p.grid.nct;
         const int x0 = 16 * NW * ct;
         const int Y0 = seg * p.steps * 16;
         const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
-        const bool xin = (x0 - xw >= 0) && (x0 + 16 * (NW - 1) - xw + 32 * NKX <= p.W) && (x0 + 16 * NW <= p.W);
-        if (xin) sep_task<NKX, NT, true, STREAM>(p, coefx, coefy, x0, Y0, nsteps, xw, c, g);
-        else sep_task<NKX, NT, false, STREAM>(p, coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, s_fold, coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        else sep_task<NKX, NT, NW, false, STREAM>(p, s_fold, coefx, coefy, x0, Y0, nsteps, xw, c, g);
     }
 }
 
@@ -252,36 +283,55 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
     a.ax = ax;
     a.Ty = nty;
     a.ay = ay;
-    a.nct = ceil_div(W, 16 * HB_SEP_TILES);
+    const int nct = ceil_div(W, 16 * HB_SEP_TILES);
     const int rowsteps = ceil_div(H, 16);
     // enough tasks to fill the chip, few enough that the (NT-1)-tile warm-up stays small
-    int steps = (int)(((int64_t)rowsteps * a.nct) / HB_SEP_WAVES);
+    int steps = (int)(((int64_t)rowsteps * nct) / HB_SEP_WAVES);
     steps = steps < 1 ? 1 : (steps > 64 ? 64 : steps);
     a.steps = steps;
-    a.nseg = ceil_div(rowsteps, steps);
-    a.ntasks = a.nct * a.nseg;
+    a.grid.nct = nct;
+    a.grid.nseg = ceil_div(rowsteps, steps);
+    // a strip is interior when all its windows lie inside the row and its tiles are full;
+    // rows are clamped per lane in both kernels
+    const int xw = ax + (ax & 1);
+    const int nkx = ceil_div(15 + ntx + (ax & 1), 32);
+    const int after = 16 * (HB_SEP_TILES - 1) - xw + 32 * nkx;
+    interior_range(nct, 16 * HB_SEP_TILES, xw, after > 16 * HB_SEP_TILES ? after : 16 * HB_SEP_TILES, W,
+                   a.grid.c0, a.grid.c1);
+    a.grid.s0 = 0;
+    a.grid.s1 = a.grid.c1 > a.grid.c0 ? a.grid.nseg : 0;
     a.tx = pack_taps(tx, ntx);
     a.ty = pack_taps(ty, nty);
     return HB_OK;
 }
 
+template <int NKX, int NT, bool STREAM>
+static void sep_launch2(hipStream_t st, const SepArgs& a) {
+    hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, NT, STREAM>), dim3(min(ceil_div(a.grid.count(), 4), kMaxStreamBlocks)),
+                       dim3(256), 0, st, a);
+}
 template <int NKX, bool STREAM>
-static void sep_launch_nt(int nt, int blocks, hipStream_t st, const SepArgs& a) {
+static void sep_launch_nt(int nt, hipStream_t st, const SepArgs& a) {
     switch (nt) {
-        case 1: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 1, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 2, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 3, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 4, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, 5, STREAM>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 1: sep_launch2<NKX, 1, STREAM>(st, a); break;
+        case 2: sep_launch2<NKX, 2, STREAM>(st, a); break;
+        case 3: sep_launch2<NKX, 3, STREAM>(st, a); break;
+        case 4: sep_launch2<NKX, 4, STREAM>(st, a); break;
+        default: sep_launch2<NKX, 5, STREAM>(st, a); break;
     }
 }
 template <int NKX>
-static void sep_launch(bool stream_stores, int nt, int blocks, hipStream_t st, const SepArgs& a) {
-    if (stream_stores) sep_launch_nt<NKX, true>(nt, blocks, st, a);
-    else sep_launch_nt<NKX, false>(nt, blocks, st, a);
+static void sep_launch(bool stream_stores, int nt, hipStream_t st, const SepArgs& a) {
+    if (stream_stores) sep_launch_nt<NKX, true>(nt, st, a);
+    else sep_launch_nt<NKX, false>(nt, st, a);
 }
 
 }  // namespace hb
+
+extern "C" hb_status hb_sepblur_valu(const hb_half* in, float* out, int H, int W,
+                                     int64_t in_pitch, int64_t out_pitch,
+                                     const hb_half* taps_x_host, int ntaps_x, int anchor_x,
+                                     const hb_half* taps_y_host, int ntaps_y, int anchor_y, hb_stream stream);
 
 extern "C" hb_status hb_sepblur(const hb_half* in, float* out, int H, int W,
                                 int64_t in_pitch, int64_t out_pitch,
@@ -293,14 +343,16 @@ extern "C" hb_status hb_sepblur(const hb_half* in, float* out, int H, int W,
                               taps_y_host, ntaps_y, anchor_y);
     if (s != HB_OK) return s;
     const int nkx = ceil_div(15 + ntaps_x + (anchor_x & 1), 32);
+    if (W < 32 * nkx)   // narrower than one window of the matrix formulation: vector-ALU kernel
+        return hb_sepblur_valu(in, out, H, W, in_pitch, out_pitch, taps_x_host, ntaps_x, anchor_x,
+                               taps_y_host, ntaps_y, anchor_y, stream);
     const int nt = (ntaps_y + 30) / 16;
-    const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
     switch (nkx) {
-        case 1: sep_launch<1>(ss, nt, blocks, st, a); break;
-        case 2: sep_launch<2>(ss, nt, blocks, st, a); break;
-        case 3: sep_launch<3>(ss, nt, blocks, st, a); break;
+        case 1: sep_launch<1>(ss, nt, st, a); break;
+        case 2: sep_launch<2>(ss, nt, st, a); break;
+        case 3: sep_launch<3>(ss, nt, st, a); break;
         default: return HB_ERR_UNSUPPORTED;
     }
     return launch_status();

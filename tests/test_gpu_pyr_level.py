@@ -1,0 +1,66 @@
+"""hb_pyr_level / hb_pyr_level_valu against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+
+from paper_2512_02371_amd import synth
+from hbtest import assert_close, padded, up
+
+pytestmark = pytest.mark.gpu
+
+CASES = [(64, 64), (2, 2), (4, 6), (34, 70), (130, 300), (256, 256), (96, 62), (66, 192), (30, 1026)]
+
+
+def run(fn, H, W, want_down, pitch_extra=0, seed=0):
+    import torch
+    from paper_2512_02371_amd import hb
+    img = synth.uniform01_f16(5000 + seed + H * 3 + W, (H, W))
+    d_in = up(img)
+    if pitch_extra:
+        _, d_in = padded(d_in, W + pitch_extra)
+    rbuf, res = padded(torch.zeros((H, W), dtype=torch.float32, device="cuda:0"), W + pitch_extra)
+    dbuf, down = padded(torch.zeros((H // 2, W // 2), dtype=torch.float16, device="cuda:0"), W // 2 + pitch_extra)
+    print(f"{fn} H={H} W={W} down={want_down} pitch+{pitch_extra}", flush=True)
+    getattr(hb, fn)(d_in, res, down if want_down else None)
+    torch.cuda.synchronize()
+    return img, res.cpu().numpy(), down.cpu().numpy(), rbuf.cpu().numpy(), dbuf.cpu().numpy()
+
+
+@pytest.mark.parametrize("fn", ["hb_pyr_level", "hb_pyr_level_valu"])
+@pytest.mark.parametrize("H,W", CASES)
+def test_pyr_matches_oracle(orc, fn, H, W):
+    img, res, down, _, _ = run(fn, H, W, True)
+    ref, dref = orc.pyr_level(img, want_down=True)
+    assert_close(res, ref, f"{fn} residual {H}x{W}")
+    assert_close(down.astype(np.float64), dref, f"{fn} down {H}x{W}")
+
+
+@pytest.mark.parametrize("fn", ["hb_pyr_level", "hb_pyr_level_valu"])
+def test_pyr_without_down_and_with_pitch(orc, fn):
+    H, W = 70, 150
+    img, res, down, rbuf, dbuf = run(fn, H, W, False, pitch_extra=6)
+    assert_close(res, orc.pyr_level(img), f"{fn} pitched")
+    assert np.all(rbuf[:, W:] == 7.0) and np.all(dbuf == np.float16(7.0)) or np.all(down == 0), "stray writes"
+    assert np.all(down == 0), "down written although not requested"
+
+
+@pytest.mark.parametrize("fn", ["hb_pyr_level", "hb_pyr_level_valu"])
+def test_pyr_constant_image_has_zero_residual(fn):
+    import torch
+    from paper_2512_02371_amd import hb
+    H, W = 96, 160
+    res = torch.ones((H, W), dtype=torch.float32, device="cuda:0")
+    getattr(hb, fn)(up(synth.f64_to_f16_bits(np.full((H, W), 0.75))), res, None)
+    assert float(res.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("fn", ["hb_pyr_level", "hb_pyr_level_valu"])
+def test_pyr_benchmark_width_slab(orc, fn):
+    """A 320-row slab at the benchmark's 8192-pixel width: same strips as the full image."""
+    import torch
+    from paper_2512_02371_amd import hb
+    H, W = 320, 8192
+    img = synth.uniform01_f16(1005, (H, W))
+    res = torch.zeros((H, W), dtype=torch.float32, device="cuda:0")
+    getattr(hb, fn)(up(img), res, None)
+    torch.cuda.synchronize()
+    assert_close(res.cpu().numpy(), orc.pyr_level(img), fn)
