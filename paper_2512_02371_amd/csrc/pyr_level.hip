@@ -63,6 +63,15 @@ __device__ __forceinline__ float upw_clamped(int dabs, int xabs, int n) {
     return s;
 }
 
+// Weight of pixel u in D sample n when the pixel index 2n + i (i = -2..2) is clamped to [0, len-1].
+__device__ __forceinline__ half_t down_tap_clamped(int n, int u, int len) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = -2; i <= 2; ++i)
+        if (clampi(2 * n + i, 0, len - 1) == u) s += (float)w5(i + 2);
+    return (half_t)s;                                     // multiples of 1/16 up to 1: exact
+}
+
 // B fragment of an up pass for the K = 32 window starting at D index d0 and the 16 outputs
 // starting at x0abs (lane c = output, chained slot order), D extent n.
 __device__ __forceinline__ half8 up_fragment_clamped(int d0, int x0abs, int n, int c, int g) {
@@ -105,6 +114,23 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int
 #pragma unroll
             for (int h = 0; h < 2; ++h) U1[a][t][h] = z4;
 
+    // border tasks: per D column tile, a pixel window moved inside the row and A_down
+    // fragments with the column clamp folded in
+    int wsx[NT];
+    half8 fdx32[FAST ? 1 : NT], fdx16[FAST ? 1 : NT];
+    if (!FAST) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            wsx[t] = clampi(px0 + 32 * t, 0, p.W - 48);
+            const int n = Dx0 + 16 * t + c;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                fdx32[t][i] = down_tap_clamped(n, wsx[t] + 8 * g + i, p.W);
+                fdx16[t][i] = (i < 4) ? down_tap_clamped(n, wsx[t] + 32 + 4 * g + i, p.W) : (half_t)0;
+            }
+        }
+    }
+
     half8 win32[NT], nxt32[NT];
     half4 win16[NT], nxt16[NT];
     auto load_rows = [&](int r, half8 (&a32)[NT], half4 (&a16)[NT]) {
@@ -120,30 +146,24 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int
             const half_t* row = p.in + (int64_t)clampi(y00 + 16 * r + c, 0, p.H - 1) * p.in_pitch;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                a32[t] = load8_clamp(row, px0 + 32 * t + 8 * g, p.W);
-                a16[t] = load4_clamp(row, px0 + 32 * t + 32 + 4 * g, p.W);
+                a32[t] = *reinterpret_cast<const half8_u*>(row + wsx[t] + 8 * g);
+                a16[t] = *reinterpret_cast<const half4_u*>(row + wsx[t] + 32 + 4 * g);
             }
         }
     };
 
     const int ntiles = 2 * nsteps + 3;                    // image row tiles of this task
-    if (FAST) load_rows(0, win32, win16);
+    load_rows(0, win32, win16);
     for (int r = 0; r < ntiles; ++r) {
-        // interior tasks request the next row tile before multiplying this one; the border
-        // path loads in place (fewer live registers)
-        if (FAST) {
-            if (r + 1 < ntiles) load_rows(r + 1, nxt32, nxt16);
-        } else {
-            load_rows(r, win32, win16);
-        }
+        if (r + 1 < ntiles) load_rows(r + 1, nxt32, nxt16);   // next row tile in flight during the products
         // pass 1: this image row tile, all D column tiles
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             T1[0][t] = T1[1][t];
             T1[1][t] = T1[2][t];
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-            acc = mfma16x16x32(win32[t], k.dx32, acc);
-            acc = mfma16x16x32(join(win16[t], z4), k.d16, acc);
+            acc = mfma16x16x32(win32[t], FAST ? k.dx32 : fdx32[t], acc);
+            acc = mfma16x16x32(join(win16[t], z4), FAST ? k.d16 : fdx16[t], acc);
             T1[2][t] = to_half4(acc);
         }
         if ((r & 1) == 0 && r >= 2) {
@@ -232,12 +252,10 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int
                 }
             }
         }
-        if (FAST) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                win32[t] = nxt32[t];
-                win16[t] = nxt16[t];
-            }
+        for (int t = 0; t < NT; ++t) {
+            win32[t] = nxt32[t];
+            win16[t] = nxt16[t];
         }
     }
 }
@@ -392,6 +410,10 @@ static hb_status pyr_prepare(PyrArgs& a, const hb_half* in, float* res, hb_half*
 
 }  // namespace hb
 
+extern "C" hb_status hb_pyr_level_valu(const hb_half* in, float* residual, hb_half* down_or_null,
+                                       int H, int W, int64_t in_pitch, int64_t res_pitch, int64_t down_pitch,
+                                       hb_stream stream);
+
 extern "C" hb_status hb_pyr_level(const hb_half* in, float* residual, hb_half* down_or_null,
                                   int H, int W, int64_t in_pitch, int64_t res_pitch, int64_t down_pitch,
                                   hb_stream stream) {
@@ -399,6 +421,8 @@ extern "C" hb_status hb_pyr_level(const hb_half* in, float* residual, hb_half* d
     PyrArgs a;
     hb_status s = pyr_prepare(a, in, residual, down_or_null, H, W, in_pitch, res_pitch, down_pitch);
     if (s != HB_OK) return s;
+    if (W < 48)   // narrower than one pixel window of the matrix formulation: vector-ALU kernel
+        return hb_pyr_level_valu(in, residual, down_or_null, H, W, in_pitch, res_pitch, down_pitch, stream);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const dim3 grid(min(ceil_div(a.grid.count(), 4), kMaxStreamBlocks));
     if ((int64_t)H * W * 4 <= kStreamStoreMaxBytes)

@@ -1,0 +1,393 @@
+// hb_sat2d: summed-area table.  Per 64 x 64 tile the table is L * X * U (L, U triangular
+// all-ones); between tiles it needs carries, as the tiled recursive filter of Sec. V-D
+// (tile, then fix up): three launches,
+//   1 sums    per tile: row sums (X * 1) and column sums (1^T * X)                    read 2 B/px
+//   2 scan    exclusive scans of those sums along the tile grid                       (tiny)
+//   3 apply   per tile: row prefix X * U on the matrix units seeded with the row carry,
+//             column prefix with the column carry, store                              read 2 + write 4 B/px
+// so that  S[i][j] = P(i0-1, j) + sum_{y=i0..i} ( R(y) + sum_{x=j0..j} in[y][x] )
+// with R(y) = sum of row y left of the tile and P(i0-1, j) the table value above the tile.
+//
+// MFMA formulation of the apply pass, transposed so that a lane ends with four consecutive
+// columns of one row:
+//   Z'[m][n] = sum_k Ut[m][k] * Xt[k][n] + R[n]      m = column, n = row, k = pixel in a 32-block
+//   Ut[m][k] = 1 for k <= m (+16 for the second 16 columns), so one 16-byte pixel load feeds both
+//   halves; a third product with the all-ones matrix yields the block's row totals in every lane,
+//   which advance the row carry.  The 0/1 coefficients and fp16 pixels make every product exact;
+//   sums are fp32.  The column prefix runs over the 16 rows that sit in the 16 lanes of a DPP row
+//   (four shifted adds), the column carry is the prefix value of the last row.
+//   The sums pass uses the same operands: X * 1 for row sums; X * [I|0], X * [0|I] copy the pixels
+//   into accumulator layout (exactly), whose stacked pairs times the all-ones matrix give column
+//   sums.  No cross-lane traffic in that pass at all.
+#include "hb_device.hpp"
+#include "hb_host.hpp"
+
+namespace hb {
+
+constexpr int kSatTile = 64;
+
+struct SatArgs {
+    const half_t* in;
+    float* out;
+    int H, W;
+    int64_t in_pitch, out_pitch;
+    int nb, ns;            // 64-column strips, 64-row segments
+    int Hs, Ws;            // H, W rounded up to whole tiles (workspace row lengths)
+    float* rs;             // [nb][Hs]  row sums per (strip, row)
+    float* cs;             // [ns][Ws]  column sums per (segment, column)
+    float* rcarry;         // [nb][Hs]  exclusive scan of rs over strips
+    float* ccarry;         // [ns][Ws]  exclusive scan of cs over segments
+    float* es;             // [ns][nb]  strip totals of ccarry
+};
+
+// Eight pixels row[xs .. xs+7], zero where the row or the column is outside the image.
+__device__ __forceinline__ half8 load8_zero(const half_t* in, int64_t pitch, int y, int xs, int H, int W) {
+    half8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (y < H) {
+        const half_t* row = in + (int64_t)y * pitch;
+        if (xs + 8 <= W) {
+            r = *reinterpret_cast<const half8_u*>(row + xs);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (xs + i < W) r[i] = row[xs + i];
+        }
+    }
+    return r;
+}
+
+__device__ __forceinline__ half8 ones8() { return half8{1, 1, 1, 1, 1, 1, 1, 1}; }
+
+// ---------------------------------------------------------------------------
+// 1  sums
+__global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
+    const int lane = threadIdx.x & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (wave >= p.nb * p.ns) return;
+    const int s = wave / p.nb, b = wave - s * p.nb;
+    const int y0 = kSatTile * s, x0 = kSatTile * b;
+
+    half8 sel[2];                                         // B[k][n] = (k == 16 half + n)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sel[h][i] = (half_t)((8 * g + i == 16 * h + c) ? 1.f : 0.f);
+    const half8 one = ones8();
+
+    floatx4 rowsum[4];
+    half4 T[4][2][2];                                     // pixel copies in accumulator layout
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+        rowsum[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const half8 X = load8_zero(p.in, p.in_pitch, y0 + 16 * rt + c, x0 + 32 * blk + 8 * g, p.H, p.W);
+            rowsum[rt] = mfma16x16x32(X, one, rowsum[rt]);            // [m = row][n]: row totals in every column
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                floatx4 t = {0.f, 0.f, 0.f, 0.f};
+                T[rt][blk][h] = to_half4(mfma16x16x32(X, sel[h], t)); // [m = row][n = column]: lane c = column
+            }
+        }
+    }
+    // row sums: lane (c, g) holds rows 4g + v, the same in every c
+    if (c == 0) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+            *reinterpret_cast<floatx4*>(p.rs + (int64_t)b * p.Hs + y0 + 16 * rt + 4 * g) = rowsum[rt];
+    }
+    // column sums: contract the stacked row tiles with the all-ones matrix
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            floatx4 cs = {0.f, 0.f, 0.f, 0.f};
+            cs = mfma16x16x32(join(T[0][blk][h], T[1][blk][h]), one, cs);   // [m = column][n]
+            cs = mfma16x16x32(join(T[2][blk][h], T[3][blk][h]), one, cs);
+            if (c == 0)
+                *reinterpret_cast<floatx4*>(p.cs + (int64_t)s * p.Ws + x0 + 32 * blk + 16 * h + 4 * g) = cs;
+        }
+}
+
+// ---------------------------------------------------------------------------
+// 2  scans.  Blocks [0, Hs/64): one thread per image row, exclusive scan of rs over strips.
+// Blocks [Hs/64, Hs/64 + nb): one wave per strip, one lane per column: exclusive scan of cs over
+// segments, and per segment the strip total of that scan (what lies above-left of a tile is the
+// sum of those totals over the strips to its left).
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__global__ void __launch_bounds__(64) sat_scan_kernel(SatArgs p) {
+    const int lane = threadIdx.x;
+    const int nrowblocks = p.Hs / 64;
+    if ((int)blockIdx.x < nrowblocks) {
+        const int y = 64 * blockIdx.x + lane;
+        const float* __restrict__ src = p.rs + y;
+        float* __restrict__ dst = p.rcarry + y;
+        float run = 0.f;
+        for (int b0 = 0; b0 < p.nb; b0 += 16) {
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = (b0 + i < p.nb) ? src[(int64_t)(b0 + i) * p.Hs] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (b0 + i < p.nb) {
+                    dst[(int64_t)(b0 + i) * p.Hs] = run;
+                    run += v[i];
+                }
+        }
+    } else {
+        const int b = blockIdx.x - nrowblocks;
+        const int j = 64 * b + lane;
+        const float* __restrict__ src = p.cs + j;
+        float* __restrict__ dst = p.ccarry + j;
+        float run = 0.f;
+        for (int s0 = 0; s0 < p.ns; s0 += 16) {
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = (s0 + i < p.ns) ? src[(int64_t)(s0 + i) * p.Ws] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (s0 + i < p.ns) {
+                    dst[(int64_t)(s0 + i) * p.Ws] = run;
+                    const float tot = wave_sum(run);
+                    if (lane == 0) p.es[(int64_t)(s0 + i) * p.nb + b] = tot;
+                    run += v[i];
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 3  apply
+__device__ __forceinline__ float dpp_row_shr(float v, int n) {
+    // lane i of each 16-lane row receives lane i - n of the same row, 0 where there is none
+    int r;
+    switch (n) {
+        case 1: r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111, 0xf, 0xf, true); break;
+        case 2: r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x112, 0xf, 0xf, true); break;
+        case 4: r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xf, 0xf, true); break;
+        default: r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xf, 0xf, true); break;
+    }
+    return __builtin_bit_cast(float, r);
+}
+
+template <bool STREAM>
+__global__ void __launch_bounds__(256) sat_apply_mfma_kernel(SatArgs p) {
+    const int lane = threadIdx.x & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (wave >= p.nb * p.ns) return;
+    const int s = wave / p.nb, b = wave - s * p.nb;
+    const int y0 = kSatTile * s, x0 = kSatTile * b;
+
+    // A operands: Ut[m][k] = (k <= m + 16 half): lane (c = m, g) holds k = 8g .. 8g+7
+    half8 tri[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tri[h][i] = (half_t)((8 * g + i <= c + 16 * h) ? 1.f : 0.f);
+    const half8 one = ones8();
+
+    // table row above the tile: scan of the column carries of this strip plus all that lies left of it
+    float above = (lane < b) ? p.es[(int64_t)s * p.nb + lane] : 0.f;
+    above = wave_sum(above);
+    float colp = p.ccarry[(int64_t)s * p.Ws + x0 + lane];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float t = __shfl_up(colp, off, 64);
+        if (lane >= off) colp += t;
+    }
+    colp += above;                                        // P(i0 - 1, x0 + lane)
+    floatx4 ccar[4];                                      // lane (c, g): columns 16 t + 4g + v
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ccar[t][v] = __shfl(colp, 16 * t + 4 * g + v, 64);
+
+    const bool full = (y0 + kSatTile <= p.H) && (x0 + kSatTile <= p.W);
+#pragma unroll 1
+    for (int rt = 0; rt < 4; ++rt) {
+        const int y = y0 + 16 * rt + c;
+        const float r0 = p.rcarry[(int64_t)b * p.Hs + y];
+        floatx4 rc = {r0, r0, r0, r0};                    // row carry of row c, the same in all four columns
+        float* orow = p.out + (int64_t)y * p.out_pitch;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const half8 X = load8_zero(p.in, p.in_pitch, y, x0 + 32 * blk + 8 * g, p.H, p.W);
+            floatx4 z[2];
+            z[0] = mfma16x16x32(tri[0], X, rc);           // [m = column][n = row]: lane c = row, columns 4g + v
+            z[1] = mfma16x16x32(tri[1], X, rc);
+            rc = mfma16x16x32(one, X, rc);                // row carry advanced by the block's row totals
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int t = 2 * blk + h;
+                floatx4 acc = z[h];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float x = acc[v];                     // inclusive prefix over the 16 rows of the DPP row
+                    x += dpp_row_shr(x, 1);
+                    x += dpp_row_shr(x, 2);
+                    x += dpp_row_shr(x, 4);
+                    x += dpp_row_shr(x, 8);
+                    x += ccar[t][v];
+                    acc[v] = x;
+                    ccar[t][v] = __shfl(x, (lane & 48) | 15, 64);   // value of the last row = next column carry
+                }
+                const int xo = x0 + 16 * t + 4 * g;
+                if (full) stg4<STREAM>(orow, 4u * xo, acc);
+                else if (y < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Vector-ALU twin of passes 1 and 3: the tile goes through LDS, threads add.
+__global__ void __launch_bounds__(256) sat_sums_valu_kernel(SatArgs p) {
+    __shared__ float s_px[kSatTile][kSatTile + 1];
+    const int s = blockIdx.x / p.nb, b = blockIdx.x - s * p.nb;
+    const int y0 = kSatTile * s, x0 = kSatTile * b;
+    for (int idx = threadIdx.x; idx < kSatTile * 8; idx += 256) {
+        const int r = idx >> 3, ch = idx & 7;
+        const half8 v = load8_zero(p.in, p.in_pitch, y0 + r, x0 + 8 * ch, p.H, p.W);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s_px[r][8 * ch + i] = (float)v[i];
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        float a = 0.f;
+        for (int x = 0; x < kSatTile; ++x) a += s_px[threadIdx.x][x];
+        p.rs[(int64_t)b * p.Hs + y0 + threadIdx.x] = a;
+    } else if (threadIdx.x < 128) {
+        const int x = threadIdx.x - 64;
+        float a = 0.f;
+        for (int y = 0; y < kSatTile; ++y) a += s_px[y][x];
+        p.cs[(int64_t)s * p.Ws + x0 + x] = a;
+    }
+}
+
+__global__ void __launch_bounds__(256) sat_apply_valu_kernel(SatArgs p) {
+    __shared__ float s_t[kSatTile][kSatTile + 1];
+    __shared__ float s_above[kSatTile];
+    const int s = blockIdx.x / p.nb, b = blockIdx.x - s * p.nb;
+    const int y0 = kSatTile * s, x0 = kSatTile * b;
+    for (int idx = threadIdx.x; idx < kSatTile * 8; idx += 256) {
+        const int r = idx >> 3, ch = idx & 7;
+        const half8 v = load8_zero(p.in, p.in_pitch, y0 + r, x0 + 8 * ch, p.H, p.W);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s_t[r][8 * ch + i] = (float)v[i];
+    }
+    if (threadIdx.x < 64) {
+        // table row above the tile, as in the MFMA kernel
+        const int lane = threadIdx.x;
+        float above = (lane < b) ? p.es[(int64_t)s * p.nb + lane] : 0.f;
+        above = wave_sum(above);
+        float colp = p.ccarry[(int64_t)s * p.Ws + x0 + lane];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float t = __shfl_up(colp, off, 64);
+            if (lane >= off) colp += t;
+        }
+        s_above[lane] = colp + above;
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {                               // row prefix, seeded with the row carry
+        const int r = threadIdx.x;
+        float a = p.rcarry[(int64_t)b * p.Hs + y0 + r];
+        for (int x = 0; x < kSatTile; ++x) {
+            a += s_t[r][x];
+            s_t[r][x] = a;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {                               // column prefix, seeded with the table row above
+        const int x = threadIdx.x;
+        float a = s_above[x];
+        for (int y = 0; y < kSatTile; ++y) {
+            a += s_t[y][x];
+            s_t[y][x] = a;
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kSatTile * 16; idx += 256) {
+        const int r = idx >> 4, q = idx & 15;
+        const int y = y0 + r, xo = x0 + 4 * q;
+        if (y >= p.H || xo >= p.W) continue;
+        floatx4 v = {s_t[r][4 * q], s_t[r][4 * q + 1], s_t[r][4 * q + 2], s_t[r][4 * q + 3]};
+        store4_mask(p.out + (int64_t)y * p.out_pitch, xo, p.W, v);
+    }
+}
+
+static size_t sat_workspace_floats(int H, int W) {
+    const size_t nb = (size_t)ceil_div(W, kSatTile), ns = (size_t)ceil_div(H, kSatTile);
+    return 2 * (nb * ns * kSatTile) + 2 * (ns * nb * kSatTile) + ns * nb;   // rs, rcarry, cs, ccarry, es
+}
+
+static hb_status sat_prepare(SatArgs& a, const hb_half* in, float* out, int H, int W,
+                             int64_t in_pitch, int64_t out_pitch, void* ws, size_t ws_bytes) {
+    hb_status st = check_image(in, out, H, W, in_pitch, out_pitch);
+    if (st != HB_OK) return st;
+    if (!ws || !aligned_to(ws, 256) || ws_bytes < hb_sat2d_workspace_size(H, W)) return HB_ERR_WORKSPACE;
+    a.in = reinterpret_cast<const half_t*>(in);
+    a.out = out;
+    a.H = H;
+    a.W = W;
+    a.in_pitch = in_pitch;
+    a.out_pitch = out_pitch;
+    a.nb = ceil_div(W, kSatTile);
+    a.ns = ceil_div(H, kSatTile);
+    a.Hs = a.ns * kSatTile;
+    a.Ws = a.nb * kSatTile;
+    float* f = reinterpret_cast<float*>(ws);
+    a.rs = f;
+    a.rcarry = a.rs + (size_t)a.nb * a.Hs;
+    a.cs = a.rcarry + (size_t)a.nb * a.Hs;
+    a.ccarry = a.cs + (size_t)a.ns * a.Ws;
+    a.es = a.ccarry + (size_t)a.ns * a.Ws;
+    return HB_OK;
+}
+
+}  // namespace hb
+
+extern "C" size_t hb_sat2d_workspace_size(int H, int W) {
+    if (H < 1 || W < 1) return 0;
+    return hb::sat_workspace_floats(H, W) * sizeof(float);
+}
+
+extern "C" hb_status hb_sat2d(const hb_half* in, float* out, int H, int W,
+                              int64_t in_pitch, int64_t out_pitch,
+                              void* workspace, size_t workspace_bytes, hb_stream stream) {
+    using namespace hb;
+    SatArgs a;
+    hb_status s = sat_prepare(a, in, out, H, W, in_pitch, out_pitch, workspace, workspace_bytes);
+    if (s != HB_OK) return s;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int ntiles = a.nb * a.ns;
+    hipLaunchKernelGGL(sat_sums_mfma_kernel, dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(sat_scan_kernel, dim3(a.Hs / 64 + a.nb), dim3(64), 0, st, a);
+    if ((int64_t)H * W * 4 <= kStreamStoreMaxBytes)
+        hipLaunchKernelGGL((sat_apply_mfma_kernel<true>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((sat_apply_mfma_kernel<false>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
+    return launch_status();
+}
+
+extern "C" hb_status hb_sat2d_valu(const hb_half* in, float* out, int H, int W,
+                                   int64_t in_pitch, int64_t out_pitch,
+                                   void* workspace, size_t workspace_bytes, hb_stream stream) {
+    using namespace hb;
+    SatArgs a;
+    hb_status s = sat_prepare(a, in, out, H, W, in_pitch, out_pitch, workspace, workspace_bytes);
+    if (s != HB_OK) return s;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int ntiles = a.nb * a.ns;
+    hipLaunchKernelGGL(sat_sums_valu_kernel, dim3(ntiles), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(sat_scan_kernel, dim3(a.Hs / 64 + a.nb), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(sat_apply_valu_kernel, dim3(ntiles), dim3(256), 0, st, a);
+    return launch_status();
+}

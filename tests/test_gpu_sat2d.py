@@ -1,0 +1,69 @@
+"""hb_sat2d / hb_sat2d_valu against the fp64 oracle.  Pass criterion: max |gpu - oracle| divided
+by the total sum <= 1e-3 (the benchmark's bar); the per-element scaled error is checked too,
+and integer-valued images must come out bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2512_02371_amd import synth
+from hbtest import TOL, padded, scaled_err, up
+
+pytestmark = pytest.mark.gpu
+
+CASES = [(64, 64), (1, 1), (8, 8), (37, 53), (130, 300), (256, 256), (65, 129), (200, 64), (64, 1000), (512, 4096)]
+
+
+def run(fn, img, pitch_extra=0):
+    import torch
+    from paper_2512_02371_amd import hb
+    H, W = img.shape
+    d_in = up(img)
+    if pitch_extra:
+        _, d_in = padded(d_in, W + pitch_extra)
+    obuf, out = padded(torch.zeros((H, W), dtype=torch.float32, device="cuda:0"), W + pitch_extra)
+    ws = torch.empty(hb.hb_sat2d_workspace_size(H, W) + 256, dtype=torch.uint8, device="cuda:0")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    print(f"{fn} H={H} W={W} pitch+{pitch_extra}", flush=True)
+    getattr(hb, fn)(d_in, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), obuf.cpu().numpy()
+
+
+@pytest.mark.parametrize("fn", ["hb_sat2d", "hb_sat2d_valu"])
+@pytest.mark.parametrize("H,W", CASES)
+def test_sat_matches_oracle(orc, fn, H, W):
+    img = synth.uniform01_f16(7000 + H + 3 * W, (H, W))
+    got, _ = run(fn, img)
+    ref = orc.sat2d(img)
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - ref).max() / ref[-1, -1] <= TOL
+    assert scaled_err(got, ref).max() <= TOL
+
+
+@pytest.mark.parametrize("fn", ["hb_sat2d", "hb_sat2d_valu"])
+def test_sat_binary_image_is_bit_exact(fn):
+    H, W = 300, 520
+    img = synth.binary01_f16(77, (H, W))
+    got, _ = run(fn, img)
+    ref = np.cumsum(np.cumsum(synth.f16_bits_to_f64(img), axis=0), axis=1)
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("fn", ["hb_sat2d", "hb_sat2d_valu"])
+def test_sat_all_ones_closed_form_and_pitch(fn):
+    H, W = 100, 150
+    got, obuf = run(fn, synth.f64_to_f16_bits(np.ones((H, W))), pitch_extra=6)
+    i, j = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    assert np.array_equal(got.astype(np.float64), (i + 1.0) * (j + 1.0))
+    assert np.all(obuf[:, W:] == 7.0), "wrote past the row end"
+
+
+def test_sat_workspace_is_checked():
+    import torch
+    from paper_2512_02371_amd import hb
+    H = W = 64
+    x = torch.zeros((H, W), dtype=torch.float16, device="cuda:0")
+    out = torch.zeros((H, W), dtype=torch.float32, device="cuda:0")
+    small = torch.empty(hb.hb_sat2d_workspace_size(H, W) - 4, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(hb.HbError) as e:
+        hb.hb_sat2d(x, out, small)
+    assert e.value.code == hb.HB_ERR_WORKSPACE
