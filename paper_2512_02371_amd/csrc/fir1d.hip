@@ -63,7 +63,12 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     const uint32_t bout = 4u * ((uint32_t)c * (uint32_t)p.out_pitch + 4u * g);
     const int wmax = p.W - 32 * NK;           // last window start that stays inside the row
 
-    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+#ifdef HB_NO_XCD_MAP
+    const int wgpos = blockIdx.x;
+#else
+    const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
+#endif
+    const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int task = wave; task < p.ntasks; task += nwaves) {
         const int rg = task / p.nct, ct = task - rg * p.nct;

@@ -128,7 +128,20 @@ __device__ __forceinline__ void stg4(float* base, uint32_t byte_off, floatx4 v) 
     if (STREAM) __builtin_nontemporal_store(v, q); else *q = v;
 }
 // Outputs up to this many bytes per call are written with streaming stores.
-constexpr int64_t kStreamStoreMaxBytes = (int64_t)128 << 20;
+#ifndef HB_STREAM_STORE_MAX_MB
+#define HB_STREAM_STORE_MAX_MB 128
+#endif
+constexpr int64_t kStreamStoreMaxBytes = (int64_t)HB_STREAM_STORE_MAX_MB << 20;
+
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by workgroup id.
+// This maps a workgroup id to a position such that every XCD works through one contiguous
+// eighth of the positions, in order: neighbouring tasks, which share halo pixels, then meet
+// in the same L2 at about the same time instead of each fetching the halo from memory.
+__device__ __forceinline__ int xcd_contiguous(int wg, int nwg) {
+    const int per = nwg >> 3;                             // positions per XCD (remainder handled below)
+    if (wg >= per * 8) return wg;                         // tail workgroups keep their place
+    return (wg & 7) * per + (wg >> 3);
+}
 
 // Zero-padded tap table in LDS: entry kTapPad + t holds taps[t] for 0 <= t < ntaps and
 // zero for every other t in [-kTapPad, kTapLen - kTapPad).  A Toeplitz fragment is then

@@ -277,7 +277,12 @@ __global__ void __launch_bounds__(256) pyr_mfma_kernel(PyrArgs p) {
             k.up[h][i] = (half_t)upw(c & 1, krow32(g, i) - 8 - 8 * h - (c >> 1));
     }
 
-    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+#ifdef HB_NO_XCD_MAP
+    const int wgpos = blockIdx.x;
+#else
+    const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
+#endif
+    const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     const int ntasks = p.grid.count();
     for (int task = wave; task < ntasks; task += nwaves) {

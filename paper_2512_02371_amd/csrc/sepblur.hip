@@ -193,7 +193,12 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) coefy[j][i] = s_ty[kTapPad + 32 * j + krow32(g, i) - c];
 
-    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+#ifdef HB_NO_XCD_MAP
+    const int wgpos = blockIdx.x;
+#else
+    const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
+#endif
+    const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     const int ntasks = p.grid.count();
     for (int task = wave; task < ntasks; task += nwaves) {
