@@ -133,6 +133,41 @@ __device__ __forceinline__ void stg4(float* base, uint32_t byte_off, floatx4 v) 
 #endif
 constexpr int64_t kStreamStoreMaxBytes = (int64_t)HB_STREAM_STORE_MAX_MB << 20;
 
+// Accumulator tiles leave the MFMA with a lane owning four columns of ONE row and the 16 lanes
+// of a quarter-wave owning 16 DIFFERENT rows, so a store instruction would touch each row with
+// 16-byte pieces only.  Passing the NW tiles (16 rows x 16*NW floats) through a wave-private LDS
+// patch turns that into stores of 16 consecutive lanes x 16 bytes = one 256-byte run of one row.
+// The patch has a row pitch of 16*NW + 4 floats: both the accumulator-layout writes and the
+// row-major reads are bank-conflict free.  Only the owning wave touches its patch and LDS serves
+// one wave's instructions in order, so no workgroup barrier is needed.
+template <int NW>
+struct RowPatch {
+    static constexpr int kPitch = 16 * NW + 4;
+    static constexpr int kFloats = 16 * kPitch;
+};
+template <int NW, bool STREAM>
+__device__ __forceinline__ void store_rows_via_lds(float* patch, float* dst, uint32_t pitch_elems,
+                                                   const floatx4 (&acc)[NW], int lane) {
+    const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+        *reinterpret_cast<floatx4*>(patch + c * RowPatch<NW>::kPitch + 16 * w + 4 * g) = acc[w];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int kLanesPerRow = 4 * NW;                  // 16-byte pieces in a row of the patch
+    constexpr int kRowsPerPass = 64 / kLanesPerRow;
+    const int rr = lane / kLanesPerRow, xq = lane - rr * kLanesPerRow;
+#pragma unroll
+    for (int s = 0; s < 16 / kRowsPerPass; ++s) {
+        const int row = s * kRowsPerPass + rr;
+        const floatx4 v = *reinterpret_cast<const floatx4*>(patch + row * RowPatch<NW>::kPitch + 4 * xq);
+        stg4<STREAM>(dst, ((uint32_t)row * pitch_elems + 4u * xq) * 4u, v);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by workgroup id.
 // This maps a workgroup id to a position such that every XCD works through one contiguous
 // eighth of the positions, in order: neighbouring tasks, which share halo pixels, then meet

@@ -54,7 +54,8 @@ __device__ __forceinline__ half_t sep_tap(uint16_t b) { return __builtin_bit_cas
 // Otherwise each tile's window is moved inside the row and the column clamp is folded
 // into a per-tile hi + lo fragment.
 template <int NKX, int NT, int NW, bool XIN, bool STREAM>
-__device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fold, const half8 (&coefx)[NKX],
+__device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fold, float* patch,
+                                         const half8 (&coefx)[NKX],
                                          const half8 (&coefy)[(NT + 1) / 2],
                                          int x0, int Y0, int nsteps, int xw, int c, int g) {
     constexpr int NK = (NT + 1) / 2;
@@ -146,11 +147,25 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fol
                     acc[w] = mfma16x16x32(join(lo, hi), coefy[j], acc[w]);
                 }
             }
-            if (yo < p.H) {
-                if (XIN) {
+#ifndef HB_DIRECT_STORES
+            if (XIN) {
+                if (Y0 + 16 * s + 16 <= p.H) {
+                    store_rows_via_lds<NW, STREAM>(patch, dst + (int64_t)(Y0 + 16 * s) * p.out_pitch,
+                                                   (uint32_t)p.out_pitch, acc, (g << 4) | c);
+                } else if (yo < p.H) {
                     const uint32_t off = ((uint32_t)yo * (uint32_t)p.out_pitch + 4u * g) * 4u;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
+                }
+            }
+#endif
+            if (yo < p.H) {
+                if (XIN) {
+#ifdef HB_DIRECT_STORES
+                    const uint32_t off = ((uint32_t)yo * (uint32_t)p.out_pitch + 4u * g) * 4u;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
+#endif
                 } else {
                     float* orow = p.out + (int64_t)yo * p.out_pitch;
 #pragma unroll
@@ -174,6 +189,7 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
     constexpr int NW = HB_SEP_TILES;
     __shared__ half_t s_tx[kTapLen], s_ty[kTapLen];
     __shared__ FoldTables s_fold;
+    __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<HB_SEP_TILES>::kFloats];
     fill_tap_table(s_tx, p.tx.v, p.Tx);
     fill_tap_table(s_ty, p.ty.v, p.Ty);
     fill_fold_tables(s_fold, p.tx.v, p.Tx);
@@ -206,8 +222,8 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
         const int x0 = 16 * NW * ct;
         const int Y0 = seg * p.steps * 16;
         const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
-        if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, s_fold, coefx, coefy, x0, Y0, nsteps, xw, c, g);
-        else sep_task<NKX, NT, NW, false, STREAM>(p, s_fold, coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, s_fold, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        else sep_task<NKX, NT, NW, false, STREAM>(p, s_fold, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
     }
 }
 
