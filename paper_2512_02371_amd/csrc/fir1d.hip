@@ -21,7 +21,10 @@
 #include "hb_host.hpp"
 
 #ifndef HB_FIR_TILES
-#define HB_FIR_TILES 4        // 16-column tiles per wave task
+#define HB_FIR_TILES 2        // 16-column tiles per wave strip
+#endif
+#ifndef HB_FIR_WAVES
+#define HB_FIR_WAVES 4096     // at most this many wave tasks per launch: one resident round
 #endif
 
 namespace hb {
@@ -32,8 +35,9 @@ struct FirArgs {
     int H, W;
     int64_t in_pitch, out_pitch;
     int T, anchor;
-    int nct;             // column tasks per row group
-    int ntasks;          // (16-row groups) x nct
+    int nct;             // strips per row group
+    int steps;           // 16-row steps per task
+    int ntasks;          // strips x row segments
     Taps taps;
 };
 
@@ -41,10 +45,14 @@ __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
     return __builtin_bit_cast(half_t, b);
 }
 
+// A wave owns a strip of HB_FIR_TILES tiles and walks down it in steps of 16 rows; the pixels of
+// the next step are requested before the current step is multiplied.
 template <int NK, bool STREAM>
 __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
+    constexpr int NW = HB_FIR_TILES;
     __shared__ half_t s_tab[kTapLen];
     __shared__ FoldTables s_fold;
+    __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<NW>::kFloats];
     fill_tap_table(s_tab, p.taps.v, p.T);
     fill_fold_tables(s_fold, p.taps.v, p.T);
     __syncthreads();
@@ -58,67 +66,85 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     half8 coef[NK];
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(s_tab, 32 * kk + 8 * g - c - e);
-
-    const uint32_t bin = 2u * ((uint32_t)c * (uint32_t)p.in_pitch + 8u * g);
-    const uint32_t bout = 4u * ((uint32_t)c * (uint32_t)p.out_pitch + 4u * g);
     const int wmax = p.W - 32 * NK;           // last window start that stays inside the row
 
-#ifdef HB_NO_XCD_MAP
-    const int wgpos = blockIdx.x;
-#else
     const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
-#endif
     const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int task = wave; task < p.ntasks; task += nwaves) {
-        const int rg = task / p.nct, ct = task - rg * p.nct;
-        const int y0 = 16 * rg, x0 = 16 * HB_FIR_TILES * ct;
-        const bool interior = (y0 + 16 <= p.H) && (x0 - aw >= 0) &&
-                              (x0 + 16 * (HB_FIR_TILES - 1) - aw + 32 * NK <= p.W) &&
-                              (x0 + 16 * HB_FIR_TILES <= p.W);
-        if (interior) {
-            // whole task inside the image: uniform bases, 32-bit lane offsets, no masks
-            const half_t* src = p.in + (int64_t)y0 * p.in_pitch + (x0 - aw);
-            float* dst = p.out + (int64_t)y0 * p.out_pitch + x0;
-            half8 win[HB_FIR_TILES][NK];
+        const int seg = task / p.nct, ct = task - seg * p.nct;
+        const int x0 = 16 * NW * ct;
+        const int Y0 = seg * p.steps * 16;
+        const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
+        const bool xin = (x0 - aw >= 0) && (x0 + 16 * (NW - 1) - aw + 32 * NK <= p.W) && (x0 + 16 * NW <= p.W);
+        if (xin) {
+            // strip inside the row: uniform bases, 32-bit lane offsets, coalesced row stores
+            const half_t* src = p.in + (x0 - aw);
+            float* dst = p.out + x0;
+            half8 cur[NW][NK], nxt[NW][NK];
+            auto load_step = [&](int q, half8 (&d)[NW][NK]) {
+                const int yr = min(Y0 + 16 * q + c, p.H - 1);
+                const uint32_t off = ((uint32_t)yr * (uint32_t)p.in_pitch + 8u * g) * 2u;
 #pragma unroll
-            for (int j = 0; j < HB_FIR_TILES; ++j)
+                for (int w = 0; w < NW; ++w)
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) win[j][kk] = ldg8(src, bin + 2u * (16u * j + 32u * kk));
+                    for (int kk = 0; kk < NK; ++kk) d[w][kk] = ldg8(src, off + 2u * (16u * w + 32u * kk));
+            };
+            load_step(0, cur);
+            for (int q = 0; q < nsteps; ++q) {
+                if (q + 1 < nsteps) load_step(q + 1, nxt);
+                floatx4 acc[NW];
 #pragma unroll
-            for (int j = 0; j < HB_FIR_TILES; ++j) {
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                for (int w = 0; w < NW; ++w) {
+                    acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) acc = mfma16x16x32(coef[kk], win[j][kk], acc);
-                stg4<STREAM>(dst, bout + 64u * j, acc);
+                    for (int kk = 0; kk < NK; ++kk) acc[w] = mfma16x16x32(coef[kk], cur[w][kk], acc[w]);
+                }
+                const int y0 = Y0 + 16 * q;
+                if (y0 + 16 <= p.H) {
+                    store_rows_via_lds<NW, STREAM>(s_patch[threadIdx.x >> 6], dst + (int64_t)y0 * p.out_pitch,
+                                                   (uint32_t)p.out_pitch, acc, lane);
+                } else if (y0 + c < p.H) {
+                    const uint32_t off = ((uint32_t)(y0 + c) * (uint32_t)p.out_pitch + 4u * g) * 4u;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
+                }
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) cur[w][kk] = nxt[w][kk];
             }
         } else {
-            // border task, tile by tile: the window is moved inside the row and the clamp
-            // is folded into the fragment; rows past the image repeat the last one
-            const int y = y0 + c;
-            const half_t* row = p.in + (int64_t)min(y, p.H - 1) * p.in_pitch;
-            float* orow = p.out + (int64_t)y * p.out_pitch;
+            // border strip, tile by tile: the window is moved inside the row and the clamp is
+            // folded into the fragment; rows past the image repeat the last one
 #pragma unroll 1
-            for (int j = 0; j < HB_FIR_TILES; ++j) {
-                const int xt = x0 + 16 * j;
+            for (int w = 0; w < NW; ++w) {
+                const int xt = x0 + 16 * w;
                 if (xt >= p.W) break;
                 const int ws = clampi(xt - aw, 0, wmax);
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-                if (ws == xt - aw && xt + 16 <= p.W) {
+                const bool plain = (ws == xt - aw) && (xt + 16 <= p.W);
+                half8 hi[NK], lo[NK];
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk)
-                        acc = mfma16x16x32(coef[kk], *reinterpret_cast<const half8_u*>(row + ws + 32 * kk + 8 * g), acc);
-                } else {
-#pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) {
-                        half8 hi, lo;
-                        folded_fragment(s_fold, p.T, p.anchor, p.W, xt, ws, kk, c, g, hi, lo);
-                        const half8 px = *reinterpret_cast<const half8_u*>(row + ws + 32 * kk + 8 * g);
-                        acc = mfma16x16x32(hi, px, acc);
-                        acc = mfma16x16x32(lo, px, acc);
+                for (int kk = 0; kk < NK; ++kk) {
+                    if (plain) {
+                        hi[kk] = coef[kk];
+                        lo[kk] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+                    } else {
+                        folded_fragment(s_fold, p.T, p.anchor, p.W, xt, ws, kk, c, g, hi[kk], lo[kk]);
                     }
                 }
-                if (y < p.H) store4_mask(orow, xt + 4 * g, p.W, acc);
+                for (int q = 0; q < nsteps; ++q) {
+                    const int y = Y0 + 16 * q + c;
+                    const half_t* row = p.in + (int64_t)min(y, p.H - 1) * p.in_pitch;
+                    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) {
+                        const half8 px = *reinterpret_cast<const half8_u*>(row + ws + 32 * kk + 8 * g);
+                        acc = mfma16x16x32(hi[kk], px, acc);
+                        acc = mfma16x16x32(lo[kk], px, acc);
+                    }
+                    if (y < p.H) store4_mask(p.out + (int64_t)y * p.out_pitch, xt + 4 * g, p.W, acc);
+                }
             }
         }
     }
@@ -187,7 +213,10 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
     a.T = ntaps;
     a.anchor = anchor;
     a.nct = ceil_div(W, 16 * HB_FIR_TILES);
-    a.ntasks = ceil_div(H, 16) * a.nct;
+    const int rowsteps = ceil_div(H, 16);
+    int steps = (int)(((int64_t)rowsteps * a.nct + HB_FIR_WAVES - 1) / HB_FIR_WAVES);
+    a.steps = steps < 1 ? 1 : steps;
+    a.ntasks = ceil_div(rowsteps, a.steps) * a.nct;
     a.taps = pack_taps(taps_host, ntaps);
     return HB_OK;
 }

@@ -28,10 +28,10 @@
 #include "hb_host.hpp"
 
 #ifndef HB_SEP_TILES
-#define HB_SEP_TILES 4        // 16-column tiles per wave strip
+#define HB_SEP_TILES 2        // 16-column tiles per wave strip
 #endif
 #ifndef HB_SEP_WAVES
-#define HB_SEP_WAVES 4096     // aim for about this many wave tasks per launch
+#define HB_SEP_WAVES 4096     // at most this many wave tasks per launch: one resident round, no straggler round
 #endif
 
 namespace hb {
@@ -307,8 +307,8 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
     const int nct = ceil_div(W, 16 * HB_SEP_TILES);
     const int rowsteps = ceil_div(H, 16);
     // enough tasks to fill the chip, few enough that the (NT-1)-tile warm-up stays small
-    int steps = (int)(((int64_t)rowsteps * nct) / HB_SEP_WAVES);
-    steps = steps < 1 ? 1 : (steps > 64 ? 64 : steps);
+    int steps = (int)(((int64_t)rowsteps * nct + HB_SEP_WAVES - 1) / HB_SEP_WAVES);
+    steps = steps < 1 ? 1 : steps;
     a.steps = steps;
     a.grid.nct = nct;
     a.grid.nseg = ceil_div(rowsteps, steps);
