@@ -92,8 +92,8 @@ struct PyrCoef {
 // One task: a strip of NS blocks, nsteps output steps.  FAST = the task touches no image
 // border: plain loads, interior fragments, unmasked stores.
 template <int NS, bool FAST, bool STREAM>
-__device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int X0, int R0, int nsteps,
-                                         int c, int g) {
+__device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, float* patch, int X0, int R0,
+                                         int nsteps, int c, int g) {
     constexpr int NT = NS + 1;                            // D column tiles per strip
     const int Dx0 = X0 / 2 - 8;                           // first D column of tile 0
     const int M0 = R0 / 2 - 8;                            // first D row of row tile 0
@@ -221,16 +221,23 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int
                         for (int t = 0; t < NS; ++t)
 #pragma unroll
                             for (int h = 0; h < 2; ++h) px[t][h] = ldg4(isrc, ioff + 2u * (32u * t + 16u * h));
+                        floatx4 rv[2 * NS];
 #pragma unroll
                         for (int t = 0; t < NS; ++t)
 #pragma unroll
                             for (int h = 0; h < 2; ++h) {
                                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
                                 acc = mfma16x16x32(join(U1[0][t][h], U1[1][t][h]), b, acc);
-                                floatx4 rv = {(float)px[t][h][0] - acc[0], (float)px[t][h][1] - acc[1],
-                                              (float)px[t][h][2] - acc[2], (float)px[t][h][3] - acc[3]};
-                                stg4<STREAM>(odst, ooff + 4u * (32u * t + 16u * h), rv);
+                                rv[2 * t + h] = floatx4{(float)px[t][h][0] - acc[0], (float)px[t][h][1] - acc[1],
+                                                        (float)px[t][h][2] - acc[2], (float)px[t][h][3] - acc[3]};
                             }
+#ifdef HB_DIRECT_STORES
+#pragma unroll
+                        for (int w = 0; w < 2 * NS; ++w) stg4<STREAM>(odst, ooff + 64u * w, rv[w]);
+#else
+                        store_rows_via_lds<2 * NS, STREAM>(patch, odst + (int64_t)(Rq + 16 * h2) * p.res_pitch,
+                                                           (uint32_t)p.res_pitch, rv, (g << 4) | c);
+#endif
                     } else {
                         const half_t* irow = p.in + (int64_t)min(yo, p.H - 1) * p.in_pitch;
                         float* orow = p.res + (int64_t)yo * p.res_pitch;
@@ -266,6 +273,7 @@ __global__ void __launch_bounds__(256) pyr_mfma_kernel(PyrArgs p) {
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
 
+    __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2 * NS>::kFloats];
     PyrCoef k;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -291,13 +299,13 @@ __global__ void __launch_bounds__(256) pyr_mfma_kernel(PyrArgs p) {
         const int R0 = seg * p.steps * 32;                // first output row
         const int nsteps = min(p.steps, (p.H - R0 + 31) / 32);
         if (p.grid.interior(seg, ct)) {
-            pyr_task<NS, true, STREAM>(p, k, X0, R0, nsteps, c, g);
+            pyr_task<NS, true, STREAM>(p, k, s_patch[threadIdx.x >> 6], X0, R0, nsteps, c, g);
         } else {
 #ifndef HB_PYR_NOBORDER
             // border task: one 32-column block at a time keeps this path's register use low
 #pragma unroll 1
             for (int b = 0; b < NS; ++b)
-                if (X0 + 32 * b < p.W) pyr_task<1, false, STREAM>(p, k, X0 + 32 * b, R0, nsteps, c, g);
+                if (X0 + 32 * b < p.W) pyr_task<1, false, STREAM>(p, k, s_patch[threadIdx.x >> 6], X0 + 32 * b, R0, nsteps, c, g);
 #endif
         }
     }
@@ -400,8 +408,8 @@ static hb_status pyr_prepare(PyrArgs& a, const hb_half* in, float* res, hb_half*
     a.down_pitch = down_pitch;
     const int nct = ceil_div(W, 32 * HB_PYR_NS);
     const int rowsteps = ceil_div(H, 32);
-    int steps = (int)(((int64_t)rowsteps * nct) / HB_PYR_WAVES);
-    steps = steps < 1 ? 1 : (steps > 64 ? 64 : steps);
+    int steps = (int)(((int64_t)rowsteps * nct + HB_PYR_WAVES - 1) / HB_PYR_WAVES);
+    steps = steps < 1 ? 1 : steps;
     a.steps = steps;
     a.grid.nct = nct;
     a.grid.nseg = ceil_div(rowsteps, steps);
