@@ -33,11 +33,13 @@ struct SatArgs {
     int64_t in_pitch, out_pitch;
     int nb, ns;            // 64-column strips, 64-row segments
     int Hs, Ws;            // H, W rounded up to whole tiles (workspace row lengths)
-    float* rs;             // [nb][Hs]  row sums per (strip, row)
-    float* cs;             // [ns][Ws]  column sums per (segment, column)
-    float* rcarry;         // [nb][Hs]  exclusive scan of rs over strips
-    float* ccarry;         // [ns][Ws]  exclusive scan of cs over segments
-    float* es;             // [ns][nb]  strip totals of ccarry
+    // all tables keep the scanned index innermost, so that a scan is one coalesced wave access
+    float* rs;             // [Hs][nb]  row sums per (row, strip)
+    float* cs;             // [Ws][ns]  column sums per (column, segment)
+    float* tot;            // [nb][ns]  tile totals per (strip, segment)
+    float* rcarry;         // [Hs][nb]  exclusive scan of rs over strips
+    float* ccarry;         // [Ws][ns]  exclusive scan of cs over segments
+    float* es;             // [nb][ns]  exclusive scan of tot over segments
 };
 
 // Eight pixels row[xs .. xs+7], zero where the row or the column is outside the image.
@@ -58,6 +60,13 @@ __device__ __forceinline__ half8 load8_zero(const half_t* in, int64_t pitch, int
 
 __device__ __forceinline__ half8 ones8() { return half8{1, 1, 1, 1, 1, 1, 1, 1}; }
 
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+
 // ---------------------------------------------------------------------------
 // 1  sums
 __global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
@@ -75,6 +84,23 @@ __global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
         for (int i = 0; i < 8; ++i) sel[h][i] = (half_t)((8 * g + i == 16 * h + c) ? 1.f : 0.f);
     const half8 one = ones8();
 
+    half8 X[4][2];                                        // all eight loads of the tile in flight at once
+    if (y0 + kSatTile <= p.H && x0 + kSatTile <= p.W) {
+        const half_t* src = p.in + (int64_t)y0 * p.in_pitch + x0;
+        const uint32_t off = ((uint32_t)c * (uint32_t)p.in_pitch + 8u * g) * 2u;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+                X[rt][blk] = ldg8(src, off + 2u * (16u * rt * (uint32_t)p.in_pitch + 32u * blk));
+    } else {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+                X[rt][blk] = load8_zero(p.in, p.in_pitch, y0 + 16 * rt + c, x0 + 32 * blk + 8 * g, p.H, p.W);
+    }
+
     floatx4 rowsum[4];
     half4 T[4][2][2];                                     // pixel copies in accumulator layout
 #pragma unroll
@@ -82,20 +108,23 @@ __global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
         rowsum[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            const half8 X = load8_zero(p.in, p.in_pitch, y0 + 16 * rt + c, x0 + 32 * blk + 8 * g, p.H, p.W);
-            rowsum[rt] = mfma16x16x32(X, one, rowsum[rt]);            // [m = row][n]: row totals in every column
+            rowsum[rt] = mfma16x16x32(X[rt][blk], one, rowsum[rt]);          // [m = row][n]: row totals in every column
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 floatx4 t = {0.f, 0.f, 0.f, 0.f};
-                T[rt][blk][h] = to_half4(mfma16x16x32(X, sel[h], t)); // [m = row][n = column]: lane c = column
+                T[rt][blk][h] = to_half4(mfma16x16x32(X[rt][blk], sel[h], t)); // [m = row][n = column]: lane c = column
             }
         }
     }
-    // row sums: lane (c, g) holds rows 4g + v, the same in every c
-    if (c == 0) {
+    // row sums: lane (c, g) holds rows 4g + v, the same in every c; lane c = v writes row 4g + v
+    float tile_total = 0.f;
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt)
-            *reinterpret_cast<floatx4*>(p.rs + (int64_t)b * p.Hs + y0 + 16 * rt + 4 * g) = rowsum[rt];
+    for (int rt = 0; rt < 4; ++rt) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (c == v) p.rs[(int64_t)(y0 + 16 * rt + 4 * g + v) * p.nb + b] = rowsum[rt][v];
+            if (c == 0) tile_total += rowsum[rt][v];
+        }
     }
     // column sums: contract the stacked row tiles with the all-ones matrix
 #pragma unroll
@@ -105,60 +134,50 @@ __global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
             floatx4 cs = {0.f, 0.f, 0.f, 0.f};
             cs = mfma16x16x32(join(T[0][blk][h], T[1][blk][h]), one, cs);   // [m = column][n]
             cs = mfma16x16x32(join(T[2][blk][h], T[3][blk][h]), one, cs);
-            if (c == 0)
-                *reinterpret_cast<floatx4*>(p.cs + (int64_t)s * p.Ws + x0 + 32 * blk + 16 * h + 4 * g) = cs;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (c == v) p.cs[(int64_t)(x0 + 32 * blk + 16 * h + 4 * g + v) * p.ns + s] = cs[v];
         }
+    // tile total: the four lane groups' partial row-sum totals
+    tile_total = (c == 0) ? tile_total : 0.f;
+    tile_total = wave_sum(tile_total);
+    if (lane == 0) p.tot[(int64_t)b * p.ns + s] = tile_total;
 }
 
 // ---------------------------------------------------------------------------
-// 2  scans.  Blocks [0, Hs/64): one thread per image row, exclusive scan of rs over strips.
-// Blocks [Hs/64, Hs/64 + nb): one wave per strip, one lane per column: exclusive scan of cs over
-// segments, and per segment the strip total of that scan (what lies above-left of a tile is the
-// sum of those totals over the strips to its left).
-__device__ __forceinline__ float wave_sum(float v) {
+// 2  scans.  One wave per line, one lane per element, 64 elements at a time with a running carry:
+// waves [0, Hs): image row y, exclusive scan of rs[y][.] over strips;
+// waves [Hs, Hs + Ws): image column x, exclusive scan of cs[x][.] over segments;
+// waves [Hs + Ws, Hs + Ws + nb): strip b, exclusive scan of tot[b][.] over segments (what lies
+// above-left of a tile is the sum of these over the strips to its left).
+__device__ __forceinline__ void wave_exclusive_scan_line(const float* __restrict__ src, float* __restrict__ dst,
+                                                         int n, int lane) {
+    float carry = 0.f;
+    for (int i0 = 0; i0 < n; i0 += 64) {
+        const int i = i0 + lane;
+        const float v = (i < n) ? src[i] : 0.f;
+        float x = v;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const float t = __shfl_up(x, off, 64);
+            if (lane >= off) x += t;
+        }
+        if (i < n) dst[i] = carry + x - v;
+        carry += __shfl(x, 63, 64);
+    }
 }
 
-__global__ void __launch_bounds__(64) sat_scan_kernel(SatArgs p) {
-    const int lane = threadIdx.x;
-    const int nrowblocks = p.Hs / 64;
-    if ((int)blockIdx.x < nrowblocks) {
-        const int y = 64 * blockIdx.x + lane;
-        const float* __restrict__ src = p.rs + y;
-        float* __restrict__ dst = p.rcarry + y;
-        float run = 0.f;
-        for (int b0 = 0; b0 < p.nb; b0 += 16) {
-            float v[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = (b0 + i < p.nb) ? src[(int64_t)(b0 + i) * p.Hs] : 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (b0 + i < p.nb) {
-                    dst[(int64_t)(b0 + i) * p.Hs] = run;
-                    run += v[i];
-                }
-        }
-    } else {
-        const int b = blockIdx.x - nrowblocks;
-        const int j = 64 * b + lane;
-        const float* __restrict__ src = p.cs + j;
-        float* __restrict__ dst = p.ccarry + j;
-        float run = 0.f;
-        for (int s0 = 0; s0 < p.ns; s0 += 16) {
-            float v[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = (s0 + i < p.ns) ? src[(int64_t)(s0 + i) * p.Ws] : 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (s0 + i < p.ns) {
-                    dst[(int64_t)(s0 + i) * p.Ws] = run;
-                    const float tot = wave_sum(run);
-                    if (lane == 0) p.es[(int64_t)(s0 + i) * p.nb + b] = tot;
-                    run += v[i];
-                }
-        }
+__global__ void __launch_bounds__(256) sat_scan_kernel(SatArgs p) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (wave < p.Hs) {
+        wave_exclusive_scan_line(p.rs + (int64_t)wave * p.nb, p.rcarry + (int64_t)wave * p.nb, p.nb, lane);
+    } else if (wave < p.Hs + p.Ws) {
+        const int x = wave - p.Hs;
+        wave_exclusive_scan_line(p.cs + (int64_t)x * p.ns, p.ccarry + (int64_t)x * p.ns, p.ns, lane);
+    } else if (wave < p.Hs + p.Ws + p.nb) {
+        const int b = wave - p.Hs - p.Ws;
+        wave_exclusive_scan_line(p.tot + (int64_t)b * p.ns, p.es + (int64_t)b * p.ns, p.ns, lane);
     }
 }
 
@@ -176,14 +195,53 @@ __device__ __forceinline__ float dpp_row_shr(float v, int n) {
     return __builtin_bit_cast(float, r);
 }
 
+// Table row above the tile: P(i0 - 1, x0 + lane) = everything above-left of the tile plus the
+// prefix over this strip's columns of the column carries.
+__device__ __forceinline__ float sat_row_above(const SatArgs& p, int s, int b, int lane) {
+    float above = 0.f;
+    for (int b0 = 0; b0 < b; b0 += 64)
+        if (b0 + lane < b) above += p.es[(int64_t)(b0 + lane) * p.ns + s];
+    above = wave_sum(above);
+    float colp = p.ccarry[(int64_t)(kSatTile * b + lane) * p.ns + s];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float t = __shfl_up(colp, off, 64);
+        if (lane >= off) colp += t;
+    }
+    return colp + above;
+}
+
 template <bool STREAM>
 __global__ void __launch_bounds__(256) sat_apply_mfma_kernel(SatArgs p) {
+    __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<4>::kFloats];
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     if (wave >= p.nb * p.ns) return;
     const int s = wave / p.nb, b = wave - s * p.nb;
     const int y0 = kSatTile * s, x0 = kSatTile * b;
+    const bool full = (y0 + kSatTile <= p.H) && (x0 + kSatTile <= p.W);
+
+    // all eight pixel loads and the four row carries of the tile go out first
+    half8 X[4][2];
+    float r0[4];
+    if (full) {
+        const half_t* src = p.in + (int64_t)y0 * p.in_pitch + x0;
+        const uint32_t off = ((uint32_t)c * (uint32_t)p.in_pitch + 8u * g) * 2u;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+                X[rt][blk] = ldg8(src, off + 2u * (16u * rt * (uint32_t)p.in_pitch + 32u * blk));
+    } else {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+                X[rt][blk] = load8_zero(p.in, p.in_pitch, y0 + 16 * rt + c, x0 + 32 * blk + 8 * g, p.H, p.W);
+    }
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) r0[rt] = p.rcarry[(int64_t)(y0 + 16 * rt + c) * p.nb + b];
 
     // A operands: Ut[m][k] = (k <= m + 16 half): lane (c = m, g) holds k = 8g .. 8g+7
     half8 tri[2];
@@ -193,54 +251,48 @@ __global__ void __launch_bounds__(256) sat_apply_mfma_kernel(SatArgs p) {
         for (int i = 0; i < 8; ++i) tri[h][i] = (half_t)((8 * g + i <= c + 16 * h) ? 1.f : 0.f);
     const half8 one = ones8();
 
-    // table row above the tile: scan of the column carries of this strip plus all that lies left of it
-    float above = (lane < b) ? p.es[(int64_t)s * p.nb + lane] : 0.f;
-    above = wave_sum(above);
-    float colp = p.ccarry[(int64_t)s * p.Ws + x0 + lane];
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const float t = __shfl_up(colp, off, 64);
-        if (lane >= off) colp += t;
-    }
-    colp += above;                                        // P(i0 - 1, x0 + lane)
+    const float colp = sat_row_above(p, s, b, lane);
     floatx4 ccar[4];                                      // lane (c, g): columns 16 t + 4g + v
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) ccar[t][v] = __shfl(colp, 16 * t + 4 * g + v, 64);
 
-    const bool full = (y0 + kSatTile <= p.H) && (x0 + kSatTile <= p.W);
-#pragma unroll 1
+#pragma unroll
     for (int rt = 0; rt < 4; ++rt) {
-        const int y = y0 + 16 * rt + c;
-        const float r0 = p.rcarry[(int64_t)b * p.Hs + y];
-        floatx4 rc = {r0, r0, r0, r0};                    // row carry of row c, the same in all four columns
-        float* orow = p.out + (int64_t)y * p.out_pitch;
+        floatx4 rc = {r0[rt], r0[rt], r0[rt], r0[rt]};    // row carry of row c, the same in all four columns
+        floatx4 acc[4];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            const half8 X = load8_zero(p.in, p.in_pitch, y, x0 + 32 * blk + 8 * g, p.H, p.W);
-            floatx4 z[2];
-            z[0] = mfma16x16x32(tri[0], X, rc);           // [m = column][n = row]: lane c = row, columns 4g + v
-            z[1] = mfma16x16x32(tri[1], X, rc);
-            rc = mfma16x16x32(one, X, rc);                // row carry advanced by the block's row totals
+            acc[2 * blk] = mfma16x16x32(tri[0], X[rt][blk], rc);      // [m = column][n = row]: lane c = row, columns 4g + v
+            acc[2 * blk + 1] = mfma16x16x32(tri[1], X[rt][blk], rc);
+            rc = mfma16x16x32(one, X[rt][blk], rc);                   // row carry advanced by the block's row totals
+        }
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int t = 2 * blk + h;
-                floatx4 acc = z[h];
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float x = acc[v];                     // inclusive prefix over the 16 rows of the DPP row
-                    x += dpp_row_shr(x, 1);
-                    x += dpp_row_shr(x, 2);
-                    x += dpp_row_shr(x, 4);
-                    x += dpp_row_shr(x, 8);
-                    x += ccar[t][v];
-                    acc[v] = x;
-                    ccar[t][v] = __shfl(x, (lane & 48) | 15, 64);   // value of the last row = next column carry
+            for (int v = 0; v < 4; ++v) {
+                float x = acc[t][v];                      // inclusive prefix over the 16 rows of the DPP row
+                x += dpp_row_shr(x, 1);
+                x += dpp_row_shr(x, 2);
+                x += dpp_row_shr(x, 4);
+                x += dpp_row_shr(x, 8);
+                x += ccar[t][v];
+                acc[t][v] = x;
+                ccar[t][v] = __shfl(x, (lane & 48) | 15, 64);         // value of the last row = next column carry
+            }
+        if (full) {
+            store_rows_via_lds<4, STREAM>(s_patch[threadIdx.x >> 6], p.out + (int64_t)(y0 + 16 * rt) * p.out_pitch + x0,
+                                          (uint32_t)p.out_pitch, acc, lane);
+        } else {
+            const int y = y0 + 16 * rt + c;
+            if (y < p.H) {
+                float* orow = p.out + (int64_t)y * p.out_pitch;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int xo = x0 + 16 * t + 4 * g;
+                    if (xo < p.W) store4_mask(orow, xo, p.W, acc[t]);
                 }
-                const int xo = x0 + 16 * t + 4 * g;
-                if (full) stg4<STREAM>(orow, 4u * xo, acc);
-                else if (y < p.H && xo < p.W) store4_mask(orow, xo, p.W, acc);
             }
         }
     }
@@ -262,12 +314,14 @@ __global__ void __launch_bounds__(256) sat_sums_valu_kernel(SatArgs p) {
     if (threadIdx.x < 64) {
         float a = 0.f;
         for (int x = 0; x < kSatTile; ++x) a += s_px[threadIdx.x][x];
-        p.rs[(int64_t)b * p.Hs + y0 + threadIdx.x] = a;
+        p.rs[(int64_t)(y0 + threadIdx.x) * p.nb + b] = a;
+        a = wave_sum(a);
+        if (threadIdx.x == 0) p.tot[(int64_t)b * p.ns + s] = a;
     } else if (threadIdx.x < 128) {
         const int x = threadIdx.x - 64;
         float a = 0.f;
         for (int y = 0; y < kSatTile; ++y) a += s_px[y][x];
-        p.cs[(int64_t)s * p.Ws + x0 + x] = a;
+        p.cs[(int64_t)(x0 + x) * p.ns + s] = a;
     }
 }
 
@@ -284,21 +338,12 @@ __global__ void __launch_bounds__(256) sat_apply_valu_kernel(SatArgs p) {
     }
     if (threadIdx.x < 64) {
         // table row above the tile, as in the MFMA kernel
-        const int lane = threadIdx.x;
-        float above = (lane < b) ? p.es[(int64_t)s * p.nb + lane] : 0.f;
-        above = wave_sum(above);
-        float colp = p.ccarry[(int64_t)s * p.Ws + x0 + lane];
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float t = __shfl_up(colp, off, 64);
-            if (lane >= off) colp += t;
-        }
-        s_above[lane] = colp + above;
+        s_above[threadIdx.x] = sat_row_above(p, s, b, threadIdx.x);
     }
     __syncthreads();
     if (threadIdx.x < 64) {                               // row prefix, seeded with the row carry
         const int r = threadIdx.x;
-        float a = p.rcarry[(int64_t)b * p.Hs + y0 + r];
+        float a = p.rcarry[(int64_t)(y0 + r) * p.nb + b];
         for (int x = 0; x < kSatTile; ++x) {
             a += s_t[r][x];
             s_t[r][x] = a;
@@ -325,7 +370,7 @@ __global__ void __launch_bounds__(256) sat_apply_valu_kernel(SatArgs p) {
 
 static size_t sat_workspace_floats(int H, int W) {
     const size_t nb = (size_t)ceil_div(W, kSatTile), ns = (size_t)ceil_div(H, kSatTile);
-    return 2 * (nb * ns * kSatTile) + 2 * (ns * nb * kSatTile) + ns * nb;   // rs, rcarry, cs, ccarry, es
+    return 2 * (nb * ns * kSatTile) + 2 * (ns * nb * kSatTile) + 2 * ns * nb;   // rs, rcarry, cs, ccarry, tot, es
 }
 
 static hb_status sat_prepare(SatArgs& a, const hb_half* in, float* out, int H, int W,
@@ -348,7 +393,8 @@ static hb_status sat_prepare(SatArgs& a, const hb_half* in, float* out, int H, i
     a.rcarry = a.rs + (size_t)a.nb * a.Hs;
     a.cs = a.rcarry + (size_t)a.nb * a.Hs;
     a.ccarry = a.cs + (size_t)a.ns * a.Ws;
-    a.es = a.ccarry + (size_t)a.ns * a.Ws;
+    a.tot = a.ccarry + (size_t)a.ns * a.Ws;
+    a.es = a.tot + (size_t)a.ns * a.nb;
     return HB_OK;
 }
 
@@ -369,7 +415,7 @@ extern "C" hb_status hb_sat2d(const hb_half* in, float* out, int H, int W,
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int ntiles = a.nb * a.ns;
     hipLaunchKernelGGL(sat_sums_mfma_kernel, dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(sat_scan_kernel, dim3(a.Hs / 64 + a.nb), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(sat_scan_kernel, dim3(ceil_div(a.Hs + a.Ws + a.nb, 4)), dim3(256), 0, st, a);
     if ((int64_t)H * W * 4 <= kStreamStoreMaxBytes)
         hipLaunchKernelGGL((sat_apply_mfma_kernel<true>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
     else
@@ -387,7 +433,7 @@ extern "C" hb_status hb_sat2d_valu(const hb_half* in, float* out, int H, int W,
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int ntiles = a.nb * a.ns;
     hipLaunchKernelGGL(sat_sums_valu_kernel, dim3(ntiles), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(sat_scan_kernel, dim3(a.Hs / 64 + a.nb), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(sat_scan_kernel, dim3(ceil_div(a.Hs + a.Ws + a.nb, 4)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(sat_apply_valu_kernel, dim3(ntiles), dim3(256), 0, st, a);
     return launch_status();
 }
