@@ -21,10 +21,11 @@
 #include "hb_host.hpp"
 
 #ifndef HB_FIR_TILES
-#define HB_FIR_TILES 2        // 16-column tiles per wave strip
+#define HB_FIR_TILES 4        // 16-column tiles per wave strip
 #endif
 #ifndef HB_FIR_WAVES
-#define HB_FIR_WAVES 4096     // at most this many wave tasks per launch: one resident round
+#define HB_FIR_WAVES (1 << 20) // wave tasks per launch before a task takes more than one 16-row step;
+                              // rows are independent here, so short-lived waves stream best
 #endif
 
 namespace hb {
@@ -39,6 +40,7 @@ struct FirArgs {
     int steps;           // 16-row steps per task
     int ntasks;          // strips x row segments
     Taps taps;
+    FoldTables fold;
 };
 
 __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
@@ -50,12 +52,7 @@ __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
 template <int NK, bool STREAM>
 __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     constexpr int NW = HB_FIR_TILES;
-    __shared__ half_t s_tab[kTapLen];
-    __shared__ FoldTables s_fold;
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<NW>::kFloats];
-    fill_tap_table(s_tab, p.taps.v, p.T);
-    fill_fold_tables(s_fold, p.taps.v, p.T);
-    __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
@@ -65,7 +62,7 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     const int aw = p.anchor + e;              // window start, left of the tile
     half8 coef[NK];
 #pragma unroll
-    for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(s_tab, 32 * kk + 8 * g - c - e);
+    for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(p.taps.tab, 32 * kk + 8 * g - c - e);
     const int wmax = p.W - 32 * NK;           // last window start that stays inside the row
 
     const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -101,10 +98,13 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
                     for (int kk = 0; kk < NK; ++kk) acc[w] = mfma16x16x32(coef[kk], cur[w][kk], acc[w]);
                 }
                 const int y0 = Y0 + 16 * q;
+#ifndef HB_DIRECT_STORES
                 if (y0 + 16 <= p.H) {
                     store_rows_via_lds<NW, STREAM>(s_patch[threadIdx.x >> 6], dst + (int64_t)y0 * p.out_pitch,
                                                    (uint32_t)p.out_pitch, acc, lane);
-                } else if (y0 + c < p.H) {
+                } else
+#endif
+                if (y0 + c < p.H) {
                     const uint32_t off = ((uint32_t)(y0 + c) * (uint32_t)p.out_pitch + 4u * g) * 4u;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
@@ -130,7 +130,7 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
                         hi[kk] = coef[kk];
                         lo[kk] = half8{0, 0, 0, 0, 0, 0, 0, 0};
                     } else {
-                        folded_fragment(s_fold, p.T, p.anchor, p.W, xt, ws, kk, c, g, hi[kk], lo[kk]);
+                        folded_fragment(p.fold, p.T, p.anchor, p.W, xt, ws, kk, c, g, hi[kk], lo[kk]);
                     }
                 }
                 for (int q = 0; q < nsteps; ++q) {
@@ -159,7 +159,7 @@ constexpr int kValuPitch = kValuMaxChunks * 8 + 8;
 __global__ void __launch_bounds__(256) fir1d_valu_kernel(FirArgs p) {
     __shared__ half_t s_px[16 * kValuPitch];
     __shared__ float s_k[HB_MAX_TAPS];
-    if (threadIdx.x < HB_MAX_TAPS) s_k[threadIdx.x] = (float)tap_from_bits(p.taps.v[threadIdx.x]);
+    if (threadIdx.x < HB_MAX_TAPS) s_k[threadIdx.x] = (float)tap_at(p.taps.tab, threadIdx.x);
 
     const int nctv = (p.W + kValuTileW - 1) / kValuTileW;
     const int rg = blockIdx.x / nctv, ct = blockIdx.x - rg * nctv;
@@ -218,6 +218,7 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
     a.steps = steps < 1 ? 1 : steps;
     a.ntasks = ceil_div(rowsteps, a.steps) * a.nct;
     a.taps = pack_taps(taps_host, ntaps);
+    a.fold = pack_fold_tables(taps_host, ntaps);
     return HB_OK;
 }
 

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "hb_host.hpp"
+
 namespace hb {
 
 typedef _Float16 half_t;
@@ -178,22 +180,14 @@ __device__ __forceinline__ int xcd_contiguous(int wg, int nwg) {
     return (wg & 7) * per + (wg >> 3);
 }
 
-// Zero-padded tap table in LDS: entry kTapPad + t holds taps[t] for 0 <= t < ntaps and
-// zero for every other t in [-kTapPad, kTapLen - kTapPad).  A Toeplitz fragment is then
-// eight consecutive entries, fetched with one (unaligned) 16-byte LDS read.
-constexpr int kTapPad = 16;
-constexpr int kTapLen = 16 + 64 + 48;
-
-__device__ __forceinline__ void fill_tap_table(half_t* tab, const uint16_t* taps_bits, int ntaps) {
-    for (int i = threadIdx.x; i < kTapLen; i += blockDim.x) {
-        const int t = i - kTapPad;
-        tab[i] = (t >= 0 && t < ntaps) ? __builtin_bit_cast(half_t, taps_bits[t]) : (half_t)0;
-    }
-}
-__device__ __forceinline__ half8 tap_run(const half_t* tab, int t0) {
+// Toeplitz fragment = eight consecutive entries of the zero-padded tap table that travels in the
+// kernel arguments (see Taps): one 16-byte load at a 2-byte aligned address.
+__device__ __forceinline__ half8 tap_run(const uint16_t* tab, int t0) {
     return *reinterpret_cast<const half8_u*>(tab + kTapPad + t0);
 }
-
+__device__ __forceinline__ half_t tap_at(const uint16_t* tab, int t) {
+    return __builtin_bit_cast(half_t, tab[kTapPad + t]);
+}
 
 // ---------------------------------------------------------------------------
 // Clamp-to-edge folded into the coefficient matrix.
@@ -206,19 +200,7 @@ __device__ __forceinline__ half8 tap_run(const half_t* tab, int t0) {
 // Sums of fp16 taps are not fp16 numbers, so a folded fragment is carried as hi + lo
 // (two products), which keeps the border as accurate as the interior.
 //
-// Tables in LDS: kf[t] = taps as fp32 (t < ntaps), pfx[i] = sum of taps t < i (i <= ntaps).
-struct FoldTables {
-    float kf[64];
-    float pfx[65];
-};
-__device__ __forceinline__ void fill_fold_tables(FoldTables& ft, const uint16_t* taps_bits, int ntaps) {
-    for (int i = threadIdx.x; i <= 64; i += blockDim.x) {
-        float s = 0.f;
-        for (int t = 0; t < i && t < ntaps; ++t) s += (float)__builtin_bit_cast(half_t, taps_bits[t]);
-        ft.pfx[i] = s;
-        if (i < 64) ft.kf[i] = i < ntaps ? (float)__builtin_bit_cast(half_t, taps_bits[i]) : 0.f;
-    }
-}
+// Tables (FoldTables, filled on the host): kf[t] = taps as fp32, pfx[i] = sum of taps t < i.
 // Weight of pixel u in output x: sum of taps[t] over t with clamp(x + t - anchor, 0, n-1) == u.
 __device__ __forceinline__ float folded_tap(const FoldTables& ft, int ntaps, int anchor, int n, int x, int u) {
     float v = 0.f;

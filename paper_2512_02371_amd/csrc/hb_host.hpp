@@ -9,9 +9,18 @@
 
 namespace hb {
 
-// Filter taps as they travel inside the kernel arguments (fp16 bits, zero padded).
+// Filter taps as they travel inside the kernel arguments: a zero-padded fp16 table (entry
+// kTapPad + t holds taps[t] for 0 <= t < ntaps and zero for every other t in
+// [-kTapPad, kTapLen - kTapPad)), from which a Toeplitz fragment is eight consecutive entries,
+// and, for the border tiles, the taps and their running sums in fp32.
+constexpr int kTapPad = 16;
+constexpr int kTapLen = 16 + 64 + 48;
 struct Taps {
-    uint16_t v[HB_MAX_TAPS];
+    uint16_t tab[kTapLen];
+};
+struct FoldTables {
+    float kf[64];        // taps as fp32, zero beyond ntaps
+    float pfx[65];       // pfx[i] = sum of taps t < i
 };
 
 // MI355X: 256 compute units, 4 SIMDs each.  Streaming kernels launch one short-lived
@@ -60,11 +69,47 @@ inline hb_status check_taps(const hb_half* taps, int ntaps, int anchor) {
     return HB_OK;
 }
 
+inline float half_bits_to_float(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h >> 15) << 31;
+    int e = (h >> 10) & 0x1f;
+    uint32_t f = h & 0x3ff, bits;
+    if (e == 0) {
+        if (f == 0) {
+            bits = sign;
+        } else {                                          // subnormal: renormalise
+            e = 1;
+            while (!(f & 0x400)) { f <<= 1; --e; }
+            bits = sign | ((uint32_t)(e + 112) << 23) | ((f & 0x3ff) << 13);
+        }
+    } else if (e == 31) {
+        bits = sign | 0x7f800000u | (f << 13);
+    } else {
+        bits = sign | ((uint32_t)(e + 112) << 23) | (f << 13);
+    }
+    float out;
+    memcpy(&out, &bits, sizeof(out));
+    return out;
+}
+
 inline Taps pack_taps(const hb_half* taps, int ntaps) {
     Taps t;
     memset(&t, 0, sizeof(t));
-    memcpy(t.v, taps, sizeof(uint16_t) * (size_t)ntaps);
+    memcpy(t.tab + kTapPad, taps, sizeof(uint16_t) * (size_t)ntaps);
     return t;
+}
+
+inline FoldTables pack_fold_tables(const hb_half* taps, int ntaps) {
+    FoldTables ft;
+    memset(&ft, 0, sizeof(ft));
+    float run = 0.f;
+    for (int i = 0; i <= 64; ++i) {
+        ft.pfx[i] = run;
+        if (i < ntaps) {
+            ft.kf[i] = half_bits_to_float(taps[i]);
+            run += ft.kf[i];
+        }
+    }
+    return ft;
 }
 
 inline hb_status launch_status() { return hipGetLastError() == hipSuccess ? HB_OK : HB_ERR_HIP; }

@@ -45,6 +45,7 @@ struct SepArgs {
     int steps;         // 16-row steps per task
     TaskGrid grid;     // strips x row segments
     Taps tx, ty;
+    FoldTables foldx;
 };
 
 __device__ __forceinline__ half_t sep_tap(uint16_t b) { return __builtin_bit_cast(half_t, b); }
@@ -187,13 +188,7 @@ template <int NKX, int NT, bool STREAM>
 __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
     constexpr int NK = (NT + 1) / 2;          // K = 32 chunks of the column pass
     constexpr int NW = HB_SEP_TILES;
-    __shared__ half_t s_tx[kTapLen], s_ty[kTapLen];
-    __shared__ FoldTables s_fold;
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<HB_SEP_TILES>::kFloats];
-    fill_tap_table(s_tx, p.tx.v, p.Tx);
-    fill_tap_table(s_ty, p.ty.v, p.Ty);
-    fill_fold_tables(s_fold, p.tx.v, p.Tx);
-    __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
@@ -202,12 +197,12 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
     const int xw = p.ax + e;                  // window start, left of the tile
     half8 coefx[NKX];                         // B operand of the row pass: Bx[32kk + 8g + i][c]
 #pragma unroll
-    for (int kk = 0; kk < NKX; ++kk) coefx[kk] = tap_run(s_tx, 32 * kk + 8 * g - c - e);
+    for (int kk = 0; kk < NKX; ++kk) coefx[kk] = tap_run(p.tx.tab, 32 * kk + 8 * g - c - e);
     half8 coefy[NK];                          // B operand of the column pass, chained slot order
 #pragma unroll
     for (int j = 0; j < NK; ++j)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) coefy[j][i] = s_ty[kTapPad + 32 * j + krow32(g, i) - c];
+        for (int i = 0; i < 8; ++i) coefy[j][i] = tap_at(p.ty.tab, 32 * j + krow32(g, i) - c);
 
 #ifdef HB_NO_XCD_MAP
     const int wgpos = blockIdx.x;
@@ -222,8 +217,8 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
         const int x0 = 16 * NW * ct;
         const int Y0 = seg * p.steps * 16;
         const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
-        if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, s_fold, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
-        else sep_task<NKX, NT, NW, false, STREAM>(p, s_fold, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, p.foldx, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        else sep_task<NKX, NT, NW, false, STREAM>(p, p.foldx, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
     }
 }
 
@@ -240,8 +235,8 @@ __global__ void __launch_bounds__(256) sepblur_valu_kernel(SepArgs p) {
     __shared__ half_t s_tmp[kVRows * kVTmpPitch];
     __shared__ float s_kx[HB_MAX_TAPS], s_ky[HB_MAX_TAPS];
     if (threadIdx.x < HB_MAX_TAPS) {
-        s_kx[threadIdx.x] = (float)sep_tap(p.tx.v[threadIdx.x]);
-        s_ky[threadIdx.x] = (float)sep_tap(p.ty.v[threadIdx.x]);
+        s_kx[threadIdx.x] = (float)tap_at(p.tx.tab, threadIdx.x);
+        s_ky[threadIdx.x] = (float)tap_at(p.ty.tab, threadIdx.x);
     }
     const int nctv = (p.W + kVTW - 1) / kVTW;
     const int rt = blockIdx.x / nctv, ct = blockIdx.x - rt * nctv;
@@ -323,6 +318,7 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
     a.grid.s1 = a.grid.c1 > a.grid.c0 ? a.grid.nseg : 0;
     a.tx = pack_taps(tx, ntx);
     a.ty = pack_taps(ty, nty);
+    a.foldx = pack_fold_tables(tx, ntx);
     return HB_OK;
 }
 
