@@ -14,13 +14,25 @@
 // columns of one row per lane and the residual in - U leaves with 16-byte stores.
 //
 // Geometry.  A wave owns a strip of NS blocks of 32 output columns and walks down in steps
-// of 32 output rows.  D tiles (16 x 16) lie on a grid shifted by 8 so that the K = 32
-// window of an up pass (two adjacent D tiles) covers the 18 values that 32 outputs need:
+// of 32 output rows.  D tiles (16 x 16) lie on a grid shifted against the outputs so that the
+// K = 32 window of an up pass (two adjacent D tiles) covers the 18 values that 32 outputs need:
 // NS + 1 column tiles per strip, one extra row tile per task.  A D tile needs 35 image
-// rows/columns: a K = 32 plus a K = 16 product over three image row tiles / a 48-pixel
-// window.  At the image border the up passes clamp the D index; there the coefficient
+// rows/columns: a K = 32 plus a K = 16 product over three image row tiles / a 48-pixel window.
+//
+// Interior tasks (pyr_fast_task) shift the D grid by 7: image tiles then start 16 rows / columns
+// before the outputs, so an image row tile holds exactly the rows of one 16-row output tile.  The
+// loaded operand fragments are parked in a wave-private LDS ring and come back, three tiles
+// later, as the B operand of a 0/1 selection product that seeds the accumulator of the last
+// pass with the original pixels: the residual in - U then needs no second read of the image
+// and no separate subtraction (the up-x pass stores -U1).  Image tiles are requested
+// HB_PYR_PD tiles ahead into a register ring (the loop is unrolled over the ring, so no copy
+// waits on a load in flight).
+//
+// At the image border (pyr_task) the up passes clamp the D index; there the coefficient
 // fragments are rebuilt from absolute indices (taps that clamp onto the same D sample
 // add up), which also makes out-of-range D tiles (computed from clamped pixels) inert.
+#include <type_traits>
+
 #include "hb_device.hpp"
 #include "hb_host.hpp"
 
@@ -28,7 +40,10 @@
 #define HB_PYR_NS 2           // 32-column output blocks per wave strip
 #endif
 #ifndef HB_PYR_WAVES
-#define HB_PYR_WAVES 8192     // aim for about this many wave tasks per launch
+#define HB_PYR_WAVES 2048     // aim for about this many wave tasks per launch (one resident round)
+#endif
+#ifndef HB_PYR_PD
+#define HB_PYR_PD 3           // image row tiles requested ahead of the one being consumed
 #endif
 
 namespace hb {
@@ -39,8 +54,16 @@ struct PyrArgs {
     half_t* down;      // may be null
     int H, W, Hd, Wd;
     int64_t in_pitch, res_pitch, down_pitch;
-    int steps;         // 32-row output steps per task
-    TaskGrid grid;     // strips x row segments
+    // Task list of one launch.  Strips are 32*NS output columns wide, row steps 32 output rows high.
+    // Border tasks come first (one strip x one row step each, the slow path): the row steps above r0
+    // and from r1 on over all strips, then the strips left of c0 and from c1 on over the row steps
+    // between.  Interior tasks follow: strips [c0, c1) x segments of `steps` row steps out of [r0, r1).
+    int nct, rowsteps;
+    int c0, c1, r0, r1;
+    int steps, nseg;   // row steps per interior task, interior segments per strip
+    int ntop, nbot, nleft, nborder;
+
+    __host__ __device__ int count() const { return nborder + (c1 - c0) * nseg; }
 };
 
 __device__ __forceinline__ half_t w5(int t) {
@@ -81,19 +104,15 @@ __device__ __forceinline__ half8 up_fragment_clamped(int d0, int x0abs, int n, i
     return r;
 }
 
-// Interior coefficient fragments (B operands; lane c = output index of the pass).
+// Row-direction coefficient fragments of the border path (B operands; lane c = D row).
 struct PyrCoef {
-    half8 dx32;        // A_down, slots = pixels 0..31 of the window (natural order)
     half8 dy32;        // A_down, slots = rows 0..31 of the window (chained order)
-    half8 d16;         // A_down for pixels / rows 32..35, in slots 8g + (0..3); zero in 8g + (4..7)
-    half8 up[2];       // phase matrix for the first / second 16 outputs of a 32-output block
+    half8 d16;         // A_down for rows 32..35, in slots 8g + (0..3); zero in 8g + (4..7)
 };
 
-// One task: a strip of NS blocks, nsteps output steps.  FAST = the task touches no image
-// border: plain loads, interior fragments, unmasked stores.
-template <int NS, bool FAST, bool STREAM>
-__device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, float* patch, int X0, int R0,
-                                         int nsteps, int c, int g) {
+// One border task: a strip of NS blocks, nsteps output steps, anywhere in the image (D grid shift 8).
+template <int NS, bool STREAM>
+__device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int X0, int R0, int nsteps, int c, int g) {
     constexpr int NT = NS + 1;                            // D column tiles per strip
     const int Dx0 = X0 / 2 - 8;                           // first D column of tile 0
     const int M0 = R0 / 2 - 8;                            // first D row of row tile 0
@@ -114,41 +133,29 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, flo
 #pragma unroll
             for (int h = 0; h < 2; ++h) U1[a][t][h] = z4;
 
-    // border tasks: per D column tile, a pixel window moved inside the row and A_down
-    // fragments with the column clamp folded in
+    // per D column tile, a pixel window moved inside the row and A_down fragments with the
+    // column clamp folded in
     int wsx[NT];
-    half8 fdx32[FAST ? 1 : NT], fdx16[FAST ? 1 : NT];
-    if (!FAST) {
+    half8 fdx32[NT], fdx16[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            wsx[t] = clampi(px0 + 32 * t, 0, p.W - 48);
-            const int n = Dx0 + 16 * t + c;
+    for (int t = 0; t < NT; ++t) {
+        wsx[t] = clampi(px0 + 32 * t, 0, p.W - 48);
+        const int n = Dx0 + 16 * t + c;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                fdx32[t][i] = down_tap_clamped(n, wsx[t] + 8 * g + i, p.W);
-                fdx16[t][i] = (i < 4) ? down_tap_clamped(n, wsx[t] + 32 + 4 * g + i, p.W) : (half_t)0;
-            }
+        for (int i = 0; i < 8; ++i) {
+            fdx32[t][i] = down_tap_clamped(n, wsx[t] + 8 * g + i, p.W);
+            fdx16[t][i] = (i < 4) ? down_tap_clamped(n, wsx[t] + 32 + 4 * g + i, p.W) : (half_t)0;
         }
     }
 
     half8 win32[NT], nxt32[NT];
     half4 win16[NT], nxt16[NT];
     auto load_rows = [&](int r, half8 (&a32)[NT], half4 (&a16)[NT]) {
-        if (FAST) {
-            const half_t* src = p.in + px0;
-            const uint32_t off = ((uint32_t)(y00 + 16 * r + c) * (uint32_t)p.in_pitch) * 2u;
+        const half_t* row = p.in + (int64_t)clampi(y00 + 16 * r + c, 0, p.H - 1) * p.in_pitch;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                a32[t] = ldg8(src, off + 2u * (32u * t + 8u * g));
-                a16[t] = ldg4(src, off + 2u * (32u * t + 32u + 4u * g));
-            }
-        } else {
-            const half_t* row = p.in + (int64_t)clampi(y00 + 16 * r + c, 0, p.H - 1) * p.in_pitch;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                a32[t] = *reinterpret_cast<const half8_u*>(row + wsx[t] + 8 * g);
-                a16[t] = *reinterpret_cast<const half4_u*>(row + wsx[t] + 32 + 4 * g);
-            }
+        for (int t = 0; t < NT; ++t) {
+            a32[t] = *reinterpret_cast<const half8_u*>(row + wsx[t] + 8 * g);
+            a16[t] = *reinterpret_cast<const half4_u*>(row + wsx[t] + 32 + 4 * g);
         }
     };
 
@@ -162,8 +169,8 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, flo
             T1[0][t] = T1[1][t];
             T1[1][t] = T1[2][t];
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-            acc = mfma16x16x32(win32[t], FAST ? k.dx32 : fdx32[t], acc);
-            acc = mfma16x16x32(join(win16[t], z4), FAST ? k.d16 : fdx16[t], acc);
+            acc = mfma16x16x32(win32[t], fdx32[t], acc);
+            acc = mfma16x16x32(join(win16[t], z4), fdx16[t], acc);
             T1[2][t] = to_half4(acc);
         }
         if ((r & 1) == 0 && r >= 2) {
@@ -197,8 +204,7 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, flo
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     U1[0][t][h] = U1[1][t][h];
-                    const half8 b = FAST ? k.up[h]
-                                         : up_fragment_clamped(Dx0 + 16 * t, X0 + 32 * t + 16 * h, p.Wd, c, g);
+                    const half8 b = up_fragment_clamped(Dx0 + 16 * t, X0 + 32 * t + 16 * h, p.Wd, c, g);
                     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
                     acc = mfma16x16x32(join(D[t], D[t + 1]), b, acc);
                     U1[1][t][h] = to_half4(acc);
@@ -208,54 +214,24 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, flo
                 const int Rq = R0 + 32 * (q - 1);
 #pragma unroll
                 for (int h2 = 0; h2 < 2; ++h2) {
-                    const half8 b = FAST ? k.up[h2]
-                                         : up_fragment_clamped(M0 + 16 * (q - 1), Rq + 16 * h2, p.Hd, c, g);
+                    const half8 b = up_fragment_clamped(M0 + 16 * (q - 1), Rq + 16 * h2, p.Hd, c, g);
                     const int yo = Rq + 16 * h2 + c;
-                    if (FAST) {
-                        const half_t* isrc = p.in + X0;
-                        float* odst = p.res + X0;
-                        const uint32_t ioff = ((uint32_t)yo * (uint32_t)p.in_pitch + 4u * g) * 2u;
-                        const uint32_t ooff = ((uint32_t)yo * (uint32_t)p.res_pitch + 4u * g) * 4u;
-                        half4 px[NS][2];
+                    const half_t* irow = p.in + (int64_t)min(yo, p.H - 1) * p.in_pitch;
+                    float* orow = p.res + (int64_t)yo * p.res_pitch;
 #pragma unroll
-                        for (int t = 0; t < NS; ++t)
+                    for (int t = 0; t < NS; ++t)
 #pragma unroll
-                            for (int h = 0; h < 2; ++h) px[t][h] = ldg4(isrc, ioff + 2u * (32u * t + 16u * h));
-                        floatx4 rv[2 * NS];
-#pragma unroll
-                        for (int t = 0; t < NS; ++t)
-#pragma unroll
-                            for (int h = 0; h < 2; ++h) {
-                                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-                                acc = mfma16x16x32(join(U1[0][t][h], U1[1][t][h]), b, acc);
-                                rv[2 * t + h] = floatx4{(float)px[t][h][0] - acc[0], (float)px[t][h][1] - acc[1],
-                                                        (float)px[t][h][2] - acc[2], (float)px[t][h][3] - acc[3]};
+                        for (int h = 0; h < 2; ++h) {
+                            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                            acc = mfma16x16x32(join(U1[0][t][h], U1[1][t][h]), b, acc);
+                            const int xo = X0 + 32 * t + 16 * h + 4 * g;
+                            if (yo < p.H && xo < p.W) {
+                                const half4 px = load4_clamp(irow, xo, p.W);
+                                floatx4 rv = {(float)px[0] - acc[0], (float)px[1] - acc[1],
+                                              (float)px[2] - acc[2], (float)px[3] - acc[3]};
+                                store4_mask(orow, xo, p.W, rv);
                             }
-#ifdef HB_DIRECT_STORES
-#pragma unroll
-                        for (int w = 0; w < 2 * NS; ++w) stg4<STREAM>(odst, ooff + 64u * w, rv[w]);
-#else
-                        store_rows_via_lds<2 * NS, STREAM>(patch, odst + (int64_t)(Rq + 16 * h2) * p.res_pitch,
-                                                           (uint32_t)p.res_pitch, rv, (g << 4) | c);
-#endif
-                    } else {
-                        const half_t* irow = p.in + (int64_t)min(yo, p.H - 1) * p.in_pitch;
-                        float* orow = p.res + (int64_t)yo * p.res_pitch;
-#pragma unroll
-                        for (int t = 0; t < NS; ++t)
-#pragma unroll
-                            for (int h = 0; h < 2; ++h) {
-                                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-                                acc = mfma16x16x32(join(U1[0][t][h], U1[1][t][h]), b, acc);
-                                const int xo = X0 + 32 * t + 16 * h + 4 * g;
-                                if (yo < p.H && xo < p.W) {
-                                    const half4 px = load4_clamp(irow, xo, p.W);
-                                    floatx4 rv = {(float)px[0] - acc[0], (float)px[1] - acc[1],
-                                                  (float)px[2] - acc[2], (float)px[3] - acc[3]};
-                                    store4_mask(orow, xo, p.W, rv);
-                                }
-                            }
-                    }
+                        }
                 }
             }
         }
@@ -267,23 +243,215 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, flo
     }
 }
 
-template <bool STREAM>
-__global__ void __launch_bounds__(256) pyr_mfma_kernel(PyrArgs p) {
+// ---------------------------------------------------------------------------
+// Interior tasks.
+//
+// Coefficient fragments of the interior path (D grid shift 7, image column tiles of 32 pixels
+// starting 16 left of the strip).  The two halves of a chained K = 32 operand live in one
+// register quadruple that is filled alternately (tile r goes to half r % 2), so every second
+// use sees the halves in swapped order and takes the fragment built for that order: no
+// register is ever copied to line operands up.
+struct PyrFastCoef {
+    half8 dxa, dxb;    // A_down over image column tiles j and j + 1 (slot = pixel)
+    half8 dy32;        // A_down over image row tiles r-2 | r-1 (chained slot order)
+    half8 dy16;        // A_down for rows 32..35 in slots 8g + (0..3), zero in 8g + (4..7)
+    half8 up[2];       // phase matrix of the first / second 16 outputs, operand halves (older | newer)
+    half8 upsw[2];     // same for halves (newer | older)
+    half8 sel[2];      // 0/1 selection (A operand): output column m <- tile pixel 16 + m / pixel m
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kBufFlags = 0x00020000;                     // raw buffer, 32-bit data format
+
+__device__ __forceinline__ half4 lo4(half8 v) { return __builtin_shufflevector(v, v, 0, 1, 2, 3); }
+__device__ __forceinline__ half4 hi4(half8 v) { return __builtin_shufflevector(v, v, 4, 5, 6, 7); }
+
+constexpr int kPyrStashTile = 1024;                       // bytes per parked fragment: 64 lanes x 16
+template <int NS>
+struct PyrStash { static constexpr int kSlot = (NS + 1) * kPyrStashTile, kBytes = 3 * kSlot; };
+
+// One interior task: a strip of NS blocks, nsteps (even) output steps, no image border in reach.
+// Image row tile r holds rows R0 - 16 + 16 r + (0..15); image column tile j holds pixels
+// X0 - 16 + 32 j + (0..31).  Tile loads are buffer loads: a wave-uniform descriptor of the
+// task's footprint, one per-lane offset for the whole task, the row tile as scalar offset.
+template <int NS, bool STREAM, bool DOWN>
+__device__ __forceinline__ void pyr_fast_task(const PyrArgs& p, const PyrFastCoef& k, float* patch, char* stash,
+                                              int X0, int R0, int nsteps, int lane) {
+    constexpr int NT = NS + 1;                            // D column tiles per strip
+    constexpr int NC = NS + 2;                            // image column tiles per strip
+    constexpr int NB = 4;                                 // register ring of image row tiles (3 ahead)
+    constexpr int NW = 2 * NS;                            // 16-column output tiles per row tile
+    const int c = lane & 15, g = lane >> 4;
+    const int Dx0 = X0 / 2 - 7, M0 = R0 / 2 - 7;          // first D column / row of tile 0
+
+    const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<half_t*>(p.in + (int64_t)(R0 - 16) * p.in_pitch + (X0 - 16)), 0, 0x7fffffff, kBufFlags);
+    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+        p.res + (int64_t)R0 * p.res_pitch + X0, 0, 0x7fffffff, kBufFlags);
+    const uint32_t ivoff = (uint32_t)c * (uint32_t)p.in_pitch * 2u + 16u * g;
+    const uint32_t itile = 32u * (uint32_t)p.in_pitch;    // bytes per image row tile
+    const uint32_t ovoff = ((uint32_t)g * (uint32_t)p.res_pitch + 4u * c) * 4u;
+    const uint32_t orow4 = 16u * (uint32_t)p.res_pitch;   // bytes per four output rows
+    const int ntiles = 2 * nsteps + 3;
+
+    half8 W[NB][NC];                                      // image row tiles in flight / in use
+    half8 TP[2][NT];                                      // row-filtered tiles: TP[a] = tiles (4i+2a | 4i+2a+1)
+    half8 UP[NS][2];                                      // -(up-x results) of D row tiles (even q | odd q)
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) TP[a][t] = half8{0, 0, 0, 0, 0, 0, 0, 0};   // (finite: zero weights meet these)
+#pragma unroll
+    for (int t = 0; t < NS; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) UP[t][h] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+
+    auto load_tile = [&](int r, half8 (&w)[NC]) {
+        const uint32_t soff = (uint32_t)min(r, ntiles - 1) * itile;   // past the end: the last tile again
+#pragma unroll
+        for (int j = 0; j < NC; ++j)
+            w[j] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(rin, ivoff + 64u * j, soff, 0));
+    };
+    int sslot = 0;                                        // stash slot of the current tile: r % 3
+    char* const mystash = stash + 16 * lane;
+
+    // One image row tile.  S = r % 4 (compile time): ring slot of the tile, half of TP it fills.
+    auto tile = [&](auto Stag, int r, __amdgpu_buffer_rsrc_t rdst) {
+        constexpr int S = decltype(Stag)::value;
+        // (no instruction may move between tiles: a product hoisted from a later tile would wait for
+        // loads that are meant to stay in flight)
+        __builtin_amdgcn_sched_barrier(0);
+        load_tile(r + 3, W[(S + 3) % NB]);
+        const half8 (&w)[NC] = W[S];
+        // pass 1: down along x, all D column tiles
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+            acc = mfma16x16x32(w[t], k.dxa, acc);
+            acc = mfma16x16x32(w[t + 1], k.dxb, acc);
+            const half4 h = to_half4(acc);
+            TP[S >> 1][t] = (S & 1) ? join(lo4(TP[S >> 1][t]), h) : join(h, hi4(TP[S >> 1][t]));
+        }
+        if constexpr ((S & 1) == 0) {
+            const int q = r / 2 - 1;                      // D row tile completed by image tiles r-2 .. r
+            constexpr int QO = (S == 0);                  // q is odd for S = 0, even for S = 2
+            // pass 2: down along y (lane c = D row, four D columns)
+            half4 D[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                acc = mfma16x16x32(TP[(S >> 1) ^ 1][t], k.dy32, acc);
+                acc = mfma16x16x32(TP[S >> 1][t], k.dy16, acc);   // upper half: older rows, zero weights
+                D[t] = to_half4(acc);
+            }
+            if constexpr (DOWN) {
+                // each task writes the D samples under its own outputs
+                const int m = M0 + 16 * q + c;
+                if (m >= R0 / 2 && m < R0 / 2 + 16 * nsteps) {
+                    half_t* drow = p.down + (int64_t)m * p.down_pitch;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int n = Dx0 + 16 * t + 4 * g + v;
+                            if (n >= X0 / 2 && n < X0 / 2 + 16 * NS) drow[n] = D[t][v];
+                        }
+                }
+            }
+            // pass 3: up along x (lane c = output column, four D rows), sign flipped
+#pragma unroll
+            for (int t = 0; t < NS; ++t) {
+                const half8 dd = join(D[t], D[t + 1]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                    acc = mfma16x16x32(dd, k.up[h], acc);
+                    const half4 u = to_half4(-acc);
+                    UP[t][h] = QO ? join(lo4(UP[t][h]), u) : join(u, hi4(UP[t][h]));
+                }
+            }
+            {
+                // pass 4: parked pixels (tiles r-3, r-2) minus up along y, output rows 32 (q-1) + (0..31)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const int sl = (sslot + h2 >= 3) ? sslot + h2 - 3 : sslot + h2;
+                    const char* park = mystash + sl * PyrStash<NS>::kSlot;
+                    half8 px[NT];
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) px[j] = *reinterpret_cast<const half8*>(park + j * kPyrStashTile);
+                    const half8 b = QO ? k.up[h2] : k.upsw[h2];
+                    floatx4 rv[NW];
+#pragma unroll
+                    for (int t = 0; t < NS; ++t)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                            acc = mfma16x16x32(k.sel[h], px[t + h], acc);
+                            acc = mfma16x16x32(UP[t][h], b, acc);
+                            rv[2 * t + h] = acc;
+                        }
+                    // rows through the wave-private patch: 256-byte runs of one row per 16 lanes
+#pragma unroll
+                    for (int w2 = 0; w2 < NW; ++w2)
+                        *reinterpret_cast<floatx4*>(patch + c * RowPatch<NW>::kPitch + 16 * w2 + 4 * g) = rv[w2];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const uint32_t so = (uint32_t)(8 * (q - 1) + 4 * h2) * orow4;
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4) {
+                        const floatx4 v = *reinterpret_cast<const floatx4*>(patch + (4 * s4 + g) * RowPatch<NW>::kPitch + 4 * c);
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rdst, ovoff,
+                                                               so + (uint32_t)s4 * orow4, STREAM ? 2 : 0);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+        // park this tile's fragments that lie under the outputs (read back three tiles later)
+        {
+            char* park = mystash + sslot * PyrStash<NS>::kSlot;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) *reinterpret_cast<half8*>(park + j * kPyrStashTile) = w[j];
+            sslot = (sslot == 2) ? 0 : sslot + 1;
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+
+    // Tiles run in rounds of four (ring slots 0..3); slots 0 and 2 complete a D row tile and store the
+    // 32 output rows above it.  The first round has nothing to store yet: its stores go through a
+    // descriptor of zero length, which the hardware drops.  Every round thereby issues the same
+    // sequence of memory instructions, and so does the start-up below (loads, eight dropped stores,
+    // loads): the compiler's counted waits then leave three tiles in flight instead of falling back
+    // to the shortest path through the code.
+    const __amdgpu_buffer_rsrc_t rnull = __builtin_amdgcn_make_buffer_rsrc(p.res, 0, 0, kBufFlags);
+    load_tile(0, W[0]);
+    load_tile(1, W[1]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{0u, 0u, 0u, 0u}, rnull, ovoff, 0, 0);
+    load_tile(2, W[2]);
+    for (int r = 0; r < ntiles; r += 4) {                 // tiles 0 .. 2 nsteps + 2, one spare at the end
+        const __amdgpu_buffer_rsrc_t rdst = (r == 0) ? rnull : rout;
+        tile(I0{}, r, rdst);
+        tile(I1{}, r + 1, rdst);
+        tile(I2{}, r + 2, rdst);
+        tile(I3{}, r + 3, rdst);
+    }
+}
+
+template <bool STREAM, bool DOWN>
+__global__ void __launch_bounds__(256, 2) pyr_mfma_kernel(PyrArgs p) {
     constexpr int NS = HB_PYR_NS;
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
 
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2 * NS>::kFloats];
-    PyrCoef k;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        k.dx32[i] = w5(8 * g + i - 2 * c);
-        k.dy32[i] = w5(krow32(g, i) - 2 * c);
-        k.d16[i] = (i < 4) ? w5(32 + 4 * g + i - 2 * c) : (half_t)0;
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            k.up[h][i] = (half_t)upw(c & 1, krow32(g, i) - 8 - 8 * h - (c >> 1));
-    }
+    __shared__ __attribute__((aligned(16))) char s_stash[4][PyrStash<NS>::kBytes];
 
 #ifdef HB_NO_XCD_MAP
     const int wgpos = blockIdx.x;
@@ -292,21 +460,53 @@ __global__ void __launch_bounds__(256) pyr_mfma_kernel(PyrArgs p) {
 #endif
     const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    const int ntasks = p.grid.count();
+    const int ntasks = p.count();
     for (int task = wave; task < ntasks; task += nwaves) {
-        const int seg = task / p.grid.nct, ct = task - seg * p.grid.nct;
-        const int X0 = 32 * NS * ct;                      // first output column
-        const int R0 = seg * p.steps * 32;                // first output row
-        const int nsteps = min(p.steps, (p.H - R0 + 31) / 32);
-        if (p.grid.interior(seg, ct)) {
-            pyr_task<NS, true, STREAM>(p, k, s_patch[threadIdx.x >> 6], X0, R0, nsteps, c, g);
+        if (task >= p.nborder) {
+            PyrFastCoef k;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                k.dxa[i] = w5(8 * g + i - 2 * c);
+                k.dxb[i] = w5(32 + 8 * g + i - 2 * c);
+                k.dy32[i] = w5(krow32(g, i) - 2 * c);
+                k.dy16[i] = (i < 4) ? w5(32 + 4 * g + i - 2 * c) : (half_t)0;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    k.up[h][i] = (half_t)upw(c & 1, krow32(g, i) - 7 - 8 * h - (c >> 1));
+                    k.upsw[h][i] = (half_t)upw(c & 1, krow32(g, i ^ 4) - 7 - 8 * h - (c >> 1));
+                }
+                k.sel[0][i] = (half_t)((8 * g + i == 16 + c) ? 1.f : 0.f);
+                k.sel[1][i] = (half_t)((8 * g + i == c) ? 1.f : 0.f);
+            }
+            const int id = task - p.nborder, nci = p.c1 - p.c0;
+            const int seg = id / nci, ct = p.c0 + (id - seg * nci);
+            const int rs = p.r0 + seg * p.steps;
+            pyr_fast_task<NS, STREAM, DOWN>(p, k, s_patch[threadIdx.x >> 6], s_stash[threadIdx.x >> 6],
+                                            32 * NS * ct, 32 * rs, min(p.steps, p.r1 - rs), lane);
         } else {
-#ifndef HB_PYR_NOBORDER
-            // border task: one 32-column block at a time keeps this path's register use low
+            PyrCoef k;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                k.dy32[i] = w5(krow32(g, i) - 2 * c);
+                k.d16[i] = (i < 4) ? w5(32 + 4 * g + i - 2 * c) : (half_t)0;
+            }
+            int rs, ct;                                   // one strip x one row step
+            if (task < p.ntop) {
+                rs = task / p.nct, ct = task - rs * p.nct;
+            } else if (task < p.ntop + p.nbot) {
+                const int id = task - p.ntop;
+                rs = id / p.nct, ct = id - rs * p.nct, rs += p.r1;
+            } else {
+                const int id = task - p.ntop - p.nbot, nr = p.r1 - p.r0;
+                ct = id / nr, rs = p.r0 + (id - ct * nr);
+                if (id >= p.nleft) ct += p.c1 - p.c0;
+            }
+            // one 32-column block at a time keeps this path's register use low
 #pragma unroll 1
-            for (int b = 0; b < NS; ++b)
-                if (X0 + 32 * b < p.W) pyr_task<1, false, STREAM>(p, k, s_patch[threadIdx.x >> 6], X0 + 32 * b, R0, nsteps, c, g);
-#endif
+            for (int b = 0; b < NS; ++b) {
+                const int X0 = 32 * (NS * ct + b);
+                if (X0 < p.W) pyr_task<1, STREAM>(p, k, X0, 32 * rs, 1, c, g);
+            }
         }
     }
 }
@@ -406,18 +606,32 @@ static hb_status pyr_prepare(PyrArgs& a, const hb_half* in, float* res, hb_half*
     a.in_pitch = in_pitch;
     a.res_pitch = res_pitch;
     a.down_pitch = down_pitch;
-    const int nct = ceil_div(W, 32 * HB_PYR_NS);
-    const int rowsteps = ceil_div(H, 32);
-    int steps = (int)(((int64_t)rowsteps * nct + HB_PYR_WAVES - 1) / HB_PYR_WAVES);
-    steps = steps < 1 ? 1 : steps;
-    a.steps = steps;
-    a.grid.nct = nct;
-    a.grid.nseg = ceil_div(rowsteps, steps);
-    // interior task: its pixel windows start 18 before its first output and end 30 past its
-    // last one, in both directions; then no up pass reads a clamped D index either
-    interior_range(nct, 32 * HB_PYR_NS, 18, 32 * HB_PYR_NS + 30, W, a.grid.c0, a.grid.c1);
-    interior_range(a.grid.nseg, 32 * steps, 18, 32 * steps + 30, H, a.grid.s0, a.grid.s1);
-    if (a.grid.c1 <= a.grid.c0 || a.grid.s1 <= a.grid.s0) a.grid.c0 = a.grid.c1 = a.grid.s0 = a.grid.s1 = 0;
+    constexpr int SW = 32 * HB_PYR_NS;                    // strip width
+    a.nct = ceil_div(W, SW);
+    a.rowsteps = ceil_div(H, 32);
+    // interior: pixel windows start 16 before the first output of a task and end 32 past its last
+    // one, in both directions; then no up pass reads a clamped D index either
+    a.c0 = 1;
+    a.c1 = (W - SW - 32 >= 0) ? (W - SW - 32) / SW + 1 : 0;
+    a.r0 = 1;
+    a.r1 = (H - 64 >= 0) ? (H - 64) / 32 + 1 : 0;        // last interior step e: 32 e + 32 + 32 <= H
+    if ((a.r1 - a.r0) & 1) --a.r1;                        // interior tasks take two row steps per round
+    // a task's footprint must stay below 2 GiB from its first row (32-bit buffer offsets)
+    const int64_t rowbytes = in_pitch * 2 > res_pitch * 4 ? in_pitch * 2 : res_pitch * 4;
+    const int64_t maxrows = (((int64_t)1 << 31) - 1) / rowbytes;
+    if (maxrows < 2 * 32 + 64 || a.c1 <= a.c0 || a.r1 <= a.r0) {   // no interior: everything is "top"
+        a.c0 = a.c1 = 0;
+        a.r0 = a.r1 = a.rowsteps;
+    }
+    const int nr = a.r1 - a.r0, nci = a.c1 - a.c0;
+    int steps = 2 * (int)(((int64_t)nr * nci + 2 * HB_PYR_WAVES - 1) / (2 * HB_PYR_WAVES));
+    if ((int64_t)32 * steps + 64 > maxrows) steps = (int)((maxrows - 64) / 64) * 2;
+    a.steps = steps < 2 ? 2 : steps;
+    a.nseg = nci > 0 ? ceil_div(nr, a.steps) : 0;
+    a.ntop = a.r0 * a.nct;
+    a.nbot = (a.rowsteps - a.r1) * a.nct;
+    a.nleft = a.c0 * nr;
+    a.nborder = a.ntop + a.nbot + a.nleft + (a.nct - a.c1) * nr;
     return HB_OK;
 }
 
@@ -437,11 +651,15 @@ extern "C" hb_status hb_pyr_level(const hb_half* in, float* residual, hb_half* d
     if (W < 48)   // narrower than one pixel window of the matrix formulation: vector-ALU kernel
         return hb_pyr_level_valu(in, residual, down_or_null, H, W, in_pitch, res_pitch, down_pitch, stream);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const dim3 grid(min(ceil_div(a.grid.count(), 4), kMaxStreamBlocks));
-    if ((int64_t)H * W * 4 <= kStreamStoreMaxBytes)
-        hipLaunchKernelGGL((pyr_mfma_kernel<true>), grid, dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL((pyr_mfma_kernel<false>), grid, dim3(256), 0, st, a);
+    const dim3 grid(min(ceil_div(a.count(), 4), kMaxStreamBlocks));
+    const bool stream_stores = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
+    if (a.down) {
+        if (stream_stores) hipLaunchKernelGGL((pyr_mfma_kernel<true, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((pyr_mfma_kernel<false, true>), grid, dim3(256), 0, st, a);
+    } else {
+        if (stream_stores) hipLaunchKernelGGL((pyr_mfma_kernel<true, false>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((pyr_mfma_kernel<false, false>), grid, dim3(256), 0, st, a);
+    }
     return launch_status();
 }
 

@@ -64,3 +64,26 @@ def test_pyr_benchmark_width_slab(orc, fn):
     getattr(hb, fn)(up(img), res, None)
     torch.cuda.synchronize()
     assert_close(res.cpu().numpy(), orc.pyr_level(img), fn)
+
+
+@pytest.mark.parametrize("want_down", [False, True])
+def test_pyr_full_benchmark_size_sampled_bands(orc, want_down):
+    """The benchmark's 8192 x 8192 launch (long interior tasks, many rounds of the tile ring), checked on
+    row bands: the oracle runs on a crop with 16 rows of margin, whose inner rows do not see the crop."""
+    import torch
+    from paper_2512_02371_amd import hb
+    H = W = 8192
+    img = synth.uniform01_f16(1005, (H, W))
+    res = torch.zeros((H, W), dtype=torch.float32, device="cuda:0")
+    down = torch.zeros((H // 2, W // 2), dtype=torch.float16, device="cuda:0") if want_down else None
+    print(f"hb_pyr_level {H}x{W} down={want_down}", flush=True)
+    hb.hb_pyr_level(up(img), res, down)
+    torch.cuda.synchronize()
+    for y0 in (0, 16, 480, 1008, 2040, 4096 - 32, 6000, H - 96, H - 64):
+        lo, hi = max(y0 - 16, 0), min(y0 + 64 + 16, H)
+        ref, dref = orc.pyr_level(img[lo:hi], want_down=True)
+        a, b = (0 if lo == 0 else 16), (hi - lo if hi == H else hi - lo - 16)
+        assert_close(res[lo + a:lo + b].cpu().numpy(), ref[a:b], f"residual rows {lo + a}..{lo + b}")
+        if want_down:
+            got = down[(lo + a) // 2:(lo + b) // 2].cpu().numpy().astype(np.float64)
+            assert_close(got, dref[a // 2:b // 2], f"down rows {(lo + a) // 2}..{(lo + b) // 2}")
