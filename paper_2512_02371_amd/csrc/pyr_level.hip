@@ -40,7 +40,7 @@
 #define HB_PYR_NS 2           // 32-column output blocks per wave strip
 #endif
 #ifndef HB_PYR_WAVES
-#define HB_PYR_WAVES 2048     // aim for about this many wave tasks per launch (one resident round)
+#define HB_PYR_WAVES 8192     // aim for about this many interior wave tasks per launch
 #endif
 #ifndef HB_PYR_PD
 #define HB_PYR_PD 3           // image row tiles requested ahead of the one being consumed
@@ -54,17 +54,20 @@ struct PyrArgs {
     half_t* down;      // may be null
     int H, W, Hd, Wd;
     int64_t in_pitch, res_pitch, down_pitch;
-    // Task list of one launch.  Strips are 32*NS output columns wide, row steps 32 output rows high.
-    // Border tasks come first (one strip x one row step each, the slow path): the row steps above r0
-    // and from r1 on over all strips, then the strips left of c0 and from c1 on over the row steps
-    // between.  Interior tasks follow: strips [c0, c1) x segments of `steps` row steps out of [r0, r1).
-    int nct, rowsteps;
-    int c0, c1, r0, r1;
-    int steps, nseg;   // row steps per interior task, interior segments per strip
-    int ntop, nbot, nleft, nborder;
+    // Task list of one launch (wave tasks).  Row steps are 32 output rows high.
+    // Border tasks come first, each one 32-column block wide (the general path): the row steps above
+    // r0 and from r1 on, one step per task, over all nblk blocks; then the blocks left of the interior
+    // (nbl of them) and right of it (from block bR on) over the row steps [r0, r1) in chunks of
+    // kPyrBorderSteps.  Interior tasks follow: nci strips of 32*NS columns starting at column 32*nbl,
+    // each cut into nseg segments of `steps` row steps out of [r0, r1).
+    int nblk, rowsteps;
+    int nbl, bR, nci, r0, r1;
+    int steps, nseg, nchunk;
+    int ntop, nbot, nborder;
 
-    __host__ __device__ int count() const { return nborder + (c1 - c0) * nseg; }
+    __host__ __device__ int count() const { return nborder + nci * nseg; }
 };
+constexpr int kPyrBorderSteps = 4;
 
 __device__ __forceinline__ half_t w5(int t) {
     // [1,4,6,4,1]/16, zero outside
@@ -76,22 +79,31 @@ __device__ __forceinline__ float upw(int phase, int delta) {
     if (phase) return (delta == 0 || delta == 1) ? 0.5f : 0.f;
     return (delta == 0) ? 0.75f : (delta == -1 || delta == 1) ? 0.125f : 0.f;
 }
-// Weight of D[dabs] in output xabs when the D index is clamped to [0, n-1].
+// Weight of D[dabs] in output xabs when the D index is clamped to [0, n-1]: the plain phase weight,
+// plus, on the first and last D sample, the weights of the neighbours that clamp onto it.
 __device__ __forceinline__ float upw_clamped(int dabs, int xabs, int n) {
     const int q = xabs >> 1, ph = xabs & 1;
-    float s = 0.f;
+    float s = (dabs >= 0 && dabs < n) ? upw(ph, dabs - q) : 0.f;
+    if (dabs == 0 || dabs == n - 1) {
 #pragma unroll
-    for (int delta = -1; delta <= 1; ++delta)
-        if (clampi(q + delta, 0, n - 1) == dabs) s += upw(ph, delta);
+        for (int delta = -1; delta <= 1; ++delta) {
+            const int d = q + delta;
+            if ((dabs == 0 && d < 0) || (dabs == n - 1 && d > n - 1)) s += upw(ph, delta);
+        }
+    }
     return s;
 }
 
-// Weight of pixel u in D sample n when the pixel index 2n + i (i = -2..2) is clamped to [0, len-1].
+// Sum of the taps t < j of [1,4,6,4,1]/16.
+__device__ __forceinline__ float w5_prefix(int j) {
+    return j <= 0 ? 0.f : j == 1 ? 0.0625f : j == 2 ? 0.3125f : j == 3 ? 0.6875f : j == 4 ? 0.9375f : 1.f;
+}
+// Weight of pixel u in D sample n when the pixel index 2n + t - 2 (t = 0..4) is clamped to [0, len-1]:
+// the plain tap, plus, on the first and last pixel, the taps that clamp onto it.
 __device__ __forceinline__ half_t down_tap_clamped(int n, int u, int len) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = -2; i <= 2; ++i)
-        if (clampi(2 * n + i, 0, len - 1) == u) s += (float)w5(i + 2);
+    float s = (u >= 0 && u < len) ? (float)w5(u - 2 * n + 2) : 0.f;
+    if (u == 0) s += w5_prefix(2 - 2 * n);                         // taps with 2n + t - 2 < 0
+    if (u == len - 1) s += 1.f - w5_prefix(len + 2 - 2 * n);       // taps with 2n + t - 2 > len - 1
     return (half_t)s;                                     // multiples of 1/16 up to 1: exact
 }
 
@@ -147,6 +159,12 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int
             fdx16[t][i] = (i < 4) ? down_tap_clamped(n, wsx[t] + 32 + 4 * g + i, p.W) : (half_t)0;
         }
     }
+
+    half8 fux[NS][2];                                     // up-x fragments with the D column clamp folded in
+#pragma unroll
+    for (int t = 0; t < NS; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) fux[t][h] = up_fragment_clamped(Dx0 + 16 * t, X0 + 32 * t + 16 * h, p.Wd, c, g);
 
     half8 win32[NT], nxt32[NT];
     half4 win16[NT], nxt16[NT];
@@ -204,9 +222,8 @@ __device__ __forceinline__ void pyr_task(const PyrArgs& p, const PyrCoef& k, int
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     U1[0][t][h] = U1[1][t][h];
-                    const half8 b = up_fragment_clamped(Dx0 + 16 * t, X0 + 32 * t + 16 * h, p.Wd, c, g);
                     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-                    acc = mfma16x16x32(join(D[t], D[t + 1]), b, acc);
+                    acc = mfma16x16x32(join(D[t], D[t + 1]), fux[t][h], acc);
                     U1[1][t][h] = to_half4(acc);
                 }
             if (q >= 1) {
@@ -284,11 +301,19 @@ __device__ __forceinline__ void pyr_fast_task(const PyrArgs& p, const PyrFastCoe
     const int c = lane & 15, g = lane >> 4;
     const int Dx0 = X0 / 2 - 7, M0 = R0 / 2 - 7;          // first D column / row of tile 0
 
+    // descriptors end with the image: an access past the last pixel would return zero / be dropped
+    const int64_t in_left = ((int64_t)(p.H - 1 - (R0 - 16)) * p.in_pitch + (p.W - (X0 - 16))) * 2;
+    const int64_t out_left = ((int64_t)(p.H - 1 - R0) * p.res_pitch + (p.W - X0)) * 4;
     const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<half_t*>(p.in + (int64_t)(R0 - 16) * p.in_pitch + (X0 - 16)), 0, 0x7fffffff, kBufFlags);
+        const_cast<half_t*>(p.in + (int64_t)(R0 - 16) * p.in_pitch + (X0 - 16)), 0,
+        (int)(in_left < 0x7fffffff ? in_left : 0x7fffffff), kBufFlags);
     const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
-        p.res + (int64_t)R0 * p.res_pitch + X0, 0, 0x7fffffff, kBufFlags);
+        p.res + (int64_t)R0 * p.res_pitch + X0, 0, (int)(out_left < 0x7fffffff ? out_left : 0x7fffffff), kBufFlags);
     const uint32_t ivoff = (uint32_t)c * (uint32_t)p.in_pitch * 2u + 16u * g;
+    // The last image column tile only feeds its first three pixels into a product (A_down of the last
+    // D column); all four lanes of a row read its first eight pixels, so that a strip touches no
+    // pixel beyond 24 past its last output.
+    const uint32_t ivoff_last = (uint32_t)c * (uint32_t)p.in_pitch * 2u + 64u * (NC - 1);
     const uint32_t itile = 32u * (uint32_t)p.in_pitch;    // bytes per image row tile
     const uint32_t ovoff = ((uint32_t)g * (uint32_t)p.res_pitch + 4u * c) * 4u;
     const uint32_t orow4 = 16u * (uint32_t)p.res_pitch;   // bytes per four output rows
@@ -309,8 +334,9 @@ __device__ __forceinline__ void pyr_fast_task(const PyrArgs& p, const PyrFastCoe
     auto load_tile = [&](int r, half8 (&w)[NC]) {
         const uint32_t soff = (uint32_t)min(r, ntiles - 1) * itile;   // past the end: the last tile again
 #pragma unroll
-        for (int j = 0; j < NC; ++j)
+        for (int j = 0; j < NC - 1; ++j)
             w[j] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(rin, ivoff + 64u * j, soff, 0));
+        w[NC - 1] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(rin, ivoff_last, soff, 0));
     };
     int sslot = 0;                                        // stash slot of the current tile: r % 3
     char* const mystash = stash + 16 * lane;
@@ -478,11 +504,11 @@ __global__ void __launch_bounds__(256, 2) pyr_mfma_kernel(PyrArgs p) {
                 k.sel[0][i] = (half_t)((8 * g + i == 16 + c) ? 1.f : 0.f);
                 k.sel[1][i] = (half_t)((8 * g + i == c) ? 1.f : 0.f);
             }
-            const int id = task - p.nborder, nci = p.c1 - p.c0;
-            const int seg = id / nci, ct = p.c0 + (id - seg * nci);
+            const int id = task - p.nborder;
+            const int seg = id / p.nci, ct = id - seg * p.nci;
             const int rs = p.r0 + seg * p.steps;
             pyr_fast_task<NS, STREAM, DOWN>(p, k, s_patch[threadIdx.x >> 6], s_stash[threadIdx.x >> 6],
-                                            32 * NS * ct, 32 * rs, min(p.steps, p.r1 - rs), lane);
+                                            32 * (p.nbl + NS * ct), 32 * rs, min(p.steps, p.r1 - rs), lane);
         } else {
             PyrCoef k;
 #pragma unroll
@@ -490,23 +516,20 @@ __global__ void __launch_bounds__(256, 2) pyr_mfma_kernel(PyrArgs p) {
                 k.dy32[i] = w5(krow32(g, i) - 2 * c);
                 k.d16[i] = (i < 4) ? w5(32 + 4 * g + i - 2 * c) : (half_t)0;
             }
-            int rs, ct;                                   // one strip x one row step
+            int rs, blk, nst = 1;                         // one 32-column block, nst row steps
             if (task < p.ntop) {
-                rs = task / p.nct, ct = task - rs * p.nct;
+                rs = task / p.nblk, blk = task - rs * p.nblk;
             } else if (task < p.ntop + p.nbot) {
                 const int id = task - p.ntop;
-                rs = id / p.nct, ct = id - rs * p.nct, rs += p.r1;
+                rs = id / p.nblk, blk = id - rs * p.nblk, rs += p.r1;
             } else {
-                const int id = task - p.ntop - p.nbot, nr = p.r1 - p.r0;
-                ct = id / nr, rs = p.r0 + (id - ct * nr);
-                if (id >= p.nleft) ct += p.c1 - p.c0;
+                const int id = task - p.ntop - p.nbot;
+                const int bi = id / p.nchunk, ch = id - bi * p.nchunk;
+                blk = bi < p.nbl ? bi : p.bR + (bi - p.nbl);
+                rs = p.r0 + kPyrBorderSteps * ch;
+                nst = min(kPyrBorderSteps, p.r1 - rs);
             }
-            // one 32-column block at a time keeps this path's register use low
-#pragma unroll 1
-            for (int b = 0; b < NS; ++b) {
-                const int X0 = 32 * (NS * ct + b);
-                if (X0 < p.W) pyr_task<1, STREAM>(p, k, X0, 32 * rs, 1, c, g);
-            }
+            pyr_task<1, STREAM>(p, k, 32 * blk, 32 * rs, nst, c, g);
         }
     }
 }
@@ -606,32 +629,35 @@ static hb_status pyr_prepare(PyrArgs& a, const hb_half* in, float* res, hb_half*
     a.in_pitch = in_pitch;
     a.res_pitch = res_pitch;
     a.down_pitch = down_pitch;
-    constexpr int SW = 32 * HB_PYR_NS;                    // strip width
-    a.nct = ceil_div(W, SW);
+    constexpr int SW = 32 * HB_PYR_NS;                    // interior strip width
+    a.nblk = ceil_div(W, 32);
     a.rowsteps = ceil_div(H, 32);
-    // interior: pixel windows start 16 before the first output of a task and end 32 past its last
-    // one, in both directions; then no up pass reads a clamped D index either
-    a.c0 = 1;
-    a.c1 = (W - SW - 32 >= 0) ? (W - SW - 32) / SW + 1 : 0;
+    // interior: a task reads pixels from 16 before its first output to 32 past its last one (24 along
+    // x), in both directions; then no up pass reads a clamped D index either.  One border block on
+    // the left; on the right whatever the strips leave.
+    a.nbl = 1;
+    a.nci = (W - 32 - 32 >= SW) ? (W - 32 - 32) / SW : 0;
+    a.bR = a.nbl + HB_PYR_NS * a.nci;
     a.r0 = 1;
     a.r1 = (H - 64 >= 0) ? (H - 64) / 32 + 1 : 0;        // last interior step e: 32 e + 32 + 32 <= H
     if ((a.r1 - a.r0) & 1) --a.r1;                        // interior tasks take two row steps per round
     // a task's footprint must stay below 2 GiB from its first row (32-bit buffer offsets)
     const int64_t rowbytes = in_pitch * 2 > res_pitch * 4 ? in_pitch * 2 : res_pitch * 4;
     const int64_t maxrows = (((int64_t)1 << 31) - 1) / rowbytes;
-    if (maxrows < 2 * 32 + 64 || a.c1 <= a.c0 || a.r1 <= a.r0) {   // no interior: everything is "top"
-        a.c0 = a.c1 = 0;
+    if (maxrows < 2 * 32 + 64 || a.nci <= 0 || a.r1 <= a.r0) {     // no interior: everything is "top"
+        a.nci = 0;
+        a.nbl = a.bR = a.nblk;
         a.r0 = a.r1 = a.rowsteps;
     }
-    const int nr = a.r1 - a.r0, nci = a.c1 - a.c0;
-    int steps = 2 * (int)(((int64_t)nr * nci + 2 * HB_PYR_WAVES - 1) / (2 * HB_PYR_WAVES));
+    const int nr = a.r1 - a.r0;
+    int steps = 2 * (int)(((int64_t)nr * a.nci + 2 * HB_PYR_WAVES - 1) / (2 * HB_PYR_WAVES));
     if ((int64_t)32 * steps + 64 > maxrows) steps = (int)((maxrows - 64) / 64) * 2;
     a.steps = steps < 2 ? 2 : steps;
-    a.nseg = nci > 0 ? ceil_div(nr, a.steps) : 0;
-    a.ntop = a.r0 * a.nct;
-    a.nbot = (a.rowsteps - a.r1) * a.nct;
-    a.nleft = a.c0 * nr;
-    a.nborder = a.ntop + a.nbot + a.nleft + (a.nct - a.c1) * nr;
+    a.nseg = a.nci > 0 ? ceil_div(nr, a.steps) : 0;
+    a.nchunk = ceil_div(nr, kPyrBorderSteps);
+    a.ntop = a.r0 * a.nblk;
+    a.nbot = (a.rowsteps - a.r1) * a.nblk;
+    a.nborder = a.ntop + a.nbot + (nr > 0 ? (a.nbl + a.nblk - a.bR) * a.nchunk : 0);
     return HB_OK;
 }
 
