@@ -40,7 +40,7 @@
 #define HB_PYR_NS 2           // 32-column output blocks per wave strip
 #endif
 #ifndef HB_PYR_WAVES
-#define HB_PYR_WAVES 8192     // aim for about this many interior wave tasks per launch
+#define HB_PYR_WAVES 5400     // aim for about this many interior wave tasks per launch
 #endif
 #ifndef HB_PYR_PD
 #define HB_PYR_PD 3           // image row tiles requested ahead of the one being consumed
