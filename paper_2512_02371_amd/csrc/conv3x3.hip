@@ -44,12 +44,17 @@ __device__ __forceinline__ int cv_lds_index(int r, int kc, int half, int px) {
     return (((r * 4 + kc) * 2 + half) * kCvPx + px) * 8;
 }
 
-// 16-byte pieces of one staged tile, spread over the 512 threads in two batches so that a wave
-// has the next tile's pixels in flight while it multiplies the current one.
+// A staged tile is 2720 16-byte pieces.  It is filled by buffer loads that write LDS directly
+// (64 lanes x 16 bytes = 1 KB of consecutive LDS per instruction, any global address per lane):
+// no register holds a pixel on its way in.  Every wave issues kCvDma such loads per tile, so a
+// buffer is padded to 8 * kCvDma KB; pieces of the padding and pixels outside the image are
+// requested beyond the end of the buffer descriptor, which makes the hardware deliver zeros: that
+// is the zero padding of the convolution.
 constexpr int kCvThreads = 512;
 constexpr int kCvPieces = kCvRows * kCvPx * 8;                               // 2720
-constexpr int kCvIters = (kCvPieces + kCvThreads - 1) / kCvThreads;          // 6
-constexpr int kCvBatchA = 3, kCvBatchB = kCvIters - kCvBatchA;               // 3 + 3
+constexpr int kCvDma = (kCvPieces + kCvThreads - 1) / kCvThreads;            // 6 per wave and tile
+constexpr int kCvBufHalves = kCvDma * kCvThreads * 8;                        // 24576 halves = 48 KB
+constexpr uint32_t kCvOutside = 0x80000000u;              // offset beyond any descriptor used here
 
 struct CvTile {
     int n, y0, x0;
@@ -63,58 +68,58 @@ __device__ __forceinline__ CvTile cv_tile(const ConvArgs& p, int tile) {
     t.x0 = (rem - ty * p.tiles_x) * kCvTX;
     return t;
 }
-// piece idx of a tile = (staged row r, staged pixel px, 8-channel piece)
-__device__ __forceinline__ void cv_piece(int idx, int& r, int& px, int& piece) {
-    idx = min(idx, kCvPieces - 1);                        // the tail repeats the last piece (same data)
-    piece = idx & 7;
-    const int pr = idx >> 3;
-    r = pr / kCvPx;
-    px = pr - r * kCvPx;
-}
-// border tiles: pixels (y0-1+r, x0-1+px), zeros outside the image
-__device__ __forceinline__ half8 cv_fetch(const ConvArgs& p, const CvTile& t, int idx) {
-    int r, px, piece;
-    cv_piece(idx, r, px, piece);
-    half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int y = t.y0 - 1 + r, x = t.x0 - 1 + px;
-    if (y >= 0 && y < p.H && x >= 0 && x < p.W)
-        v = *reinterpret_cast<const half8*>(p.in + (((int64_t)t.n * p.H + y) * p.W + x) * kCvC + 8 * piece);
-    return v;
-}
-// interior tiles: byte offset of the piece from the tile's first staged pixel (the same for every tile)
-__device__ __forceinline__ uint32_t cv_goff(const ConvArgs& p, int idx) {
-    int r, px, piece;
-    cv_piece(idx, r, px, piece);
-    return (uint32_t)(((r * p.W + px) * kCvC + 8 * piece) * 2);
-}
-__device__ __forceinline__ void cv_put(half_t* buf, int idx, half8 v) {
-    int r, px, piece;
-    cv_piece(idx, r, px, piece);
-    *reinterpret_cast<half8*>(&buf[cv_lds_index(r, piece >> 1, piece & 1, px)]) = v;
-}
 // whole staged tile inside the image?
 __device__ __forceinline__ bool cv_interior(const ConvArgs& p, const CvTile& t) {
     return t.y0 >= 1 && t.y0 + kCvTY + 1 <= p.H && t.x0 >= 1 && t.x0 + kCvTX + 1 <= p.W;
 }
-__device__ __forceinline__ const half_t* cv_origin(const ConvArgs& p, const CvTile& t) {
-    return p.in + (((int64_t)t.n * p.H + (t.y0 - 1)) * p.W + (t.x0 - 1)) * kCvC;
+
+// Per-lane constants of the kCvDma loads of a wave: piece (r, px, channel piece) -> byte offset from
+// the tile's first staged pixel (y0-1, x0-1), and (r, px) for the border test.
+struct CvDma {
+    uint32_t off[kCvDma];
+    int rpx[kCvDma];          // r | px << 8, or -1 for a piece of the padding
+};
+
+// Requests the staged tile of `t` into `buf` (this wave's share).
+__device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, const CvDma& d, half_t* buf, int wv) {
+    // the descriptor starts at the (possibly virtual) pixel (y0-1, x0-1); lanes outside the image never
+    // reach memory
+    const half_t* org = p.in + (((int64_t)t.n * p.H + (t.y0 - 1)) * p.W + (t.x0 - 1)) * kCvC;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(org), 0, 0x7fffffff, 0x00020000);
+    const bool inside = cv_interior(p, t);                // uniform
+#pragma unroll
+    for (int i = 0; i < kCvDma; ++i) {
+        uint32_t off = d.off[i];
+        if (d.rpx[i] < 0) {
+            off = kCvOutside;
+        } else if (!inside) {
+            const int y = t.y0 - 1 + (d.rpx[i] & 0xff), x = t.x0 - 1 + (d.rpx[i] >> 8);
+            if (y < 0 || y >= p.H || x < 0 || x >= p.W) off = kCvOutside;
+        }
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(buf + 512 * (wv + 8 * i)),
+                                                 16, off, 0, 0, 0);
+    }
 }
 
-// Two output rows (2 x 32 pixels) x 32 channels from the staged tile: K-steps S0 .. S1-1 of 36, two
-// products each.
-template <int S0, int S1>
+// Two output rows (2 x 32 pixels) x 32 channels from the staged tile.  The four staged rows under
+// the two output rows are read once per (channel chunk, horizontal tap) and serve both rows:
+// 48 reads for 72 products.
 __device__ __forceinline__ void cv_rows(const half_t* buf, const half8 (&wf)[36], int ro, int c32, int h,
                                         floatx16 (&acc)[2]) {
     const half_t* base = buf + cv_lds_index(ro, 0, h, c32);
 #pragma unroll
-    for (int s = S0; s < S1; ++s) {
-        const int tap = s >> 2, kc = s & 3, ky = tap / 3, kx = tap - 3 * ky;
-        const half_t* q = base + cv_lds_index(ky, kc, 0, kx);
-        const half8 b0 = *reinterpret_cast<const half8*>(q);
-        const half8 b1 = *reinterpret_cast<const half8*>(q + cv_lds_index(1, 0, 0, 0));   // next tile row
-        acc[0] = mfma32x32x16(wf[s], b0, acc[0]);
-        acc[1] = mfma32x32x16(wf[s], b1, acc[1]);
-    }
+    for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) {
+            half8 b[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) b[rr] = *reinterpret_cast<const half8*>(base + cv_lds_index(rr, kc, 0, kx));
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                if (rr <= 2) acc[0] = mfma32x32x16(wf[(3 * rr + kx) * 4 + kc], b[rr], acc[0]);
+                if (rr >= 1) acc[1] = mfma32x32x16(wf[(3 * (rr - 1) + kx) * 4 + kc], b[rr], acc[1]);
+            }
+        }
 }
 
 __device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t, int ro, int j, int c32, int h,
@@ -132,10 +137,31 @@ __device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t,
     }
 }
 
+// One tile: request the next tile into the other buffer, multiply this one, meet, store.
+// `cur` and `nxt` are distinct LDS arrays at every call site, so the reads of `cur` need not wait
+// for the loads into `nxt`; those are awaited at the barrier.
+__device__ __forceinline__ void cv_step(const ConvArgs& p, const CvDma& d, const half8 (&wf)[36],
+                                        const half_t* cur, half_t* nxt, int tile, int stride,
+                                        int wv, int ro, int j, int c32, int h) {
+    const CvTile t = cv_tile(p, tile);
+    if (tile + stride < p.ntiles) cv_request(p, cv_tile(p, tile + stride), d, nxt, wv);   // uniform
+    __builtin_amdgcn_sched_barrier(0);                    // the requests go out before the first product
+    floatx16 acc[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
+    cv_rows(cur, wf, ro, c32, h, acc);
+    __syncthreads();                                      // next buffer complete, this one released
+    cv_store_row(p, t, ro, j, c32, h, acc[0]);            // in flight during the next tile's products
+    cv_store_row(p, t, ro + 1, j, c32, h, acc[1]);
+}
+
 __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
-    extern __shared__ __attribute__((aligned(16))) half_t s_dyn[];   // two tile buffers
+    __shared__ __attribute__((aligned(16))) half_t s_a[kCvBufHalves];
+    __shared__ __attribute__((aligned(16))) half_t s_b[kCvBufHalves];
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wv = tid >> 6;
+    const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, h = lane >> 5;
     const int j = wv >> 2;                                // channel tile of this wave
     const int ro = 2 * (wv & 3);                          // its two output rows inside the tile
@@ -144,73 +170,45 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     if (tile >= p.ntiles) return;
 
     // coefficient fragments: wf[s] lane (c32, h) = w[tap][16 kc + 8h + i][32 j + c32], s = 4 tap + kc.
-    // The 72 KB of weights pass through LDS once (coalesced 16-byte copies in, 2-byte gathers out:
-    // lanes of a half-wave read 32 consecutive halves, no bank conflict).
+    // The 72 KB of weights pass through LDS once, taps 0..4 through one buffer and 5..8 through the
+    // other (coalesced 16-byte copies in, 2-byte gathers out: lanes of a half-wave read 32
+    // consecutive halves, no bank conflict).
     half8 wf[36];
-    for (int i = tid; i < 9 * kCvC * kCvC / 8; i += kCvThreads)
-        reinterpret_cast<half8*>(s_dyn)[i] = reinterpret_cast<const half8*>(p.w)[i];
+    constexpr int kTapHalves = kCvC * kCvC;
+    for (int i = tid; i < 5 * kTapHalves / 8; i += kCvThreads)
+        reinterpret_cast<half8*>(s_a)[i] = reinterpret_cast<const half8*>(p.w)[i];
+    for (int i = tid; i < 4 * kTapHalves / 8; i += kCvThreads)
+        reinterpret_cast<half8*>(s_b)[i] = reinterpret_cast<const half8*>(p.w + 5 * kTapHalves)[i];
     __syncthreads();
 #pragma unroll
-    for (int s = 0; s < 36; ++s)
+    for (int s = 0; s < 36; ++s) {
+        const int tap = s >> 2;
+        const half_t* src = tap < 5 ? s_a + tap * kTapHalves : s_b + (tap - 5) * kTapHalves;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            wf[s][i] = s_dyn[((s >> 2) * kCvC + 16 * (s & 3) + 8 * h + i) * kCvC + 32 * j + c32];
-    __syncthreads();
-
-    {
-        const CvTile t = cv_tile(p, tile);
-        for (int it = 0; it < kCvIters; ++it)
-            cv_put(s_dyn, tid + kCvThreads * it, cv_fetch(p, t, tid + kCvThreads * it));
+        for (int i = 0; i < 8; ++i) wf[s][i] = src[(16 * (s & 3) + 8 * h + i) * kCvC + 32 * j + c32];
     }
     __syncthreads();
 
-    int cur = 0;
-    for (; tile < p.ntiles; tile += gridDim.x) {
-        const CvTile t = cv_tile(p, tile);
-        const int next = tile + gridDim.x;
-        const bool more = next < p.ntiles;                // uniform
-        CvTile tn = t;
-        if (more) tn = cv_tile(p, next);
-        const half_t* buf = s_dyn + cur * kCvLdsHalves;
-        half_t* nbuf = s_dyn + (cur ^ 1) * kCvLdsHalves;
+    CvDma d;
+#pragma unroll
+    for (int i = 0; i < kCvDma; ++i) {
+        const int piece = 64 * (wv + 8 * i) + lane;       // 16-byte piece of the buffer
+        const int run = piece / kCvPx, px = piece - run * kCvPx;
+        const int r = run >> 3, cp = run & 7;             // staged row, channel piece (2 kc + half)
+        d.off[i] = (uint32_t)(((r * p.W + px) * kCvC + 8 * cp) * 2);
+        d.rpx[i] = piece < kCvPieces ? (r | (px << 8)) : -1;
+    }
 
-        half8 g[kCvBatchA];
-        floatx16 acc[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
-        const bool fast = more && cv_interior(p, tn);     // uniform
-        const half_t* org = cv_origin(p, tn);
-        if (fast) {
-#pragma unroll
-            for (int it = 0; it < kCvBatchA; ++it) g[it] = ldg8(org, cv_goff(p, tid + kCvThreads * it));
-        } else if (more) {
-#pragma unroll
-            for (int it = 0; it < kCvBatchA; ++it) g[it] = cv_fetch(p, tn, tid + kCvThreads * it);
-        }
-        cv_rows<0, 18>(buf, wf, ro, c32, h, acc);
-        if (more) {
-#pragma unroll
-            for (int it = 0; it < kCvBatchA; ++it) cv_put(nbuf, tid + kCvThreads * it, g[it]);
-        }
-        if (fast) {
-#pragma unroll
-            for (int it = 0; it < kCvBatchB; ++it)
-                g[it] = ldg8(org, cv_goff(p, tid + kCvThreads * (kCvBatchA + it)));
-        } else if (more) {
-#pragma unroll
-            for (int it = 0; it < kCvBatchB; ++it) g[it] = cv_fetch(p, tn, tid + kCvThreads * (kCvBatchA + it));
-        }
-        cv_rows<18, 36>(buf, wf, ro, c32, h, acc);
-        if (more) {                                       // before the output stores: waits on the fetches only
-#pragma unroll
-            for (int it = 0; it < kCvBatchB; ++it) cv_put(nbuf, tid + kCvThreads * (kCvBatchA + it), g[it]);
-        }
-        cv_store_row(p, t, ro, j, c32, h, acc[0]);
-        cv_store_row(p, t, ro + 1, j, c32, h, acc[1]);
-        __syncthreads();                                  // next buffer complete, current one released
-        cur ^= 1;
+    cv_request(p, cv_tile(p, tile), d, s_a, wv);
+    __syncthreads();
+    const int stride = gridDim.x;
+    while (true) {
+        cv_step(p, d, wf, s_a, s_b, tile, stride, wv, ro, j, c32, h);
+        tile += stride;
+        if (tile >= p.ntiles) break;
+        cv_step(p, d, wf, s_b, s_a, tile, stride, wv, ro, j, c32, h);
+        tile += stride;
+        if (tile >= p.ntiles) break;
     }
 }
 
@@ -278,6 +276,7 @@ static hb_status conv_prepare(ConvArgs& a, const hb_half* in, const hb_half* w, 
     if (Cin != kCvC || Cout != kCvC) return HB_ERR_UNSUPPORTED;
     const int64_t tiles = (int64_t)N * ceil_div(H, kCvTY) * ceil_div(W, kCvTX);
     if (tiles > 0x7fffffff || (int64_t)N * H * W > ((int64_t)1 << 40)) return HB_ERR_UNSUPPORTED;
+    if ((int64_t)W * kCvRows * kCvC * 2 >= ((int64_t)1 << 30)) return HB_ERR_UNSUPPORTED;   // 32-bit tile offsets
     a.in = reinterpret_cast<const half_t*>(in);
     a.w = reinterpret_cast<const half_t*>(w);
     a.out = reinterpret_cast<half_t*>(out);
@@ -299,11 +298,7 @@ extern "C" hb_status hb_conv3x3(const hb_half* in_nhwc, const hb_half* w_hwio, h
     hb_status s = conv_prepare(a, in_nhwc, w_hwio, out_nhwc, N, H, W, Cin, Cout);
     if (s != HB_OK) return s;
     const int blocks = min(a.ntiles, kNumCU);
-    const size_t lds = 2 * kCvLdsHalves * sizeof(half_t);      // 85 KB of the 160 KB per compute unit
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_mfma_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return HB_ERR_HIP;
-    hipLaunchKernelGGL(conv3x3_mfma_kernel, dim3(blocks), dim3(kCvThreads), lds,
+    hipLaunchKernelGGL(conv3x3_mfma_kernel, dim3(blocks), dim3(kCvThreads), 0,
                        reinterpret_cast<hipStream_t>(stream), a);
     return launch_status();
 }
