@@ -53,7 +53,7 @@ __device__ __forceinline__ int cv_lds_index(int r, int kc, int half, int px) {
 constexpr int kCvThreads = 512;
 constexpr int kCvPieces = kCvRows * kCvPx * 8;                               // 2720
 constexpr int kCvDma = (kCvPieces + kCvThreads - 1) / kCvThreads;            // 6 per wave and tile
-constexpr int kCvBufHalves = kCvDma * kCvThreads * 8;                        // 24576 halves = 48 KB
+constexpr int kCvBufHalves = kCvDma * kCvThreads * 8;                        // 24576 halves = 48 KB, three of them
 constexpr uint32_t kCvOutside = 0x80000000u;              // offset beyond any descriptor used here
 
 struct CvTile {
@@ -80,13 +80,27 @@ struct CvDma {
     int rpx[kCvDma];          // r | px << 8, or -1 for a piece of the padding
 };
 
-// Requests the staged tile of `t` into `buf` (this wave's share).
+// One LDS-direct load: 64 lanes x 16 bytes from base + voff (per lane) to 1 KB of LDS at lds_addr
+// (wave-uniform).  Written as assembly so that the compiler keeps no book on it: it would make
+// LDS reads of the other tile buffers wait for these loads, which are meant to stay in flight
+// for two tiles.  The waits that order them are explicit in cv_step.
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void cv_dma16(u32x4s rsrc, uint32_t lds_addr, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ uint32_t cv_lds_addr(const half_t* p) {
+    return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// Requests the staged tile of `t` into `buf` (this wave's share): kCvDma loads, always.
 __device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, const CvDma& d, half_t* buf, int wv) {
     // the descriptor starts at the (possibly virtual) pixel (y0-1, x0-1); lanes outside the image never
     // reach memory
-    const half_t* org = p.in + (((int64_t)t.n * p.H + (t.y0 - 1)) * p.W + (t.x0 - 1)) * kCvC;
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(org), 0, 0x7fffffff, 0x00020000);
+    const uint64_t org = (uint64_t)(p.in + (((int64_t)t.n * p.H + (t.y0 - 1)) * p.W + (t.x0 - 1)) * kCvC);
+    const u32x4s rs = {(uint32_t)org, (uint32_t)(org >> 32) & 0xffffu, 0x7fffffffu, 0x00020000u};
     const bool inside = cv_interior(p, t);                // uniform
+    const uint32_t lds0 = cv_lds_addr(buf) + 1024u * wv;
 #pragma unroll
     for (int i = 0; i < kCvDma; ++i) {
         uint32_t off = d.off[i];
@@ -96,30 +110,48 @@ __device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, c
             const int y = t.y0 - 1 + (d.rpx[i] & 0xff), x = t.x0 - 1 + (d.rpx[i] >> 8);
             if (y < 0 || y >= p.H || x < 0 || x >= p.W) off = kCvOutside;
         }
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(buf + 512 * (wv + 8 * i)),
-                                                 16, off, 0, 0, 0);
+        cv_dma16(rs, lds0 + 8192u * i, off);
     }
 }
 
 // Two output rows (2 x 32 pixels) x 32 channels from the staged tile.  The four staged rows under
 // the two output rows are read once per (channel chunk, horizontal tap) and serve both rows:
-// 48 reads for 72 products.
+// 48 reads for 72 products, in 12 groups of 4 reads + 6 products.  The reads of a group are issued
+// kCvAhead groups before its products (the scheduling barriers pin that order), so that an LDS
+// read has the time of 6 * kCvAhead products to return.
+#ifndef HB_CONV_AHEAD
+#define HB_CONV_AHEAD 1
+#endif
+constexpr int kCvAhead = HB_CONV_AHEAD;
 __device__ __forceinline__ void cv_rows(const half_t* buf, const half8 (&wf)[36], int ro, int c32, int h,
                                         floatx16 (&acc)[2]) {
     const half_t* base = buf + cv_lds_index(ro, 0, h, c32);
+    half8 b[kCvAhead + 1][4];
+    auto read_group = [&](int grp, half8 (&dst)[4]) {
+        const int kc = grp / 3, kx = grp - 3 * kc;
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc)
+        for (int rr = 0; rr < 4; ++rr) dst[rr] = *reinterpret_cast<const half8*>(base + cv_lds_index(rr, kc, 0, kx));
+    };
 #pragma unroll
-        for (int kx = 0; kx < 3; ++kx) {
-            half8 b[4];
+    for (int g0 = 0; g0 < kCvAhead; ++g0) {
+        read_group(g0, b[g0]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    }
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) b[rr] = *reinterpret_cast<const half8*>(base + cv_lds_index(rr, kc, 0, kx));
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                if (rr <= 2) acc[0] = mfma32x32x16(wf[(3 * rr + kx) * 4 + kc], b[rr], acc[0]);
-                if (rr >= 1) acc[1] = mfma32x32x16(wf[(3 * (rr - 1) + kx) * 4 + kc], b[rr], acc[1]);
-            }
+    for (int grp = 0; grp < 12; ++grp) {
+        const int kc = grp / 3, kx = grp - 3 * kc;
+        if (grp + kCvAhead < 12) {
+            read_group(grp + kCvAhead, b[(grp + kCvAhead) % (kCvAhead + 1)]);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
         }
+        const half8 (&bb)[4] = b[grp % (kCvAhead + 1)];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            if (rr <= 2) acc[0] = mfma32x32x16(wf[(3 * rr + kx) * 4 + kc], bb[rr], acc[0]);
+            if (rr >= 1) acc[1] = mfma32x32x16(wf[(3 * (rr - 1) + kx) * 4 + kc], bb[rr], acc[1]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+    }
 }
 
 __device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t, int ro, int j, int c32, int h,
@@ -137,14 +169,17 @@ __device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t,
     }
 }
 
-// One tile: request the next tile into the other buffer, multiply this one, meet, store.
-// `cur` and `nxt` are distinct LDS arrays at every call site, so the reads of `cur` need not wait
-// for the loads into `nxt`; those are awaited at the barrier.
+// One tile: request the tile after the next into the third buffer, multiply this one, meet, store.
+// The three buffers are distinct LDS arrays at every call site, so the reads of `cur` do not wait for
+// loads into another buffer.  A request has two tile times to land: at the meeting point a wave waits
+// for all its memory instructions but the kCvDma newest (the request just made; loads and stores
+// retire in order), i.e. for its share of the NEXT tile and for the previous tile's stores.
 __device__ __forceinline__ void cv_step(const ConvArgs& p, const CvDma& d, const half8 (&wf)[36],
-                                        const half_t* cur, half_t* nxt, int tile, int stride,
+                                        const half_t* cur, half_t* far, int tile, int stride,
                                         int wv, int ro, int j, int c32, int h) {
     const CvTile t = cv_tile(p, tile);
-    if (tile + stride < p.ntiles) cv_request(p, cv_tile(p, tile + stride), d, nxt, wv);   // uniform
+    const bool req = tile + 2 * stride < p.ntiles;        // uniform
+    if (req) cv_request(p, cv_tile(p, tile + 2 * stride), d, far, wv);
     __builtin_amdgcn_sched_barrier(0);                    // the requests go out before the first product
     floatx16 acc[2];
 #pragma unroll
@@ -152,7 +187,14 @@ __device__ __forceinline__ void cv_step(const ConvArgs& p, const CvDma& d, const
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
     cv_rows(cur, wf, ro, c32, h, acc);
-    __syncthreads();                                      // next buffer complete, this one released
+    __builtin_amdgcn_sched_barrier(0);
+    static_assert(kCvDma == 6, "the counted wait below is written for six loads per request");
+    if (req) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // The barrier instruction is written out: the compiler would put a wait for ALL memory
+    // instructions in front of one it emits itself, and the newest request must stay in flight.
+    // This wave's LDS reads have been consumed by its products by now (lgkmcnt(0) states it).
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next buffer complete, this one released
     cv_store_row(p, t, ro, j, c32, h, acc[0]);            // in flight during the next tile's products
     cv_store_row(p, t, ro + 1, j, c32, h, acc[1]);
 }
@@ -160,6 +202,7 @@ __device__ __forceinline__ void cv_step(const ConvArgs& p, const CvDma& d, const
 __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     __shared__ __attribute__((aligned(16))) half_t s_a[kCvBufHalves];
     __shared__ __attribute__((aligned(16))) half_t s_b[kCvBufHalves];
+    __shared__ __attribute__((aligned(16))) half_t s_c[kCvBufHalves];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, h = lane >> 5;
@@ -170,8 +213,8 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     if (tile >= p.ntiles) return;
 
     // coefficient fragments: wf[s] lane (c32, h) = w[tap][16 kc + 8h + i][32 j + c32], s = 4 tap + kc.
-    // The 72 KB of weights pass through LDS once, taps 0..4 through one buffer and 5..8 through the
-    // other (coalesced 16-byte copies in, 2-byte gathers out: lanes of a half-wave read 32
+    // The 72 KB of weights pass through LDS once, taps 0..4 through one buffer and 5..8 through
+    // another (coalesced 16-byte copies in, 2-byte gathers out: lanes of a half-wave read 32
     // consecutive halves, no bank conflict).
     half8 wf[36];
     constexpr int kTapHalves = kCvC * kCvC;
@@ -199,16 +242,18 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
         d.rpx[i] = piece < kCvPieces ? (r | (px << 8)) : -1;
     }
 
-    cv_request(p, cv_tile(p, tile), d, s_a, wv);
-    __syncthreads();
     const int stride = gridDim.x;
+    cv_request(p, cv_tile(p, tile), d, s_a, wv);
+    if (tile + stride < p.ntiles) cv_request(p, cv_tile(p, tile + stride), d, s_b, wv);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     while (true) {
-        cv_step(p, d, wf, s_a, s_b, tile, stride, wv, ro, j, c32, h);
-        tile += stride;
-        if (tile >= p.ntiles) break;
+        cv_step(p, d, wf, s_a, s_c, tile, stride, wv, ro, j, c32, h);
+        if ((tile += stride) >= p.ntiles) break;
         cv_step(p, d, wf, s_b, s_a, tile, stride, wv, ro, j, c32, h);
-        tile += stride;
-        if (tile >= p.ntiles) break;
+        if ((tile += stride) >= p.ntiles) break;
+        cv_step(p, d, wf, s_c, s_b, tile, stride, wv, ro, j, c32, h);
+        if ((tile += stride) >= p.ntiles) break;
     }
 }
 
