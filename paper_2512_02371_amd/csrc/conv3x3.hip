@@ -7,12 +7,13 @@
 // with v_mfma_f32_32x32x16_f16: 32 channels x 32 pixels per product, K = 16 input channels.
 //   A (coefficients): the 9 x 64 x 32 weights of one 32-channel tile live in the registers of a
 //     wave for the whole kernel (36 K-steps x 8 halves per lane = 144 registers), gathered once.
-//   B (pixels): a workgroup stages an (8+2) x (32+2) pixel tile of all 64 input channels in LDS,
-//     laid out [row][16-channel chunk][8-channel half][pixel][8 channels], so that the pixels of
-//     one K-step are two runs of 512 contiguous bytes for every tap shift (the overlapped view of
-//     Eq. 1: the three horizontal taps read the same LDS row at pixel offsets 0, 1, 2) and every
-//     16-byte lane read is bank-conflict free.  Pixels outside the image are written as zeros,
-//     which is the zero padding.
+//   B (pixels): a workgroup stages an (8+2) x (32+2) pixel tile of all 64 input channels in LDS in
+//     the image's own order (pixel-major, 128 bytes per pixel), with the eight 16-byte channel
+//     pieces of a pixel permuted by an XOR with bits 1..3 of the pixel index: a tile row then
+//     arrives as contiguous 1 KB copies, and the 16-byte reads of 16 consecutive pixels at one
+//     channel piece still fall into 64 different banks for every tap shift (the overlapped view of
+//     Eq. 1: the three horizontal taps read the same LDS row at pixel offsets 0, 1, 2).  Pixels
+//     outside the image arrive as zeros, which is the zero padding.
 //   A workgroup has 8 waves, two per SIMD, so that one wave's LDS reads hide behind the other's
 //   products: wave (q, j) owns output rows 2q, 2q+1 of the tile and channel tile j, i.e. 2 x 36
 //   products per tile.  fp32 accumulators are rounded to fp16 (RNE) and leave as 8-byte stores of 4
@@ -38,22 +39,29 @@ struct ConvArgs {
     int ntiles;                // N * tiles_y * tiles_x
 };
 
-// LDS layout [row][16-channel chunk][8-channel half][pixel][8 channels]: the lanes of one half-wave
-// (same half, consecutive pixels) read 512 contiguous bytes for any tap shift.
+// LDS layout of the vector-ALU twin: [row][16-channel chunk][8-channel half][pixel][8 channels].
 __device__ __forceinline__ int cv_lds_index(int r, int kc, int half, int px) {
     return (((r * 4 + kc) * 2 + half) * kCvPx + px) * 8;
 }
 
-// A staged tile is 2720 16-byte pieces.  It is filled by buffer loads that write LDS directly
-// (64 lanes x 16 bytes = 1 KB of consecutive LDS per instruction, any global address per lane):
-// no register holds a pixel on its way in.  Every wave issues kCvDma such loads per tile, so a
-// buffer is padded to 8 * kCvDma KB; pieces of the padding and pixels outside the image are
-// requested beyond the end of the buffer descriptor, which makes the hardware deliver zeros: that
-// is the zero padding of the convolution.
+// LDS layout of the MFMA kernel, in 16-byte slots: pixel-major, channel piece cp of pixel px in slot
+// cp ^ ((px >> 1) & 7) of the pixel's eight.
+constexpr int kCvRowSlots = kCvPx * 8;                    // 272 slots = 4352 bytes per staged row
+__device__ __forceinline__ int cv_slot(int r, int px, int cp) {
+    return (r * kCvPx + px) * 8 + (cp ^ ((px >> 1) & 7));
+}
+
+// A staged tile is 2720 slots.  It is filled by buffer loads that write LDS directly (64 lanes x
+// 16 bytes = 1 KB of consecutive LDS per instruction = 8 whole pixels, whose 128 bytes are
+// contiguous in memory): no register holds a pixel on its way in.  43 such loads make a tile; wave
+// w issues those numbered w, w + 8, ...: six for waves 0..2, five for the others.  Slots past the
+// tile and pixels outside the image are requested beyond the end of the buffer descriptor, which
+// makes the hardware deliver zeros: that is the zero padding of the convolution.
 constexpr int kCvThreads = 512;
-constexpr int kCvPieces = kCvRows * kCvPx * 8;                               // 2720
-constexpr int kCvDma = (kCvPieces + kCvThreads - 1) / kCvThreads;            // 6 per wave and tile
-constexpr int kCvBufHalves = kCvDma * kCvThreads * 8;                        // 24576 halves = 48 KB, three of them
+constexpr int kCvPieces = kCvRows * kCvRowSlots;                             // 2720
+constexpr int kCvLoads = (kCvPieces + 63) / 64;                              // 43 per tile
+constexpr int kCvDma = (kCvLoads + 7) / 8;                                   // at most 6 per wave
+constexpr int kCvBufHalves = kCvLoads * 64 * 8;                              // 22016 halves = 43 KB, three of them
 constexpr uint32_t kCvOutside = 0x80000000u;              // offset beyond any descriptor used here
 
 struct CvTile {
@@ -73,13 +81,6 @@ __device__ __forceinline__ bool cv_interior(const ConvArgs& p, const CvTile& t) 
     return t.y0 >= 1 && t.y0 + kCvTY + 1 <= p.H && t.x0 >= 1 && t.x0 + kCvTX + 1 <= p.W;
 }
 
-// Per-lane constants of the kCvDma loads of a wave: piece (r, px, channel piece) -> byte offset from
-// the tile's first staged pixel (y0-1, x0-1), and (r, px) for the border test.
-struct CvDma {
-    uint32_t off[kCvDma];
-    int rpx[kCvDma];          // r | px << 8, or -1 for a piece of the padding
-};
-
 // One LDS-direct load: 64 lanes x 16 bytes from base + voff (per lane) to 1 KB of LDS at lds_addr
 // (wave-uniform).  Written as assembly so that the compiler keeps no book on it: it would make
 // LDS reads of the other tile buffers wait for these loads, which are meant to stay in flight
@@ -93,24 +94,37 @@ __device__ __forceinline__ uint32_t cv_lds_addr(const half_t* p) {
     return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
 }
 
-// Requests the staged tile of `t` into `buf` (this wave's share): kCvDma loads, always.
-__device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, const CvDma& d, half_t* buf, int wv) {
+// A value the compiler must take as new: what is computed from it is computed again where it is
+// used, instead of being kept in registers (or spilled) across the whole tile loop.
+__device__ __forceinline__ int cv_fresh(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// Requests the staged tile of `t` into `buf` (this wave's share): 6 loads in waves 0..2, 5 in the others.
+// Load number wv + 8 i fills slots 64 (wv + 8 i) + lane.
+__device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, half_t* buf, int wv, int lane) {
     // the descriptor starts at the (possibly virtual) pixel (y0-1, x0-1); lanes outside the image never
     // reach memory
     const uint64_t org = (uint64_t)(p.in + (((int64_t)t.n * p.H + (t.y0 - 1)) * p.W + (t.x0 - 1)) * kCvC);
     const u32x4s rs = {(uint32_t)org, (uint32_t)(org >> 32) & 0xffffu, 0x7fffffffu, 0x00020000u};
     const bool inside = cv_interior(p, t);                // uniform
     const uint32_t lds0 = cv_lds_addr(buf) + 1024u * wv;
+    lane = cv_fresh(lane);
 #pragma unroll
     for (int i = 0; i < kCvDma; ++i) {
-        uint32_t off = d.off[i];
-        if (d.rpx[i] < 0) {
-            off = kCvOutside;
-        } else if (!inside) {
-            const int y = t.y0 - 1 + (d.rpx[i] & 0xff), x = t.x0 - 1 + (d.rpx[i] >> 8);
-            if (y < 0 || y >= p.H || x < 0 || x >= p.W) off = kCvOutside;
+        if (wv + 8 * i >= kCvLoads) break;                // uniform
+        const int slot = 64 * (wv + 8 * i) + lane;
+        const int r = (slot * 241) >> 16;                 // slot / 272 for slot < 2752
+        const int px = (slot - r * kCvRowSlots) >> 3;
+        const int cp = (lane & 7) ^ ((px >> 1) & 7);      // channel piece held by this slot
+        uint32_t off = (uint32_t)(((r * p.W + px) * kCvC + 8 * cp) * 2);
+        bool ok = slot < kCvPieces;
+        if (!inside) {
+            const int y = t.y0 - 1 + r, x = t.x0 - 1 + px;
+            ok = ok && y >= 0 && y < p.H && x >= 0 && x < p.W;
         }
-        cv_dma16(rs, lds0 + 8192u * i, off);
+        cv_dma16(rs, lds0 + 8192u * i, ok ? off : kCvOutside);
     }
 }
 
@@ -125,12 +139,23 @@ __device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, c
 constexpr int kCvAhead = HB_CONV_AHEAD;
 __device__ __forceinline__ void cv_rows(const half_t* buf, const half8 (&wf)[36], int ro, int c32, int h,
                                         floatx16 (&acc)[2]) {
-    const half_t* base = buf + cv_lds_index(ro, 0, h, c32);
+    // byte offset of (staged row ro, pixel c32 + kx) and the piece permutation there, per tap shift kx;
+    // group 3 kc + kx reads channel piece 2 kc + h, which sits in slot (2 kc) ^ (h ^ s)
+    c32 = cv_fresh(c32);
+    const char* cbuf = reinterpret_cast<const char*>(buf);
+    int apx[3], sw[3];
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) {
+        const int px = c32 + kx;
+        apx[kx] = (ro * kCvPx + px) * 128;
+        sw[kx] = 16 * (h ^ ((px >> 1) & 7));
+    }
     half8 b[kCvAhead + 1][4];
     auto read_group = [&](int grp, half8 (&dst)[4]) {
         const int kc = grp / 3, kx = grp - 3 * kc;
+        const char* a = cbuf + (apx[kx] + ((32 * kc) ^ sw[kx]));
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) dst[rr] = *reinterpret_cast<const half8*>(base + cv_lds_index(rr, kc, 0, kx));
+        for (int rr = 0; rr < 4; ++rr) dst[rr] = *reinterpret_cast<const half8*>(a + rr * (kCvRowSlots * 16));
     };
 #pragma unroll
     for (int g0 = 0; g0 < kCvAhead; ++g0) {
@@ -174,12 +199,12 @@ __device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t,
 // loads into another buffer.  A request has two tile times to land: at the meeting point a wave waits
 // for all its memory instructions but the kCvDma newest (the request just made; loads and stores
 // retire in order), i.e. for its share of the NEXT tile and for the previous tile's stores.
-__device__ __forceinline__ void cv_step(const ConvArgs& p, const CvDma& d, const half8 (&wf)[36],
+__device__ __forceinline__ void cv_step(const ConvArgs& p, int lane, const half8 (&wf)[36],
                                         const half_t* cur, half_t* far, int tile, int stride,
                                         int wv, int ro, int j, int c32, int h) {
     const CvTile t = cv_tile(p, tile);
     const bool req = tile + 2 * stride < p.ntiles;        // uniform
-    if (req) cv_request(p, cv_tile(p, tile + 2 * stride), d, far, wv);
+    if (req) cv_request(p, cv_tile(p, tile + 2 * stride), far, wv, lane);
     __builtin_amdgcn_sched_barrier(0);                    // the requests go out before the first product
     floatx16 acc[2];
 #pragma unroll
@@ -188,9 +213,10 @@ __device__ __forceinline__ void cv_step(const ConvArgs& p, const CvDma& d, const
         for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
     cv_rows(cur, wf, ro, c32, h, acc);
     __builtin_amdgcn_sched_barrier(0);
-    static_assert(kCvDma == 6, "the counted wait below is written for six loads per request");
-    if (req) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    static_assert(kCvLoads == 43, "the counted waits below are written for 6 / 5 loads per request");
+    if (!req) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (wv < 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
     // The barrier instruction is written out: the compiler would put a wait for ALL memory
     // instructions in front of one it emits itself, and the newest request must stay in flight.
     // This wave's LDS reads have been consumed by its products by now (lgkmcnt(0) states it).
@@ -232,27 +258,17 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     }
     __syncthreads();
 
-    CvDma d;
-#pragma unroll
-    for (int i = 0; i < kCvDma; ++i) {
-        const int piece = 64 * (wv + 8 * i) + lane;       // 16-byte piece of the buffer
-        const int run = piece / kCvPx, px = piece - run * kCvPx;
-        const int r = run >> 3, cp = run & 7;             // staged row, channel piece (2 kc + half)
-        d.off[i] = (uint32_t)(((r * p.W + px) * kCvC + 8 * cp) * 2);
-        d.rpx[i] = piece < kCvPieces ? (r | (px << 8)) : -1;
-    }
-
     const int stride = gridDim.x;
-    cv_request(p, cv_tile(p, tile), d, s_a, wv);
-    if (tile + stride < p.ntiles) cv_request(p, cv_tile(p, tile + stride), d, s_b, wv);
+    cv_request(p, cv_tile(p, tile), s_a, wv, lane);
+    if (tile + stride < p.ntiles) cv_request(p, cv_tile(p, tile + stride), s_b, wv, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     while (true) {
-        cv_step(p, d, wf, s_a, s_c, tile, stride, wv, ro, j, c32, h);
+        cv_step(p, lane, wf, s_a, s_c, tile, stride, wv, ro, j, c32, h);
         if ((tile += stride) >= p.ntiles) break;
-        cv_step(p, d, wf, s_b, s_a, tile, stride, wv, ro, j, c32, h);
+        cv_step(p, lane, wf, s_b, s_a, tile, stride, wv, ro, j, c32, h);
         if ((tile += stride) >= p.ntiles) break;
-        cv_step(p, d, wf, s_c, s_b, tile, stride, wv, ro, j, c32, h);
+        cv_step(p, lane, wf, s_c, s_b, tile, stride, wv, ro, j, c32, h);
         if ((tile += stride) >= p.ntiles) break;
     }
 }
