@@ -16,9 +16,9 @@
 //     outside the image arrive as zeros, which is the zero padding.
 //   A workgroup has 8 waves, two per SIMD, so that one wave's LDS reads hide behind the other's
 //   products: wave (q, j) owns output rows 2q, 2q+1 of the tile and channel tile j, i.e. 2 x 36
-//   products per tile.  fp32 accumulators are rounded to fp16 (RNE) and leave as 8-byte stores of 4
-//   consecutive channels.  The tile buffer is double: the next tile's pixels are fetched into
-//   registers before a wave starts multiplying and written to the other buffer afterwards.
+//   products per tile.  fp32 accumulators are rounded to fp16 (RNE) and leave through a small
+//   wave-private LDS stage as 16-byte pieces.  There are three tile buffers: the tile after the
+//   next is requested (global memory straight into LDS) before a wave starts multiplying.
 // Workgroups are persistent (one per compute unit) and walk over the tiles.
 #include "hb_device.hpp"
 #include "hb_host.hpp"
@@ -179,18 +179,39 @@ __device__ __forceinline__ void cv_rows(const half_t* buf, const half8 (&wf)[36]
     }
 }
 
-__device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t, int ro, int j, int c32, int h,
-                                             const floatx16& acc) {
-    const int y = t.y0 + ro, x = t.x0 + c32;
-    if (y < p.H && x < p.W) {
-        half_t* o = p.out + (((int64_t)t.n * p.H + y) * p.W + x) * kCvC + 32 * j;
+// The accumulators hold, per lane, one pixel and 16 scattered channels: stored as they are, one store
+// instruction would touch 64 different 128-byte lines with 8 bytes each.  Each of the two output rows
+// passes through a wave-private LDS stage (32 pixels x 32 channels of fp16, 80-byte pixel pitch:
+// conflict-free 16-byte reads) and leaves as 16-byte pieces, four consecutive lanes per pixel: a store
+// instruction then writes the 64 contiguous bytes of this wave's channel tile for 16 pixels.
+constexpr int kCvStagePitch = 40;                         // halves per pixel in the stage
+constexpr int kCvStageHalves = 32 * kCvStagePitch;        // 2560 bytes per wave
+__device__ __forceinline__ void cv_store_rows(const ConvArgs& p, const CvTile& t, int ro, int j, int lane,
+                                              const floatx16 (&acc)[2], half_t* stage) {
+    const int c32 = lane & 31, h = lane >> 5;
+    const int spx = lane >> 2, piece = lane & 3;
+#pragma unroll
+    for (int row = 0; row < 2; ++row) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             half4 v4;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v4[r] = (half_t)acc[4 * q + r];
-            *reinterpret_cast<half4*>(o + 8 * q + 4 * h) = v4;
+            for (int r = 0; r < 4; ++r) v4[r] = (half_t)acc[row][4 * q + r];
+            *reinterpret_cast<half4*>(stage + c32 * kCvStagePitch + 8 * q + 4 * h) = v4;
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int y = t.y0 + ro + row;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int px = spx + 16 * half, x = t.x0 + px;
+            const half8 v = *reinterpret_cast<const half8*>(stage + px * kCvStagePitch + 8 * piece);
+            if (y < p.H && x < p.W)
+                *reinterpret_cast<half8*>(p.out + (((int64_t)t.n * p.H + y) * p.W + x) * kCvC + 32 * j + 8 * piece) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -200,7 +221,7 @@ __device__ __forceinline__ void cv_store_row(const ConvArgs& p, const CvTile& t,
 // for all its memory instructions but the kCvDma newest (the request just made; loads and stores
 // retire in order), i.e. for its share of the NEXT tile and for the previous tile's stores.
 __device__ __forceinline__ void cv_step(const ConvArgs& p, int lane, const half8 (&wf)[36],
-                                        const half_t* cur, half_t* far, int tile, int stride,
+                                        const half_t* cur, half_t* far, half_t* stage, int tile, int stride,
                                         int wv, int ro, int j, int c32, int h) {
     const CvTile t = cv_tile(p, tile);
     const bool req = tile + 2 * stride < p.ntiles;        // uniform
@@ -221,14 +242,14 @@ __device__ __forceinline__ void cv_step(const ConvArgs& p, int lane, const half8
     // instructions in front of one it emits itself, and the newest request must stay in flight.
     // This wave's LDS reads have been consumed by its products by now (lgkmcnt(0) states it).
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next buffer complete, this one released
-    cv_store_row(p, t, ro, j, c32, h, acc[0]);            // in flight during the next tile's products
-    cv_store_row(p, t, ro + 1, j, c32, h, acc[1]);
+    cv_store_rows(p, t, ro, j, lane, acc, stage);         // in flight during the next tile's products
 }
 
 __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     __shared__ __attribute__((aligned(16))) half_t s_a[kCvBufHalves];
     __shared__ __attribute__((aligned(16))) half_t s_b[kCvBufHalves];
     __shared__ __attribute__((aligned(16))) half_t s_c[kCvBufHalves];
+    __shared__ __attribute__((aligned(16))) half_t s_stage[8][kCvStageHalves];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, h = lane >> 5;
@@ -264,11 +285,11 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     while (true) {
-        cv_step(p, lane, wf, s_a, s_c, tile, stride, wv, ro, j, c32, h);
+        cv_step(p, lane, wf, s_a, s_c, s_stage[wv], tile, stride, wv, ro, j, c32, h);
         if ((tile += stride) >= p.ntiles) break;
-        cv_step(p, lane, wf, s_b, s_a, tile, stride, wv, ro, j, c32, h);
+        cv_step(p, lane, wf, s_b, s_a, s_stage[wv], tile, stride, wv, ro, j, c32, h);
         if ((tile += stride) >= p.ntiles) break;
-        cv_step(p, lane, wf, s_c, s_b, tile, stride, wv, ro, j, c32, h);
+        cv_step(p, lane, wf, s_c, s_b, s_stage[wv], tile, stride, wv, ro, j, c32, h);
         if ((tile += stride) >= p.ntiles) break;
     }
 }
