@@ -7,19 +7,21 @@
 // with v_mfma_f32_32x32x16_f16: 32 channels x 32 pixels per product, K = 16 input channels.
 //   A (coefficients): the 9 x 64 x 32 weights of one 32-channel tile live in the registers of a
 //     wave for the whole kernel (36 K-steps x 8 halves per lane = 144 registers), gathered once.
-//   B (pixels): a workgroup stages an (8+2) x (32+2) pixel tile of all 64 input channels in LDS in
-//     the image's own order (pixel-major, 128 bytes per pixel), with the eight 16-byte channel
-//     pieces of a pixel permuted by an XOR with bits 1..3 of the pixel index: a tile row then
-//     arrives as contiguous 1 KB copies, and the 16-byte reads of 16 consecutive pixels at one
-//     channel piece still fall into 64 different banks for every tap shift (the overlapped view of
-//     Eq. 1: the three horizontal taps read the same LDS row at pixel offsets 0, 1, 2).  Pixels
-//     outside the image arrive as zeros, which is the zero padding.
+//   B (pixels): a workgroup walks DOWN a column of 8 x 32 pixel tiles.  The image rows it needs
+//     (34 pixels x 64 channels each, with the one-pixel halo) stream through a ring of 26 rows in
+//     LDS: a tile reads 10 of them, the 8 new rows of the next tile have landed, those of the tile
+//     after that are in flight, and the two halo rows between vertically adjacent tiles are
+//     fetched once.  Rows arrive by buffer loads that write LDS directly, in the image's own order
+//     (pixel-major, 128 bytes per pixel) with the eight 16-byte channel pieces of a pixel permuted
+//     by an XOR with bits 1..3 of the pixel index: a row is a few contiguous 1 KB copies, and the
+//     16-byte reads of 16 consecutive pixels at one channel piece still fall into 64 different
+//     banks for every tap shift (the overlapped view of Eq. 1: the three horizontal taps read the
+//     same LDS row at pixel offsets 0, 1, 2).  Pixels outside the image arrive as zeros (requested
+//     beyond the end of the buffer descriptor), which is the zero padding.
 //   A workgroup has 8 waves, two per SIMD, so that one wave's LDS reads hide behind the other's
 //   products: wave (q, j) owns output rows 2q, 2q+1 of the tile and channel tile j, i.e. 2 x 36
-//   products per tile.  fp32 accumulators are rounded to fp16 (RNE) and leave through a small
-//   wave-private LDS stage as 16-byte pieces.  There are three tile buffers: the tile after the
-//   next is requested (global memory straight into LDS) before a wave starts multiplying.
-// Workgroups are persistent (one per compute unit) and walk over the tiles.
+//   products per tile.  fp32 accumulators are rounded to fp16 (RNE) into a stage shared by the
+//   workgroup and leave as whole 128-byte pixels (1 KB per store instruction).
 #include "hb_device.hpp"
 #include "hb_host.hpp"
 
@@ -28,7 +30,7 @@ namespace hb {
 constexpr int kCvC = 64;                 // channels in and out
 constexpr int kCvTY = 8, kCvTX = 32;     // output tile (rows x pixels) per workgroup step
 constexpr int kCvRows = kCvTY + 2, kCvPx = kCvTX + 2;
-constexpr int kCvLdsHalves = kCvRows * 4 * kCvPx * 16;
+constexpr int kCvLdsHalves = kCvRows * 4 * kCvPx * 16;    // tile of the vector-ALU twin
 
 struct ConvArgs {
     const half_t* in;
@@ -37,6 +39,7 @@ struct ConvArgs {
     int N, H, W;
     int tiles_x, tiles_y;      // per image
     int ntiles;                // N * tiles_y * tiles_x
+    int seg_len, nseg;         // MFMA kernel: tiles per column segment, segments per column
 };
 
 // LDS layout of the vector-ALU twin: [row][16-channel chunk][8-channel half][pixel][8 channels].
@@ -44,55 +47,18 @@ __device__ __forceinline__ int cv_lds_index(int r, int kc, int half, int px) {
     return (((r * 4 + kc) * 2 + half) * kCvPx + px) * 8;
 }
 
-// LDS layout of the MFMA kernel, in 16-byte slots: pixel-major, channel piece cp of pixel px in slot
-// cp ^ ((px >> 1) & 7) of the pixel's eight.
-constexpr int kCvRowSlots = kCvPx * 8;                    // 272 slots = 4352 bytes per staged row
-__device__ __forceinline__ int cv_slot(int r, int px, int cp) {
-    return (r * kCvPx + px) * 8 + (cp ^ ((px >> 1) & 7));
-}
-
-// A staged tile is 2720 slots.  It is filled by buffer loads that write LDS directly (64 lanes x
-// 16 bytes = 1 KB of consecutive LDS per instruction = 8 whole pixels, whose 128 bytes are
-// contiguous in memory): no register holds a pixel on its way in.  43 such loads make a tile; wave
-// w issues those numbered w, w + 8, ...: six for waves 0..2, five for the others.  Slots past the
-// tile and pixels outside the image are requested beyond the end of the buffer descriptor, which
-// makes the hardware deliver zeros: that is the zero padding of the convolution.
+// LDS ring of the MFMA kernel: kCvRing rows of 34 pixels x 128 bytes; channel piece cp (16 bytes) of
+// pixel px sits in slot cp ^ ((px >> 1) & 7) of the pixel's eight.
 constexpr int kCvThreads = 512;
-constexpr int kCvPieces = kCvRows * kCvRowSlots;                             // 2720
-constexpr int kCvLoads = (kCvPieces + 63) / 64;                              // 43 per tile
-constexpr int kCvDma = (kCvLoads + 7) / 8;                                   // at most 6 per wave
-constexpr int kCvBufHalves = kCvLoads * 64 * 8;                              // 22016 halves = 43 KB, three of them
+constexpr int kCvRing = 26;                               // 10 in use + 8 landed + 8 in flight
+constexpr int kCvRowBytes = kCvPx * 128;                  // 4352
+constexpr int kCvRowSlots = kCvPx * 8;                    // 272 16-byte slots
+constexpr int kCvRowLoads = (kCvRowSlots + 63) / 64;      // 5 loads per row, the last one 16 lanes wide
+constexpr int kCvRingBytes = kCvRing * kCvRowBytes;       // 113152
 constexpr uint32_t kCvOutside = 0x80000000u;              // offset beyond any descriptor used here
-
-struct CvTile {
-    int n, y0, x0;
-};
-__device__ __forceinline__ CvTile cv_tile(const ConvArgs& p, int tile) {
-    CvTile t;
-    t.n = tile / (p.tiles_x * p.tiles_y);
-    const int rem = tile - t.n * (p.tiles_x * p.tiles_y);
-    const int ty = rem / p.tiles_x;
-    t.y0 = ty * kCvTY;
-    t.x0 = (rem - ty * p.tiles_x) * kCvTX;
-    return t;
-}
-// whole staged tile inside the image?
-__device__ __forceinline__ bool cv_interior(const ConvArgs& p, const CvTile& t) {
-    return t.y0 >= 1 && t.y0 + kCvTY + 1 <= p.H && t.x0 >= 1 && t.x0 + kCvTX + 1 <= p.W;
-}
-
-// One LDS-direct load: 64 lanes x 16 bytes from base + voff (per lane) to 1 KB of LDS at lds_addr
-// (wave-uniform).  Written as assembly so that the compiler keeps no book on it: it would make
-// LDS reads of the other tile buffers wait for these loads, which are meant to stay in flight
-// for two tiles.  The waits that order them are explicit in cv_step.
-typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void cv_dma16(u32x4s rsrc, uint32_t lds_addr, uint32_t voff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
-}
-__device__ __forceinline__ uint32_t cv_lds_addr(const half_t* p) {
-    return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
-}
+// Output stage: 8 rows x 32 pixels x 64 channels of fp16, 144-byte pixel pitch (conflict-free reads).
+constexpr int kCvStagePitch = 144;
+constexpr int kCvStageBytes = kCvTY * kCvTX * kCvStagePitch;   // 36864
 
 // A value the compiler must take as new: what is computed from it is computed again where it is
 // used, instead of being kept in registers (or spilled) across the whole tile loop.
@@ -101,61 +67,69 @@ __device__ __forceinline__ int cv_fresh(int v) {
     return v;
 }
 
-// Requests the staged tile of `t` into `buf` (this wave's share): 6 loads in waves 0..2, 5 in the others.
-// Load number wv + 8 i fills slots 64 (wv + 8 i) + lane.
-__device__ __forceinline__ void cv_request(const ConvArgs& p, const CvTile& t, half_t* buf, int wv, int lane) {
-    // the descriptor starts at the (possibly virtual) pixel (y0-1, x0-1); lanes outside the image never
+// One LDS-direct load: the active lanes copy 16 bytes each from base + voff (per lane) to LDS at
+// lds_addr + 16 * lane (lds_addr wave-uniform).  Written as assembly so that the compiler keeps no
+// book on it: it would make LDS reads of other ring rows wait for these loads, which are meant to
+// stay in flight for two tiles.  The waits that order them are explicit in the tile loop.
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void cv_dma16(u32x4s rsrc, uint32_t lds_addr, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ uint32_t cv_lds_addr(const void* p) {
+    return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// Requests image row y, pixels x0-1 .. x0+32, of image n into ring row `rrow`: kCvRowLoads loads by
+// the calling wave.  Rows and pixels outside the image arrive as zeros.
+__device__ __forceinline__ void cv_request_row(const ConvArgs& p, int n, int y, int x0, char* ring, int rrow, int lane) {
+    const bool yok = y >= 0 && y < p.H;                   // uniform
+    // the descriptor starts at the (possibly virtual) pixel (y, x0-1); lanes outside the image never
     // reach memory
-    const uint64_t org = (uint64_t)(p.in + (((int64_t)t.n * p.H + (t.y0 - 1)) * p.W + (t.x0 - 1)) * kCvC);
+    const uint64_t org = (uint64_t)(p.in + (((int64_t)n * p.H + (yok ? y : 0)) * p.W + (x0 - 1)) * kCvC);
     const u32x4s rs = {(uint32_t)org, (uint32_t)(org >> 32) & 0xffffu, 0x7fffffffu, 0x00020000u};
-    const bool inside = cv_interior(p, t);                // uniform
-    const uint32_t lds0 = cv_lds_addr(buf) + 1024u * wv;
+    const uint32_t lds0 = cv_lds_addr(ring) + (uint32_t)(rrow * kCvRowBytes);
     lane = cv_fresh(lane);
 #pragma unroll
-    for (int i = 0; i < kCvDma; ++i) {
-        if (wv + 8 * i >= kCvLoads) break;                // uniform
-        const int slot = 64 * (wv + 8 * i) + lane;
-        const int r = (slot * 241) >> 16;                 // slot / 272 for slot < 2752
-        const int px = (slot - r * kCvRowSlots) >> 3;
+    for (int c = 0; c < kCvRowLoads; ++c) {
+        const int slot = 64 * c + lane;
+        const int px = slot >> 3;
         const int cp = (lane & 7) ^ ((px >> 1) & 7);      // channel piece held by this slot
-        uint32_t off = (uint32_t)(((r * p.W + px) * kCvC + 8 * cp) * 2);
-        bool ok = slot < kCvPieces;
-        if (!inside) {
-            const int y = t.y0 - 1 + r, x = t.x0 - 1 + px;
-            ok = ok && y >= 0 && y < p.H && x >= 0 && x < p.W;
-        }
-        cv_dma16(rs, lds0 + 8192u * i, ok ? off : kCvOutside);
+        const int x = x0 - 1 + px;
+        const bool ok = yok && x >= 0 && x < p.W;
+        const uint32_t off = ok ? (uint32_t)(px * 128 + 16 * cp) : kCvOutside;
+        if (c < kCvRowLoads - 1 || lane < kCvRowSlots - 64 * (kCvRowLoads - 1))   // the row ends after 272 slots
+            cv_dma16(rs, lds0 + 1024u * c, off);
     }
 }
 
-// Two output rows (2 x 32 pixels) x 32 channels from the staged tile.  The four staged rows under
-// the two output rows are read once per (channel chunk, horizontal tap) and serve both rows:
-// 48 reads for 72 products, in 12 groups of 4 reads + 6 products.  The reads of a group are issued
-// kCvAhead groups before its products (the scheduling barriers pin that order), so that an LDS
-// read has the time of 6 * kCvAhead products to return.
+// Two output rows (2 x 32 pixels) x 32 channels from four ring rows (byte offsets row[0..3] from the
+// ring base, wave-uniform).  The four rows under the two output rows are read once per (channel
+// chunk, horizontal tap) and serve both output rows: 48 reads for 72 products, in 12 groups of
+// 4 reads + 6 products.  The reads of a group are issued kCvAhead groups before its products (the
+// scheduling barriers pin that order), so that an LDS read has the time of 6 * kCvAhead products.
 #ifndef HB_CONV_AHEAD
 #define HB_CONV_AHEAD 1
 #endif
 constexpr int kCvAhead = HB_CONV_AHEAD;
-__device__ __forceinline__ void cv_rows(const half_t* buf, const half8 (&wf)[36], int ro, int c32, int h,
+__device__ __forceinline__ void cv_rows(const char* ring, const int (&row)[4], const half8 (&wf)[36], int c32, int h,
                                         floatx16 (&acc)[2]) {
-    // byte offset of (staged row ro, pixel c32 + kx) and the piece permutation there, per tap shift kx;
+    // byte offset of pixel c32 + kx inside a row and the piece permutation there, per tap shift kx;
     // group 3 kc + kx reads channel piece 2 kc + h, which sits in slot (2 kc) ^ (h ^ s)
     c32 = cv_fresh(c32);
-    const char* cbuf = reinterpret_cast<const char*>(buf);
     int apx[3], sw[3];
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) {
         const int px = c32 + kx;
-        apx[kx] = (ro * kCvPx + px) * 128;
+        apx[kx] = px * 128;
         sw[kx] = 16 * (h ^ ((px >> 1) & 7));
     }
     half8 b[kCvAhead + 1][4];
     auto read_group = [&](int grp, half8 (&dst)[4]) {
         const int kc = grp / 3, kx = grp - 3 * kc;
-        const char* a = cbuf + (apx[kx] + ((32 * kc) ^ sw[kx]));
+        const int a = apx[kx] + ((32 * kc) ^ sw[kx]);
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) dst[rr] = *reinterpret_cast<const half8*>(a + rr * (kCvRowSlots * 16));
+        for (int rr = 0; rr < 4; ++rr) dst[rr] = *reinterpret_cast<const half8*>(ring + (a + row[rr]));
     };
 #pragma unroll
     for (int g0 = 0; g0 < kCvAhead; ++g0) {
@@ -179,118 +153,94 @@ __device__ __forceinline__ void cv_rows(const half_t* buf, const half8 (&wf)[36]
     }
 }
 
-// The accumulators hold, per lane, one pixel and 16 scattered channels: stored as they are, one store
-// instruction would touch 64 different 128-byte lines with 8 bytes each.  Each of the two output rows
-// passes through a wave-private LDS stage (32 pixels x 32 channels of fp16, 80-byte pixel pitch:
-// conflict-free 16-byte reads) and leaves as 16-byte pieces, four consecutive lanes per pixel: a store
-// instruction then writes the 64 contiguous bytes of this wave's channel tile for 16 pixels.
-constexpr int kCvStagePitch = 40;                         // halves per pixel in the stage
-constexpr int kCvStageHalves = 32 * kCvStagePitch;        // 2560 bytes per wave
-__device__ __forceinline__ void cv_store_rows(const ConvArgs& p, const CvTile& t, int ro, int j, int lane,
-                                              const floatx16 (&acc)[2], half_t* stage) {
-    const int c32 = lane & 31, h = lane >> 5;
-    const int spx = lane >> 2, piece = lane & 3;
-#pragma unroll
-    for (int row = 0; row < 2; ++row) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            half4 v4;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v4[r] = (half_t)acc[row][4 * q + r];
-            *reinterpret_cast<half4*>(stage + c32 * kCvStagePitch + 8 * q + 4 * h) = v4;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int y = t.y0 + ro + row;
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int px = spx + 16 * half, x = t.x0 + px;
-            const half8 v = *reinterpret_cast<const half8*>(stage + px * kCvStagePitch + 8 * piece);
-            if (y < p.H && x < p.W)
-                *reinterpret_cast<half8*>(p.out + (((int64_t)t.n * p.H + y) * p.W + x) * kCvC + 32 * j + 8 * piece) = v;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
-}
-
-// One tile: request the tile after the next into the third buffer, multiply this one, meet, store.
-// The three buffers are distinct LDS arrays at every call site, so the reads of `cur` do not wait for
-// loads into another buffer.  A request has two tile times to land: at the meeting point a wave waits
-// for all its memory instructions but the kCvDma newest (the request just made; loads and stores
-// retire in order), i.e. for its share of the NEXT tile and for the previous tile's stores.
-__device__ __forceinline__ void cv_step(const ConvArgs& p, int lane, const half8 (&wf)[36],
-                                        const half_t* cur, half_t* far, half_t* stage, int tile, int stride,
-                                        int wv, int ro, int j, int c32, int h) {
-    const CvTile t = cv_tile(p, tile);
-    const bool req = tile + 2 * stride < p.ntiles;        // uniform
-    if (req) cv_request(p, cv_tile(p, tile + 2 * stride), far, wv, lane);
-    __builtin_amdgcn_sched_barrier(0);                    // the requests go out before the first product
-    floatx16 acc[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
-    cv_rows(cur, wf, ro, c32, h, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    static_assert(kCvLoads == 43, "the counted waits below are written for 6 / 5 loads per request");
-    if (!req) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (wv < 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-    // The barrier instruction is written out: the compiler would put a wait for ALL memory
-    // instructions in front of one it emits itself, and the newest request must stay in flight.
-    // This wave's LDS reads have been consumed by its products by now (lgkmcnt(0) states it).
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next buffer complete, this one released
-    cv_store_rows(p, t, ro, j, lane, acc, stage);         // in flight during the next tile's products
-}
-
 __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
-    __shared__ __attribute__((aligned(16))) half_t s_a[kCvBufHalves];
-    __shared__ __attribute__((aligned(16))) half_t s_b[kCvBufHalves];
-    __shared__ __attribute__((aligned(16))) half_t s_c[kCvBufHalves];
-    __shared__ __attribute__((aligned(16))) half_t s_stage[8][kCvStageHalves];
+    __shared__ __attribute__((aligned(16))) char s_ring[kCvRingBytes];
+    __shared__ __attribute__((aligned(16))) char s_stage[kCvStageBytes];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, h = lane >> 5;
     const int j = wv >> 2;                                // channel tile of this wave
     const int ro = 2 * (wv & 3);                          // its two output rows inside the tile
 
-    int tile = blockIdx.x;
-    if (tile >= p.ntiles) return;
+    // task = column segment: image n, tile column cx, tile rows ty0 .. ty0 + len - 1
+    const int task = blockIdx.x;
+    const int per_img = p.tiles_x * p.nseg;
+    const int n = task / per_img;
+    const int sg = (task - n * per_img) / p.tiles_x, cx = task - n * per_img - sg * p.tiles_x;
+    const int ty0 = sg * p.seg_len;
+    const int len = min(p.seg_len, p.tiles_y - ty0);
+    const int x0 = cx * kCvTX;
+    const int ys = ty0 * kCvTY - 1;                       // image row held by ring row 0 at the start
 
     // coefficient fragments: wf[s] lane (c32, h) = w[tap][16 kc + 8h + i][32 j + c32], s = 4 tap + kc.
-    // The 72 KB of weights pass through LDS once, taps 0..4 through one buffer and 5..8 through
-    // another (coalesced 16-byte copies in, 2-byte gathers out: lanes of a half-wave read 32
-    // consecutive halves, no bank conflict).
+    // The 72 KB of weights pass through the (still empty) ring once: coalesced 16-byte copies in,
+    // 2-byte gathers out (lanes of a half-wave read 32 consecutive halves, no bank conflict).
     half8 wf[36];
-    constexpr int kTapHalves = kCvC * kCvC;
-    for (int i = tid; i < 5 * kTapHalves / 8; i += kCvThreads)
-        reinterpret_cast<half8*>(s_a)[i] = reinterpret_cast<const half8*>(p.w)[i];
-    for (int i = tid; i < 4 * kTapHalves / 8; i += kCvThreads)
-        reinterpret_cast<half8*>(s_b)[i] = reinterpret_cast<const half8*>(p.w + 5 * kTapHalves)[i];
-    __syncthreads();
+    {
+        half_t* wl = reinterpret_cast<half_t*>(s_ring);
+        for (int i = tid; i < 9 * kCvC * kCvC / 8; i += kCvThreads)
+            reinterpret_cast<half8*>(wl)[i] = reinterpret_cast<const half8*>(p.w)[i];
+        __syncthreads();
 #pragma unroll
-    for (int s = 0; s < 36; ++s) {
-        const int tap = s >> 2;
-        const half_t* src = tap < 5 ? s_a + tap * kTapHalves : s_b + (tap - 5) * kTapHalves;
+        for (int s = 0; s < 36; ++s)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wf[s][i] = src[(16 * (s & 3) + 8 * h + i) * kCvC + 32 * j + c32];
+            for (int i = 0; i < 8; ++i)
+                wf[s][i] = wl[((s >> 2) * kCvC + 16 * (s & 3) + 8 * h + i) * kCvC + 32 * j + c32];
+        __syncthreads();
     }
-    __syncthreads();
 
-    const int stride = gridDim.x;
-    cv_request(p, cv_tile(p, tile), s_a, wv, lane);
-    if (tile + stride < p.ntiles) cv_request(p, cv_tile(p, tile + stride), s_b, wv, lane);
+    // start-up: rows 0..9 of the first tile (waves 0, 1 take two rows each), the 8 new rows of the second
+    if (wv < 2) cv_request_row(p, n, ys + wv, x0, s_ring, wv, lane);
+    cv_request_row(p, n, ys + 2 + wv, x0, s_ring, 2 + wv, lane);
+    if (len > 1) cv_request_row(p, n, ys + 10 + wv, x0, s_ring, 10 + wv, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    while (true) {
-        cv_step(p, lane, wf, s_a, s_c, s_stage[wv], tile, stride, wv, ro, j, c32, h);
-        if ((tile += stride) >= p.ntiles) break;
-        cv_step(p, lane, wf, s_b, s_a, s_stage[wv], tile, stride, wv, ro, j, c32, h);
-        if ((tile += stride) >= p.ntiles) break;
-        cv_step(p, lane, wf, s_c, s_b, s_stage[wv], tile, stride, wv, ro, j, c32, h);
-        if ((tile += stride) >= p.ntiles) break;
+
+    for (int k = 0; k < len; ++k) {
+        // the rows of tile k + 2 take the ring rows that tile k - 1 has released
+        const bool req = k + 2 < len;                     // uniform
+        if (req) cv_request_row(p, n, ys + 8 * k + 18 + wv, x0, s_ring, (8 * k + 18 + wv) % kCvRing, lane);
+        __builtin_amdgcn_sched_barrier(0);                // the requests go out before the first product
+        int row[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) row[rr] = ((8 * k + ro + rr) % kCvRing) * kCvRowBytes;
+        floatx16 acc[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
+        cv_rows(s_ring, row, wf, c32, h, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        // accumulators -> stage: lane (c32, h) holds channels 32 j + 8 q + 4 h + (0..3) of pixel c32
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                half4 v4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v4[r] = (half_t)acc[u][4 * q + r];
+                *reinterpret_cast<half4*>(s_stage + ((ro + u) * kCvTX + c32) * kCvStagePitch + (32 * j + 8 * q + 4 * h) * 2) = v4;
+            }
+        // Meeting point.  A wave waits for all its memory instructions but the newest request (loads
+        // and stores retire in order): its row of the NEXT tile has landed, the previous tile's
+        // stores are done.  The barrier instructions are written out: the compiler would put a wait
+        // for ALL memory instructions in front of one it emits itself.
+        static_assert(kCvRowLoads == 5, "the counted wait below is written for five loads per request");
+        if (req) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next rows complete, this tile's rows released, stage written
+        // stage -> memory: 8 lanes per pixel, 1 KB per store instruction
+        const int y0 = (ty0 + k) * kCvTY;
+#pragma unroll
+        for (int i = 0; i < kCvTY * kCvTX * 8 / kCvThreads; ++i) {
+            const int id = tid + kCvThreads * i;
+            const int orow = id >> 8, px = (id >> 3) & 31, piece = id & 7;
+            const half8 v = *reinterpret_cast<const half8*>(s_stage + (orow * kCvTX + px) * kCvStagePitch + 16 * piece);
+            const int y = y0 + orow, x = x0 + px;
+            if (y < p.H && x < p.W)
+                *reinterpret_cast<half8*>(p.out + (((int64_t)n * p.H + y) * p.W + x) * kCvC + 8 * piece) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // stage read, free for the next tile
     }
 }
 
@@ -358,7 +308,6 @@ static hb_status conv_prepare(ConvArgs& a, const hb_half* in, const hb_half* w, 
     if (Cin != kCvC || Cout != kCvC) return HB_ERR_UNSUPPORTED;
     const int64_t tiles = (int64_t)N * ceil_div(H, kCvTY) * ceil_div(W, kCvTX);
     if (tiles > 0x7fffffff || (int64_t)N * H * W > ((int64_t)1 << 40)) return HB_ERR_UNSUPPORTED;
-    if ((int64_t)W * kCvRows * kCvC * 2 >= ((int64_t)1 << 30)) return HB_ERR_UNSUPPORTED;   // 32-bit tile offsets
     a.in = reinterpret_cast<const half_t*>(in);
     a.w = reinterpret_cast<const half_t*>(w);
     a.out = reinterpret_cast<half_t*>(out);
@@ -368,6 +317,12 @@ static hb_status conv_prepare(ConvArgs& a, const hb_half* in, const hb_half* w, 
     a.tiles_x = ceil_div(W, kCvTX);
     a.tiles_y = ceil_div(H, kCvTY);
     a.ntiles = (int)tiles;
+    // column segments of the MFMA kernel: about one per compute unit, at least 4 tiles long
+    const int want = ceil_div(kNumCU, N * a.tiles_x);
+    int len = ceil_div(a.tiles_y, want);
+    if (len < 4) len = a.tiles_y < 4 ? a.tiles_y : 4;
+    a.seg_len = len;
+    a.nseg = ceil_div(a.tiles_y, len);
     return HB_OK;
 }
 
@@ -379,8 +334,9 @@ extern "C" hb_status hb_conv3x3(const hb_half* in_nhwc, const hb_half* w_hwio, h
     ConvArgs a;
     hb_status s = conv_prepare(a, in_nhwc, w_hwio, out_nhwc, N, H, W, Cin, Cout);
     if (s != HB_OK) return s;
-    const int blocks = min(a.ntiles, kNumCU);
-    hipLaunchKernelGGL(conv3x3_mfma_kernel, dim3(blocks), dim3(kCvThreads), 0,
+    const int64_t blocks = (int64_t)N * a.tiles_x * a.nseg;
+    if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(conv3x3_mfma_kernel, dim3((unsigned)blocks), dim3(kCvThreads), 0,
                        reinterpret_cast<hipStream_t>(stream), a);
     return launch_status();
 }
