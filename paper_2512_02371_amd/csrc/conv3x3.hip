@@ -173,19 +173,26 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     const int ys = ty0 * kCvTY - 1;                       // image row held by ring row 0 at the start
 
     // coefficient fragments: wf[s] lane (c32, h) = w[tap][16 kc + 8h + i][32 j + c32], s = 4 tap + kc.
-    // The 72 KB of weights pass through the (still empty) ring once: coalesced 16-byte copies in,
-    // 2-byte gathers out (lanes of a half-wave read 32 consecutive halves, no bank conflict).
+    // The weights arrive with the output channel innermost; a fragment wants eight consecutive INPUT
+    // channels per lane.  They pass through the (still empty) ring once, transposed on the way in:
+    // coalesced 16-byte reads of eight output channels, 2-byte writes to [tap][co][ci] with a
+    // 144-byte pitch per (tap, co), so that each fragment is one conflict-free 16-byte read.
     half8 wf[36];
     {
-        half_t* wl = reinterpret_cast<half_t*>(s_ring);
-        for (int i = tid; i < 9 * kCvC * kCvC / 8; i += kCvThreads)
-            reinterpret_cast<half8*>(wl)[i] = reinterpret_cast<const half8*>(p.w)[i];
+        constexpr int kWPitch = 144;                      // bytes per (tap, output channel): 64 ci + pad
+        static_assert(9 * kCvC * kWPitch <= kCvRingBytes, "the transposed weights must fit the ring");
+        for (int i = tid; i < 9 * kCvC * kCvC / 8; i += kCvThreads) {
+            const half8 v = reinterpret_cast<const half8*>(p.w)[i];          // w[tap][ci][8 cog .. 8 cog + 7]
+            const int cog = i & 7, ci = (i >> 3) & 63, tap = i >> 9;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<half_t*>(s_ring + (tap * kCvC + 8 * cog + e) * kWPitch + 2 * ci) = v[e];
+        }
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < 36; ++s)
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                wf[s][i] = wl[((s >> 2) * kCvC + 16 * (s & 3) + 8 * h + i) * kCvC + 32 * j + c32];
+            wf[s] = *reinterpret_cast<const half8*>(s_ring + ((s >> 2) * kCvC + 32 * j + c32) * kWPitch +
+                                                    2 * (16 * (s & 3) + 8 * h));
         __syncthreads();
     }
 
