@@ -80,27 +80,38 @@ __device__ __forceinline__ uint32_t cv_lds_addr(const void* p) {
     return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
 }
 
+// Per-lane byte offsets of the kCvRowLoads loads of a row, from the row's pixel x0-1: slot 64 c + lane
+// holds channel piece (lane & 7) ^ ((px >> 1) & 7) of pixel px = 8 c + lane / 8.  Pixels left or right
+// of the image get an offset beyond the descriptor (they arrive as zeros).
+struct CvRowOff {
+    uint32_t off[kCvRowLoads];
+};
+__device__ __forceinline__ CvRowOff cv_row_offsets(const ConvArgs& p, int x0, int lane) {
+    CvRowOff d;
+#pragma unroll
+    for (int c = 0; c < kCvRowLoads; ++c) {
+        const int px = 8 * c + (lane >> 3);
+        const int cp = (lane & 7) ^ ((px >> 1) & 7);
+        const int x = x0 - 1 + px;
+        d.off[c] = (x >= 0 && x < p.W) ? (uint32_t)(px * 128 + 16 * cp) : kCvOutside;
+    }
+    return d;
+}
+
 // Requests image row y, pixels x0-1 .. x0+32, of image n into ring row `rrow`: kCvRowLoads loads by
-// the calling wave.  Rows and pixels outside the image arrive as zeros.
-__device__ __forceinline__ void cv_request_row(const ConvArgs& p, int n, int y, int x0, char* ring, int rrow, int lane) {
+// the calling wave.  A row outside the image gets a descriptor of length zero: it arrives as zeros.
+__device__ __forceinline__ void cv_request_row(const ConvArgs& p, const CvRowOff& d, int n, int y, int x0,
+                                               char* ring, int rrow, int lane) {
     const bool yok = y >= 0 && y < p.H;                   // uniform
     // the descriptor starts at the (possibly virtual) pixel (y, x0-1); lanes outside the image never
     // reach memory
     const uint64_t org = (uint64_t)(p.in + (((int64_t)n * p.H + (yok ? y : 0)) * p.W + (x0 - 1)) * kCvC);
-    const u32x4s rs = {(uint32_t)org, (uint32_t)(org >> 32) & 0xffffu, 0x7fffffffu, 0x00020000u};
+    const u32x4s rs = {(uint32_t)org, (uint32_t)(org >> 32) & 0xffffu, yok ? 0x7fffffffu : 0u, 0x00020000u};
     const uint32_t lds0 = cv_lds_addr(ring) + (uint32_t)(rrow * kCvRowBytes);
-    lane = cv_fresh(lane);
 #pragma unroll
-    for (int c = 0; c < kCvRowLoads; ++c) {
-        const int slot = 64 * c + lane;
-        const int px = slot >> 3;
-        const int cp = (lane & 7) ^ ((px >> 1) & 7);      // channel piece held by this slot
-        const int x = x0 - 1 + px;
-        const bool ok = yok && x >= 0 && x < p.W;
-        const uint32_t off = ok ? (uint32_t)(px * 128 + 16 * cp) : kCvOutside;
-        if (c < kCvRowLoads - 1 || lane < kCvRowSlots - 64 * (kCvRowLoads - 1))   // the row ends after 272 slots
-            cv_dma16(rs, lds0 + 1024u * c, off);
-    }
+    for (int c = 0; c < kCvRowLoads - 1; ++c) cv_dma16(rs, lds0 + 1024u * c, d.off[c]);
+    if (lane < kCvRowSlots - 64 * (kCvRowLoads - 1))      // the row ends after 272 slots
+        cv_dma16(rs, lds0 + 1024u * (kCvRowLoads - 1), d.off[kCvRowLoads - 1]);
 }
 
 // Two output rows (2 x 32 pixels) x 32 channels from four ring rows (byte offsets row[0..3] from the
@@ -196,21 +207,42 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
         __syncthreads();
     }
 
+    const CvRowOff d = cv_row_offsets(p, x0, lane);
+
+    // output: a descriptor over image n; thread t stores pieces t, t + 512, ... of the 8 x 32 x 8 pieces
+    // of a tile (8 lanes per pixel): row (t >> 8) + 2 i, pixel (t >> 3) & 31, piece t & 7
+    const int64_t obytes = (int64_t)p.H * p.W * kCvC * 2;     // < 2 GiB (host check)
+    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+        p.out + (int64_t)n * p.H * p.W * kCvC, 0, (int)obytes, 0x00020000);
+    const int opx = (tid >> 3) & 31, opiece = tid & 7, orow0 = tid >> 8;
+    const uint32_t ovoff = (x0 + opx < p.W) ? (uint32_t)(((orow0 * p.W + x0 + opx) * kCvC + 8 * opiece) * 2) : kCvOutside;
+    const char* sread = s_stage + (orow0 * kCvTX + opx) * kCvStagePitch + 16 * opiece;
+    char* swrite = s_stage + (ro * kCvTX + c32) * kCvStagePitch + (32 * j + 4 * h) * 2;
+
     // start-up: rows 0..9 of the first tile (waves 0, 1 take two rows each), the 8 new rows of the second
-    if (wv < 2) cv_request_row(p, n, ys + wv, x0, s_ring, wv, lane);
-    cv_request_row(p, n, ys + 2 + wv, x0, s_ring, 2 + wv, lane);
-    if (len > 1) cv_request_row(p, n, ys + 10 + wv, x0, s_ring, 10 + wv, lane);
+    if (wv < 2) cv_request_row(p, d, n, ys + wv, x0, s_ring, wv, lane);
+    cv_request_row(p, d, n, ys + 2 + wv, x0, s_ring, 2 + wv, lane);
+    if (len > 1) cv_request_row(p, d, n, ys + 10 + wv, x0, s_ring, 10 + wv, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
+    int rb = 0;                                           // ring row of the tile's first row: 8 k mod 26
     for (int k = 0; k < len; ++k) {
         // the rows of tile k + 2 take the ring rows that tile k - 1 has released
         const bool req = k + 2 < len;                     // uniform
-        if (req) cv_request_row(p, n, ys + 8 * k + 18 + wv, x0, s_ring, (8 * k + 18 + wv) % kCvRing, lane);
+        if (req) {
+            int rr2 = rb + 18 + wv;
+            if (rr2 >= kCvRing) rr2 -= kCvRing;
+            cv_request_row(p, d, n, ys + 8 * k + 18 + wv, x0, s_ring, rr2, lane);
+        }
         __builtin_amdgcn_sched_barrier(0);                // the requests go out before the first product
         int row[4];
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) row[rr] = ((8 * k + ro + rr) % kCvRing) * kCvRowBytes;
+        for (int rr = 0; rr < 4; ++rr) {
+            int r = rb + ro + rr;
+            if (r >= kCvRing) r -= kCvRing;
+            row[rr] = r * kCvRowBytes;
+        }
         floatx16 acc[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -226,7 +258,7 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
                 half4 v4;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) v4[r] = (half_t)acc[u][4 * q + r];
-                *reinterpret_cast<half4*>(s_stage + ((ro + u) * kCvTX + c32) * kCvStagePitch + (32 * j + 8 * q + 4 * h) * 2) = v4;
+                *reinterpret_cast<half4*>(swrite + u * (kCvTX * kCvStagePitch) + 16 * q) = v4;
             }
         // Meeting point.  A wave waits for all its memory instructions but the newest request (loads
         // and stores retire in order): its row of the NEXT tile has landed, the previous tile's
@@ -236,18 +268,18 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
         if (req) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next rows complete, this tile's rows released, stage written
-        // stage -> memory: 8 lanes per pixel, 1 KB per store instruction
-        const int y0 = (ty0 + k) * kCvTY;
+        // stage -> memory: 8 lanes per pixel, 1 KB per store instruction; rows below the image fall
+        // behind the end of the descriptor and are dropped
+        const uint32_t osoff = (uint32_t)((ty0 + k) * kCvTY) * (uint32_t)(p.W * kCvC * 2);
 #pragma unroll
         for (int i = 0; i < kCvTY * kCvTX * 8 / kCvThreads; ++i) {
-            const int id = tid + kCvThreads * i;
-            const int orow = id >> 8, px = (id >> 3) & 31, piece = id & 7;
-            const half8 v = *reinterpret_cast<const half8*>(s_stage + (orow * kCvTX + px) * kCvStagePitch + 16 * piece);
-            const int y = y0 + orow, x = x0 + px;
-            if (y < p.H && x < p.W)
-                *reinterpret_cast<half8*>(p.out + (((int64_t)n * p.H + y) * p.W + x) * kCvC + 8 * piece) = v;
+            const half8 v = *reinterpret_cast<const half8*>(sread + 2 * i * (kCvTX * kCvStagePitch));
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4s, v), orsrc, ovoff,
+                                                   osoff + (uint32_t)(2 * i) * (uint32_t)(p.W * kCvC * 2), 0);
         }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // stage read, free for the next tile
+        rb += 8;
+        if (rb >= kCvRing) rb -= kCvRing;
     }
 }
 
@@ -315,6 +347,7 @@ static hb_status conv_prepare(ConvArgs& a, const hb_half* in, const hb_half* w, 
     if (Cin != kCvC || Cout != kCvC) return HB_ERR_UNSUPPORTED;
     const int64_t tiles = (int64_t)N * ceil_div(H, kCvTY) * ceil_div(W, kCvTX);
     if (tiles > 0x7fffffff || (int64_t)N * H * W > ((int64_t)1 << 40)) return HB_ERR_UNSUPPORTED;
+    if ((int64_t)H * W * kCvC * 2 >= ((int64_t)1 << 31)) return HB_ERR_UNSUPPORTED;   // 32-bit offsets inside an image
     a.in = reinterpret_cast<const half_t*>(in);
     a.w = reinterpret_cast<const half_t*>(w);
     a.out = reinterpret_cast<half_t*>(out);
