@@ -14,10 +14,12 @@
  *    are read during the call and travel to the GPU inside the kernel arguments,
  *    so the caller may free or change them as soon as the call returns.
  *  - Single-channel images are row-major; pitches are in ELEMENTS (not bytes) and
- *    must be >= the width.  Any H, W >= 1 is computed correctly.  The vectorised
- *    path needs 16-byte aligned base pointers, input pitches that are multiples of
- *    8 and output pitches that are multiples of 4; other layouts take a slower
- *    element-wise path inside the same kernels.
+ *    must be >= the width (at most 2^26).  Any H, W >= 1 is computed correctly.
+ *    Base pointers need the alignment of their element type only (2 bytes for fp16,
+ *    4 for fp32); the kernels run fastest when fp16 base pointers and pitches are
+ *    multiples of 4 bytes and fp32 ones multiples of 16 bytes (torch allocations
+ *    and even pitches are).  Images narrower than one window of the matrix
+ *    formulation (32 to 96 pixels, depending on the taps) run the vector-ALU kernel.
  *  - Orientation is correlation, as the paper prints it: O(x) = sum_r I(x + r) K(r).
  *    `anchor` shifts the window, tap r reads x + r - anchor; anchor = 0 is the
  *    paper's formula verbatim.  Output has the size of the input; out-of-range
@@ -118,7 +120,8 @@ hb_status hb_sat2d_valu(const hb_half *in, float *out, int H, int W,
  *     out[n][y][x][co] = sum_{ky,kx < 3} sum_ci in[n][y+ky-1][x+kx-1][ci] * w[ky][kx][ci][co]
  * in: N x H x W x Cin fp16 (NHWC, dense), w: 3 x 3 x Cin x Cout fp16 (HWIO, dense),
  * out: N x H x W x Cout fp16 (fp32 accumulator rounded to nearest even).
- * Cin and Cout must both be 64 (HB_ERR_UNSUPPORTED otherwise); pointers 16-byte aligned.
+ * Cin and Cout must both be 64 (HB_ERR_UNSUPPORTED otherwise); pointers 16-byte aligned;
+ * one image at most 2 GiB (H * W < 2^24 pixels; HB_ERR_UNSUPPORTED beyond).
  */
 hb_status hb_conv3x3(const hb_half *in_nhwc, const hb_half *w_hwio, hb_half *out_nhwc,
                      int N, int H, int W, int Cin, int Cout, hb_stream stream);

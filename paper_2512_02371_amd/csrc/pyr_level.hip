@@ -644,7 +644,9 @@ static hb_status pyr_prepare(PyrArgs& a, const hb_half* in, float* res, hb_half*
     // a task's footprint must stay below 2 GiB from its first row (32-bit buffer offsets)
     const int64_t rowbytes = in_pitch * 2 > res_pitch * 4 ? in_pitch * 2 : res_pitch * 4;
     const int64_t maxrows = (((int64_t)1 << 31) - 1) / rowbytes;
-    if (maxrows < 2 * 32 + 64 || a.nci <= 0 || a.r1 <= a.r0) {     // no interior: everything is "top"
+    // the interior path reads with 16-byte buffer loads: rows must start on 4-byte boundaries
+    const bool dword_rows = (in_pitch % 2 == 0) && (reinterpret_cast<uintptr_t>(in) % 4 == 0);
+    if (!dword_rows || maxrows < 2 * 32 + 64 || a.nci <= 0 || a.r1 <= a.r0) {   // no interior: everything is "top"
         a.nci = 0;
         a.nbl = a.bR = a.nblk;
         a.r0 = a.r1 = a.rowsteps;

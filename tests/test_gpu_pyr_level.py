@@ -43,6 +43,17 @@ def test_pyr_without_down_and_with_pitch(orc, fn):
     assert np.all(down == 0), "down written although not requested"
 
 
+@pytest.mark.parametrize("pitch_extra", [5, 8])
+def test_pyr_pitched_image_with_interior_tasks(orc, pitch_extra):
+    """Large enough for interior tasks; an odd pitch puts every second row on a 2-byte boundary."""
+    H, W = 130, 300
+    img, res, down, rbuf, dbuf = run("hb_pyr_level", H, W, True, pitch_extra=pitch_extra, seed=3)
+    ref, dref = orc.pyr_level(img, want_down=True)
+    assert_close(res, ref, f"pitched +{pitch_extra} residual")
+    assert_close(down.astype(np.float64), dref, f"pitched +{pitch_extra} down")
+    assert np.all(rbuf[:, W:] == 7.0), "stray writes beyond the row"
+
+
 @pytest.mark.parametrize("fn", ["hb_pyr_level", "hb_pyr_level_valu"])
 def test_pyr_constant_image_has_zero_residual(fn):
     import torch
