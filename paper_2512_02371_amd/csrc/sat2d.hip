@@ -101,42 +101,48 @@ __global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
                 X[rt][blk] = load8_zero(p.in, p.in_pitch, y0 + 16 * rt + c, x0 + 32 * blk + 8 * g, p.H, p.W);
     }
 
-    floatx4 rowsum[4];
-    half4 T[4][2][2];                                     // pixel copies in accumulator layout
+    // Row tiles in pairs: row sums (X * 1), pixel copies in accumulator layout (X * [I|0], X * [0|I]),
+    // whose stacked pairs times the all-ones matrix add up the column sums.
+    floatx4 colsum[2][2];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
-        rowsum[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            rowsum[rt] = mfma16x16x32(X[rt][blk], one, rowsum[rt]);          // [m = row][n]: row totals in every column
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                floatx4 t = {0.f, 0.f, 0.f, 0.f};
-                T[rt][blk][h] = to_half4(mfma16x16x32(X[rt][blk], sel[h], t)); // [m = row][n = column]: lane c = column
-            }
-        }
-    }
-    // row sums: lane (c, g) holds rows 4g + v, the same in every c; lane c = v writes row 4g + v
+        for (int h = 0; h < 2; ++h) colsum[blk][h] = floatx4{0.f, 0.f, 0.f, 0.f};
     float tile_total = 0.f;
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
+    for (int rp = 0; rp < 2; ++rp) {
+        half4 T[2][2][2];                                 // pixel copies of row tiles 2 rp, 2 rp + 1
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            if (c == v) p.rs[(int64_t)(y0 + 16 * rt + 4 * g + v) * p.nb + b] = rowsum[rt][v];
-            if (c == 0) tile_total += rowsum[rt][v];
+        for (int u = 0; u < 2; ++u) {
+            const int rt = 2 * rp + u;
+            floatx4 rowsum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                rowsum = mfma16x16x32(X[rt][blk], one, rowsum);              // [m = row][n]: row totals in every column
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    floatx4 t = {0.f, 0.f, 0.f, 0.f};
+                    T[u][blk][h] = to_half4(mfma16x16x32(X[rt][blk], sel[h], t));   // [m = row][n = column]
+                }
+            }
+            // lane (c, g) holds the sums of rows 4g + v, the same in every c: lanes c < 4 write row 4g + c
+            const float mine = c == 0 ? rowsum[0] : c == 1 ? rowsum[1] : c == 2 ? rowsum[2] : rowsum[3];
+            if (c < 4) p.rs[(int64_t)(y0 + 16 * rt + 4 * g + c) * p.nb + b] = mine;
+            tile_total += rowsum[0] + rowsum[1] + rowsum[2] + rowsum[3];     // used from lanes c = 0 only
         }
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                colsum[blk][h] = mfma16x16x32(join(T[0][blk][h], T[1][blk][h]), one, colsum[blk][h]);   // [m = column][n]
     }
-    // column sums: contract the stacked row tiles with the all-ones matrix
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            floatx4 cs = {0.f, 0.f, 0.f, 0.f};
-            cs = mfma16x16x32(join(T[0][blk][h], T[1][blk][h]), one, cs);   // [m = column][n]
-            cs = mfma16x16x32(join(T[2][blk][h], T[3][blk][h]), one, cs);
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (c == v) p.cs[(int64_t)(x0 + 32 * blk + 16 * h + 4 * g + v) * p.ns + s] = cs[v];
+            const floatx4 cs = colsum[blk][h];
+            const float mine = c == 0 ? cs[0] : c == 1 ? cs[1] : c == 2 ? cs[2] : cs[3];
+            if (c < 4) p.cs[(int64_t)(x0 + 32 * blk + 16 * h + 4 * g + c) * p.ns + s] = mine;
         }
     // tile total: the four lane groups' partial row-sum totals
     tile_total = (c == 0) ? tile_total : 0.f;
