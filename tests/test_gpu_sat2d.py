@@ -67,3 +67,17 @@ def test_sat_workspace_is_checked():
     with pytest.raises(hb.HbError) as e:
         hb.hb_sat2d(x, out, small)
     assert e.value.code == hb.HB_ERR_WORKSPACE
+
+
+def test_sat_full_benchmark_size(orc):
+    """The benchmark's 4096 x 4096 launch: the uniform image against the oracle (error over the total
+    and per element), and a 0/1 image bit-exactly (all partial sums stay below 2^24)."""
+    img = synth.uniform01_f16(1003, (4096, 4096))
+    got, _ = run("hb_sat2d", img)
+    ref = orc.sat2d(img)
+    assert np.abs(got - ref).max() / ref[-1, -1] <= TOL
+    assert scaled_err(got, ref).max() <= TOL
+    bits = synth.binary01_f16(78, (4096, 4096))
+    got, _ = run("hb_sat2d", bits)
+    ref = np.cumsum(np.cumsum(synth.f16_bits_to_f64(bits), axis=0), axis=1)
+    assert np.array_equal(got.astype(np.float64), ref)

@@ -70,3 +70,22 @@ def test_sepblur_benchmark_shape_rows_sampled_densely(orc, fn):
     getattr(hb, fn)(up(img), out, t, 7, t, 7)
     torch.cuda.synchronize()
     assert_close(out.cpu().numpy(), orc.sepblur(img, t, 7, t, 7), fn)
+
+
+def test_sepblur_full_benchmark_size_sampled_bands(orc):
+    """The benchmark's 4096 x 4096 launch, checked on row bands: the oracle runs on a crop with 16
+    rows of margin (more than the 15-row reach of the column pass), whose inner rows do not see the crop."""
+    import torch
+    from paper_2512_02371_amd import hb
+    H = W = 4096
+    img = synth.uniform01_f16(1002, (H, W))
+    t = synth.gaussian_taps_f16(16, 3.0)
+    out = torch.zeros((H, W), dtype=torch.float32, device="cuda:0")
+    print(f"hb_sepblur {H}x{W}", flush=True)
+    hb.hb_sepblur(up(img), out, t, 7, t, 7)
+    torch.cuda.synchronize()
+    for y0 in (0, 48, 1000, 2047, 3333, H - 80):
+        lo, hi = max(y0 - 16, 0), min(y0 + 80 + 16, H)
+        ref = orc.sepblur(img[lo:hi], t, 7, t, 7)
+        a, b = (0 if lo == 0 else 16), (hi - lo if hi == H else hi - lo - 16)
+        assert_close(out[lo + a:lo + b].cpu().numpy(), ref[a:b], f"rows {lo + a}..{lo + b}")
