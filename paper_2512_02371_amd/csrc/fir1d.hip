@@ -98,13 +98,10 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
                     for (int kk = 0; kk < NK; ++kk) acc[w] = mfma16x16x32(coef[kk], cur[w][kk], acc[w]);
                 }
                 const int y0 = Y0 + 16 * q;
-#ifndef HB_DIRECT_STORES
                 if (y0 + 16 <= p.H) {
                     store_rows_via_lds<NW, STREAM>(s_patch[threadIdx.x >> 6], dst + (int64_t)y0 * p.out_pitch,
                                                    (uint32_t)p.out_pitch, acc, lane);
-                } else
-#endif
-                if (y0 + c < p.H) {
+                } else if (y0 + c < p.H) {
                     const uint32_t off = ((uint32_t)(y0 + c) * (uint32_t)p.out_pitch + 4u * g) * 4u;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);

@@ -24,9 +24,9 @@
 // loaded operand fragments are parked in a wave-private LDS ring and come back, three tiles
 // later, as the B operand of a 0/1 selection product that seeds the accumulator of the last
 // pass with the original pixels: the residual in - U then needs no second read of the image
-// and no separate subtraction (the up-x pass stores -U1).  Image tiles are requested
-// HB_PYR_PD tiles ahead into a register ring (the loop is unrolled over the ring, so no copy
-// waits on a load in flight).
+// and no separate subtraction (the up-x pass stores -U1).  Image tiles are requested three
+// tiles ahead into a register ring (the loop is unrolled over the ring, so no copy waits on a
+// load in flight).
 //
 // At the image border (pyr_task) the up passes clamp the D index; there the coefficient
 // fragments are rebuilt from absolute indices (taps that clamp onto the same D sample
@@ -41,9 +41,6 @@
 #endif
 #ifndef HB_PYR_WAVES
 #define HB_PYR_WAVES 5400     // aim for about this many interior wave tasks per launch
-#endif
-#ifndef HB_PYR_PD
-#define HB_PYR_PD 3           // image row tiles requested ahead of the one being consumed
 #endif
 
 namespace hb {
@@ -479,11 +476,7 @@ __global__ void __launch_bounds__(256, 2) pyr_mfma_kernel(PyrArgs p) {
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2 * NS>::kFloats];
     __shared__ __attribute__((aligned(16))) char s_stash[4][PyrStash<NS>::kBytes];
 
-#ifdef HB_NO_XCD_MAP
-    const int wgpos = blockIdx.x;
-#else
     const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
-#endif
     const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     const int ntasks = p.count();

@@ -148,7 +148,6 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fol
                     acc[w] = mfma16x16x32(join(lo, hi), coefy[j], acc[w]);
                 }
             }
-#ifndef HB_DIRECT_STORES
             if (XIN) {
                 if (Y0 + 16 * s + 16 <= p.H) {
                     store_rows_via_lds<NW, STREAM>(patch, dst + (int64_t)(Y0 + 16 * s) * p.out_pitch,
@@ -158,22 +157,12 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fol
 #pragma unroll
                     for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
                 }
-            }
-#endif
-            if (yo < p.H) {
-                if (XIN) {
-#ifdef HB_DIRECT_STORES
-                    const uint32_t off = ((uint32_t)yo * (uint32_t)p.out_pitch + 4u * g) * 4u;
+            } else if (yo < p.H) {
+                float* orow = p.out + (int64_t)yo * p.out_pitch;
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
-#endif
-                } else {
-                    float* orow = p.out + (int64_t)yo * p.out_pitch;
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) {
-                        const int xo = x0 + 16 * w + 4 * g;
-                        if (xo < p.W) store4_mask(orow, xo, p.W, acc[w]);
-                    }
+                for (int w = 0; w < NW; ++w) {
+                    const int xo = x0 + 16 * w + 4 * g;
+                    if (xo < p.W) store4_mask(orow, xo, p.W, acc[w]);
                 }
             }
         }
@@ -204,11 +193,7 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) coefy[j][i] = tap_at(p.ty.tab, 32 * j + krow32(g, i) - c);
 
-#ifdef HB_NO_XCD_MAP
-    const int wgpos = blockIdx.x;
-#else
     const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
-#endif
     const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     const int ntasks = p.grid.count();
