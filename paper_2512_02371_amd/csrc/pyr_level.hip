@@ -673,9 +673,7 @@ extern "C" hb_status hb_pyr_level(const hb_half* in, float* residual, hb_half* d
         return hb_pyr_level_valu(in, residual, down_or_null, H, W, in_pitch, res_pitch, down_pitch, stream);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const dim3 grid(min(ceil_div(a.count(), 4), kMaxStreamBlocks));
-    // (measured on this kernel: streaming stores win at every output size, also beyond the 128 MB
-    // where the other stages switch to plain stores)
-    const bool stream_stores = true;
+    const bool stream_stores = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
     if (a.down) {
         if (stream_stores) hipLaunchKernelGGL((pyr_mfma_kernel<true, true>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((pyr_mfma_kernel<false, true>), grid, dim3(256), 0, st, a);
