@@ -183,31 +183,44 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     const int x0 = cx * kCvTX;
     const int ys = ty0 * kCvTY - 1;                       // image row held by ring row 0 at the start
 
+    const CvRowOff d = cv_row_offsets(p, x0, lane);
+
+    // start-up, part 1: rows 0..9 of the first tile go out before anything else (waves 0, 1 take two
+    // rows each) and land in ring rows 0..9 while the weights are staged
+    if (wv < 2) cv_request_row(p, d, n, ys + wv, x0, s_ring, wv, lane);
+    cv_request_row(p, d, n, ys + 2 + wv, x0, s_ring, 2 + wv, lane);
+
     // coefficient fragments: wf[s] lane (c32, h) = w[tap][16 kc + 8h + i][32 j + c32], s = 4 tap + kc.
     // The weights arrive with the output channel innermost; a fragment wants eight consecutive INPUT
-    // channels per lane.  They pass through the (still empty) ring once, transposed on the way in:
-    // coalesced 16-byte reads of eight output channels, 2-byte writes to [tap][co][ci] with a
-    // 144-byte pitch per (tap, co), so that each fragment is one conflict-free 16-byte read.
+    // channels per lane.  They pass through LDS once, transposed on the way in: coalesced 16-byte
+    // reads of eight output channels, 2-byte writes to [tap][co][ci] with a 144-byte pitch per
+    // (tap, co), so that each fragment is one conflict-free 16-byte read.  Taps 0..6 use ring rows
+    // 10..25 (free until the second tile's rows are requested), taps 7, 8 the output stage.
     half8 wf[36];
     {
         constexpr int kWPitch = 144;                      // bytes per (tap, output channel): 64 ci + pad
-        static_assert(9 * kCvC * kWPitch <= kCvRingBytes, "the transposed weights must fit the ring");
+        constexpr int kWTap = kCvC * kWPitch;             // 9216 bytes per tap
+        constexpr int kTapsInRing = 7;
+        static_assert(kTapsInRing * kWTap <= (kCvRing - 10) * kCvRowBytes, "taps 0..6 must fit ring rows 10..25");
+        static_assert((9 - kTapsInRing) * kWTap <= kCvStageBytes, "taps 7, 8 must fit the output stage");
+        char* const wring = s_ring + 10 * kCvRowBytes;
         for (int i = tid; i < 9 * kCvC * kCvC / 8; i += kCvThreads) {
             const half8 v = reinterpret_cast<const half8*>(p.w)[i];          // w[tap][ci][8 cog .. 8 cog + 7]
             const int cog = i & 7, ci = (i >> 3) & 63, tap = i >> 9;
+            char* dst = (tap < kTapsInRing ? wring + tap * kWTap : s_stage + (tap - kTapsInRing) * kWTap) +
+                        8 * cog * kWPitch + 2 * ci;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                *reinterpret_cast<half_t*>(s_ring + (tap * kCvC + 8 * cog + e) * kWPitch + 2 * ci) = v[e];
+            for (int e = 0; e < 8; ++e) *reinterpret_cast<half_t*>(dst + e * kWPitch) = v[e];
         }
         __syncthreads();
 #pragma unroll
-        for (int s = 0; s < 36; ++s)
-            wf[s] = *reinterpret_cast<const half8*>(s_ring + ((s >> 2) * kCvC + 32 * j + c32) * kWPitch +
-                                                    2 * (16 * (s & 3) + 8 * h));
+        for (int s = 0; s < 36; ++s) {
+            const int tap = s >> 2;
+            const char* src = tap < kTapsInRing ? wring + tap * kWTap : s_stage + (tap - kTapsInRing) * kWTap;
+            wf[s] = *reinterpret_cast<const half8*>(src + (32 * j + c32) * kWPitch + 2 * (16 * (s & 3) + 8 * h));
+        }
         __syncthreads();
     }
-
-    const CvRowOff d = cv_row_offsets(p, x0, lane);
 
     // output: a descriptor over image n; thread t stores pieces t, t + 512, ... of the 8 x 32 x 8 pieces
     // of a tile (8 lanes per pixel): row (t >> 8) + 2 i, pixel (t >> 3) & 31, piece t & 7
@@ -219,9 +232,7 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     const char* sread = s_stage + (orow0 * kCvTX + opx) * kCvStagePitch + 16 * opiece;
     char* swrite = s_stage + (ro * kCvTX + c32) * kCvStagePitch + (32 * j + 4 * h) * 2;
 
-    // start-up: rows 0..9 of the first tile (waves 0, 1 take two rows each), the 8 new rows of the second
-    if (wv < 2) cv_request_row(p, d, n, ys + wv, x0, s_ring, wv, lane);
-    cv_request_row(p, d, n, ys + 2 + wv, x0, s_ring, 2 + wv, lane);
+    // start-up, part 2: the 8 new rows of the second tile, now that ring rows 10..17 are free
     if (len > 1) cv_request_row(p, d, n, ys + 10 + wv, x0, s_ring, 10 + wv, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
