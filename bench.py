@@ -7,7 +7,7 @@ hb_pyr_level 8192x8192) on seeded synthetic inputs that are already resident in 
 Buffers rotate between steps so that no input or output is reused before more than the
 256 MB memory-side cache has gone past.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--variant mfma|valu] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--variant mfma|valu] [--no-cpu] [--no-extra]
 
 prints ONE JSON line: aggregate Gpixels/s of the step (wall clock over the K timed steps), per-stage
 Gpixels/s with each stage's roofline fraction (HIP events around every stage, in an instrumented
@@ -70,6 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary stacked FIR run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -201,26 +202,27 @@ def main():
         "roofline": roofline,
     }
 
-    # Supplementary (outside the step): the FIR stage on 1024 of its 256 x 256 images stacked into
-    # one 262144 x 256 image, where its launch latency no longer hides its bandwidth.
-    del ins["pyr_level"], outs["pyr_level"], ins["conv3x3"], outs["conv3x3"]
-    torch.cuda.empty_cache()
-    Hs = 256 * 1024
-    sx = [up(host["fir1d"]).repeat(1024, 1) for _ in range(2)]
-    so = [torch.empty((Hs, 256), dtype=torch.float32, device=dev) for _ in range(2)]
-    fir = getattr(hb, "hb_fir1d" + sfx)
-    for i in range(4):
-        fir(sx[i % 2], so[i % 2], fir_taps, 3)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(10):
-        fir(sx[i % 2], so[i % 2], fir_taps, 3)
-    e1.record()
-    torch.cuda.synchronize()
-    sms = e0.elapsed_time(e1) / 10
-    out["supplementary"] = {"fir1d_stacked_262144x256": {
-        "ms": sms, "gpixels_per_s": Hs * 256 / sms / 1e6, "achieved": Hs * 256 * 6 / sms / 1e6,
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": Hs * 256 * 6 / sms / 1e6 / HBM_PEAK_GBS}}
+    if not args.no_extra:
+        # Supplementary (outside the step): the FIR stage on 1024 of its 256 x 256 images stacked into
+        # one 262144 x 256 image, where its launch latency no longer hides its bandwidth.
+        del ins["pyr_level"], outs["pyr_level"], ins["conv3x3"], outs["conv3x3"]
+        torch.cuda.empty_cache()
+        Hs = 256 * 1024
+        sx = [up(host["fir1d"]).repeat(1024, 1) for _ in range(2)]
+        so = [torch.empty((Hs, 256), dtype=torch.float32, device=dev) for _ in range(2)]
+        fir = getattr(hb, "hb_fir1d" + sfx)
+        for i in range(4):
+            fir(sx[i % 2], so[i % 2], fir_taps, 3)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(10):
+            fir(sx[i % 2], so[i % 2], fir_taps, 3)
+        e1.record()
+        torch.cuda.synchronize()
+        sms = e0.elapsed_time(e1) / 10
+        out["supplementary"] = {"fir1d_stacked_262144x256": {
+            "ms": sms, "gpixels_per_s": Hs * 256 / sms / 1e6, "achieved": Hs * 256 * 6 / sms / 1e6,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": Hs * 256 * 6 / sms / 1e6 / HBM_PEAK_GBS}}
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)
