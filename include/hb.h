@@ -14,7 +14,9 @@
  *    are read during the call and travel to the GPU inside the kernel arguments,
  *    so the caller may free or change them as soon as the call returns.
  *  - Single-channel images are row-major; pitches are in ELEMENTS (not bytes) and
- *    must be >= the width (at most 2^26).  Any H, W >= 1 is computed correctly.
+ *    must be >= the width (at most 2^26; hb_fir1d and hb_sepblur also want
+ *    H * in_pitch < 2^31 and H * out_pitch < 2^30, HB_ERR_UNSUPPORTED beyond).
+ *    Any H, W >= 1 is computed correctly.
  *    Base pointers need the alignment of their element type only (2 bytes for fp16,
  *    4 for fp32); the kernels run fastest when fp16 base pointers and pitches are
  *    multiples of 4 bytes and fp32 ones multiples of 16 bytes (torch allocations

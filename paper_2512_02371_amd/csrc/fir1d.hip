@@ -199,6 +199,8 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
                                const hb_half* taps_host, int ntaps, int anchor) {
     hb_status s = check_image(in, out, H, W, in_pitch, out_pitch);
     if (s != HB_OK) return s;
+    // lanes address rows with 32-bit byte offsets from the image base
+    if ((int64_t)H * in_pitch >= ((int64_t)1 << 31) || (int64_t)H * out_pitch >= ((int64_t)1 << 30)) return HB_ERR_UNSUPPORTED;
     s = check_taps(taps_host, ntaps, anchor);
     if (s != HB_OK) return s;
     a.in = reinterpret_cast<const half_t*>(in);

@@ -272,6 +272,8 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
                              const hb_half* tx, int ntx, int ax, const hb_half* ty, int nty, int ay) {
     hb_status s = check_image(in, out, H, W, in_pitch, out_pitch);
     if (s != HB_OK) return s;
+    // lanes address rows with 32-bit byte offsets from the image base
+    if ((int64_t)H * in_pitch >= ((int64_t)1 << 31) || (int64_t)H * out_pitch >= ((int64_t)1 << 30)) return HB_ERR_UNSUPPORTED;
     if ((s = check_taps(tx, ntx, ax)) != HB_OK) return s;
     if ((s = check_taps(ty, nty, ay)) != HB_OK) return s;
     a.in = reinterpret_cast<const half_t*>(in);

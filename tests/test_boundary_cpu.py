@@ -69,3 +69,15 @@ def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(ctypes.c_void_p(0x1004), FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_mfma_probe(4, FAKE, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_mfma_probe(0, None, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
+
+
+def test_size_limits_are_reported_not_wrapped(lib):
+    """Sizes beyond the 32-bit offsets the kernels use come back as HB_ERR_UNSUPPORTED."""
+    big = dict(H=1 << 20, W=16, ip=1 << 12, op=1 << 12)          # H * pitch = 2^32 elements
+    assert lib.hb_fir1d(FAKE, FAKE, big["H"], big["W"], big["ip"], big["op"], TAPS, 8, 3, None) == hb.HB_ERR_UNSUPPORTED
+    assert lib.hb_sepblur(FAKE, FAKE, big["H"], big["W"], big["ip"], big["op"], TAPS, 8, 3, TAPS, 8, 3,
+                          None) == hb.HB_ERR_UNSUPPORTED
+    assert lib.hb_fir1d(FAKE, FAKE, 16, 16, (1 << 26) + 8, 16, TAPS, 8, 3, None) == hb.HB_ERR_UNSUPPORTED
+    # one conv image of 2^24 pixels or more (2 GiB of fp16 x 64 channels)
+    assert lib.hb_conv3x3(FAKE, FAKE, FAKE, 1, 4096, 4096, 64, 64, None) == hb.HB_ERR_UNSUPPORTED
+    assert lib.hb_conv3x3(FAKE, FAKE, FAKE, 1, 4096, 4095, 64, 32, None) == hb.HB_ERR_UNSUPPORTED
