@@ -62,7 +62,8 @@ typedef enum {
 typedef uint16_t hb_half;
 typedef void *hb_stream;      /* hipStream_t */
 
-#define HB_MAX_TAPS 64
+#define HB_MAX_TAPS 64          /* per axis, hb_sepblur */
+#define HB_MAX_TAPS_FIR1D 256   /* hb_fir1d: the large-tap regime of Sec. V-A */
 
 /* Human-readable name of a status code (static storage). */
 const char *hb_status_string(hb_status s);
@@ -71,7 +72,7 @@ const char *hb_status_string(hb_status s);
  * Row-wise 1-D FIR (Sec. V-A, 1-D convolution as a product with the Toeplitz
  * matrix A_K(x, y) = K(y - x)):
  *     out[y][x] = sum_{r < ntaps} taps[r] * in[y][clampW(x + r - anchor)]
- * in: H x W fp16, out: H x W fp32.  1 <= ntaps <= HB_MAX_TAPS, 0 <= anchor < ntaps.
+ * in: H x W fp16, out: H x W fp32.  1 <= ntaps <= HB_MAX_TAPS_FIR1D, 0 <= anchor < ntaps.
  */
 hb_status hb_fir1d(const hb_half *in, float *out, int H, int W,
                    int64_t in_pitch, int64_t out_pitch,

@@ -21,11 +21,15 @@
 #include "hb_host.hpp"
 
 #ifndef HB_FIR_TILES
-#define HB_FIR_TILES 4        // 16-column tiles per wave strip
+#define HB_FIR_TILES 4        // 16-column tiles per wave strip (fewer for long filters, see fir_tiles)
 #endif
 #ifndef HB_FIR_WAVES
 #define HB_FIR_WAVES (1 << 20) // wave tasks per launch before a task takes more than one 16-row step;
                               // rows are independent here, so short-lived waves stream best
+#endif
+
+#ifndef HB_FIR_LONG_WAVES
+#define HB_FIR_LONG_WAVES 4096 // the same for filters of more than 80 taps (four or more windows per tile)
 #endif
 
 namespace hb {
@@ -39,9 +43,12 @@ struct FirArgs {
     int nct;             // strips per row group
     int steps;           // 16-row steps per task
     int ntasks;          // strips x row segments
-    Taps taps;
-    FoldTables fold;
+    TapsT<HB_MAX_TAPS_FIR1D> taps;
+    FoldTablesT<HB_MAX_TAPS_FIR1D> fold;
 };
+
+// Tiles per wave strip: a strip keeps 2 x tiles x NK window fragments in registers.
+constexpr int fir_tiles(int nk) { return nk <= 3 ? HB_FIR_TILES : nk <= 6 ? 2 : 1; }
 
 __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
     return __builtin_bit_cast(half_t, b);
@@ -51,7 +58,7 @@ __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
 // the next step are requested before the current step is multiplied.
 template <int NK, bool STREAM>
 __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
-    constexpr int NW = HB_FIR_TILES;
+    constexpr int NW = fir_tiles(NK);
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<NW>::kFloats];
 
     const int lane = threadIdx.x & 63;
@@ -150,13 +157,14 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
 // Vector-ALU twin: a 16 x 256 tile is staged in LDS with its halo, every thread
 // slides the taps over 4 x 4 outputs with fp32 FMAs.
 constexpr int kValuTileW = 256;
-constexpr int kValuMaxChunks = (kValuTileW + 64 + 64) / 8;   // tile + left slack + right halo
+constexpr int kValuMaxChunks = (kValuTileW + HB_MAX_TAPS_FIR1D + HB_MAX_TAPS_FIR1D) / 8;   // tile + left slack + right halo
 constexpr int kValuPitch = kValuMaxChunks * 8 + 8;
 
 __global__ void __launch_bounds__(256) fir1d_valu_kernel(FirArgs p) {
     __shared__ half_t s_px[16 * kValuPitch];
-    __shared__ float s_k[HB_MAX_TAPS];
-    if (threadIdx.x < HB_MAX_TAPS) s_k[threadIdx.x] = (float)tap_at(p.taps.tab, threadIdx.x);
+    __shared__ float s_k[HB_MAX_TAPS_FIR1D];
+    static_assert(HB_MAX_TAPS_FIR1D <= 256, "one tap per thread");
+    if (threadIdx.x < HB_MAX_TAPS_FIR1D) s_k[threadIdx.x] = (float)tap_at(p.taps.tab, threadIdx.x);
 
     const int nctv = (p.W + kValuTileW - 1) / kValuTileW;
     const int rg = blockIdx.x / nctv, ct = blockIdx.x - rg * nctv;
@@ -201,7 +209,7 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
     if (s != HB_OK) return s;
     // lanes address rows with 32-bit byte offsets from the image base
     if ((int64_t)H * in_pitch >= ((int64_t)1 << 31) || (int64_t)H * out_pitch >= ((int64_t)1 << 30)) return HB_ERR_UNSUPPORTED;
-    s = check_taps(taps_host, ntaps, anchor);
+    s = check_taps(taps_host, ntaps, anchor, HB_MAX_TAPS_FIR1D);
     if (s != HB_OK) return s;
     a.in = reinterpret_cast<const half_t*>(in);
     a.out = out;
@@ -211,13 +219,17 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
     a.out_pitch = out_pitch;
     a.T = ntaps;
     a.anchor = anchor;
-    a.nct = ceil_div(W, 16 * HB_FIR_TILES);
+    const int nk = ceil_div(15 + ntaps + (anchor & 1), 32);
+    a.nct = ceil_div(W, 16 * fir_tiles(nk));
     const int rowsteps = ceil_div(H, 16);
-    int steps = (int)(((int64_t)rowsteps * a.nct + HB_FIR_WAVES - 1) / HB_FIR_WAVES);
+    // long filters are bound by the latency of one step, not by bandwidth: their waves take several
+    // steps each, with the next step's windows in flight during the products
+    const int64_t waves = nk <= 3 ? (int64_t)HB_FIR_WAVES : HB_FIR_LONG_WAVES;
+    int steps = (int)(((int64_t)rowsteps * a.nct + waves - 1) / waves);
     a.steps = steps < 1 ? 1 : steps;
     a.ntasks = ceil_div(rowsteps, a.steps) * a.nct;
-    a.taps = pack_taps(taps_host, ntaps);
-    a.fold = pack_fold_tables(taps_host, ntaps);
+    a.taps = pack_taps<HB_MAX_TAPS_FIR1D>(taps_host, ntaps);
+    a.fold = pack_fold_tables<HB_MAX_TAPS_FIR1D>(taps_host, ntaps);
     return HB_OK;
 }
 
@@ -242,16 +254,18 @@ extern "C" hb_status hb_fir1d(const hb_half* in, float* out, int H, int W,
     const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
-    if (nk < 1 || nk > 3) return HB_ERR_UNSUPPORTED;
-    if (ss) {
-        if (nk == 1) hipLaunchKernelGGL((fir1d_mfma_kernel<1, true>), dim3(blocks), dim3(256), 0, st, a);
-        if (nk == 2) hipLaunchKernelGGL((fir1d_mfma_kernel<2, true>), dim3(blocks), dim3(256), 0, st, a);
-        if (nk == 3) hipLaunchKernelGGL((fir1d_mfma_kernel<3, true>), dim3(blocks), dim3(256), 0, st, a);
-    } else {
-        if (nk == 1) hipLaunchKernelGGL((fir1d_mfma_kernel<1, false>), dim3(blocks), dim3(256), 0, st, a);
-        if (nk == 2) hipLaunchKernelGGL((fir1d_mfma_kernel<2, false>), dim3(blocks), dim3(256), 0, st, a);
-        if (nk == 3) hipLaunchKernelGGL((fir1d_mfma_kernel<3, false>), dim3(blocks), dim3(256), 0, st, a);
+    const dim3 grid(blocks), block(256);
+#define HB_FIR_LAUNCH(N)                                                                          \
+    case N:                                                                                       \
+        if (ss) hipLaunchKernelGGL((fir1d_mfma_kernel<N, true>), grid, block, 0, st, a);          \
+        else hipLaunchKernelGGL((fir1d_mfma_kernel<N, false>), grid, block, 0, st, a);            \
+        break;
+    switch (nk) {
+        HB_FIR_LAUNCH(1) HB_FIR_LAUNCH(2) HB_FIR_LAUNCH(3) HB_FIR_LAUNCH(4) HB_FIR_LAUNCH(5)
+        HB_FIR_LAUNCH(6) HB_FIR_LAUNCH(7) HB_FIR_LAUNCH(8) HB_FIR_LAUNCH(9)
+        default: return HB_ERR_UNSUPPORTED;
     }
+#undef HB_FIR_LAUNCH
     return launch_status();
 }
 

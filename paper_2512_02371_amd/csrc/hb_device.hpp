@@ -181,7 +181,7 @@ __device__ __forceinline__ int xcd_contiguous(int wg, int nwg) {
 }
 
 // Toeplitz fragment = eight consecutive entries of the zero-padded tap table that travels in the
-// kernel arguments (see Taps): one 16-byte load at a 2-byte aligned address.
+// kernel arguments (see TapsT): one 16-byte load at a 2-byte aligned address.
 __device__ __forceinline__ half8 tap_run(const uint16_t* tab, int t0) {
     return *reinterpret_cast<const half8_u*>(tab + kTapPad + t0);
 }
@@ -200,9 +200,10 @@ __device__ __forceinline__ half_t tap_at(const uint16_t* tab, int t) {
 // Sums of fp16 taps are not fp16 numbers, so a folded fragment is carried as hi + lo
 // (two products), which keeps the border as accurate as the interior.
 //
-// Tables (FoldTables, filled on the host): kf[t] = taps as fp32, pfx[i] = sum of taps t < i.
+// Tables (FoldTablesT, filled on the host): kf[t] = taps as fp32, pfx[i] = sum of taps t < i.
 // Weight of pixel u in output x: sum of taps[t] over t with clamp(x + t - anchor, 0, n-1) == u.
-__device__ __forceinline__ float folded_tap(const FoldTables& ft, int ntaps, int anchor, int n, int x, int u) {
+template <class FT>
+__device__ __forceinline__ float folded_tap(const FT& ft, int ntaps, int anchor, int n, int x, int u) {
     float v = 0.f;
     const int t = u - x + anchor;
     if (t >= 0 && t < ntaps) v = ft.kf[t];
@@ -215,7 +216,8 @@ __device__ __forceinline__ float folded_tap(const FoldTables& ft, int ntaps, int
 }
 // Folded fragment (natural slot order: slot 8g + i = window pixel 32*kk + 8g + i) for the 16
 // outputs xbase + c and the window starting at absolute pixel ws.
-__device__ __forceinline__ void folded_fragment(const FoldTables& ft, int ntaps, int anchor, int n,
+template <class FT>
+__device__ __forceinline__ void folded_fragment(const FT& ft, int ntaps, int anchor, int n,
                                                 int xbase, int ws, int kk, int c, int g,
                                                 half8& hi, half8& lo) {
 #pragma unroll

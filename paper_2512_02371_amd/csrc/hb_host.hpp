@@ -11,17 +11,21 @@ namespace hb {
 
 // Filter taps as they travel inside the kernel arguments: a zero-padded fp16 table (entry
 // kTapPad + t holds taps[t] for 0 <= t < ntaps and zero for every other t in
-// [-kTapPad, kTapLen - kTapPad)), from which a Toeplitz fragment is eight consecutive entries,
-// and, for the border tiles, the taps and their running sums in fp32.
+// [-kTapPad, MAXT + 48)), from which a Toeplitz fragment is eight consecutive entries,
+// and, for the border tiles, the taps and their running sums in fp32.  MAXT is the largest tap
+// count of the entry point (hb_fir1d: 256, hb_sepblur: 64 per axis).
 constexpr int kTapPad = 16;
-constexpr int kTapLen = 16 + 64 + 48;
-struct Taps {
-    uint16_t tab[kTapLen];
+template <int MAXT>
+struct TapsT {
+    uint16_t tab[kTapPad + MAXT + 48];
 };
-struct FoldTables {
-    float kf[64];        // taps as fp32, zero beyond ntaps
-    float pfx[65];       // pfx[i] = sum of taps t < i
+template <int MAXT>
+struct FoldTablesT {
+    float kf[MAXT];          // taps as fp32, zero beyond ntaps
+    float pfx[MAXT + 1];     // pfx[i] = sum of taps t < i
 };
+using Taps = TapsT<HB_MAX_TAPS>;
+using FoldTables = FoldTablesT<HB_MAX_TAPS>;
 
 // MI355X: 256 compute units, 4 SIMDs each.  Streaming kernels launch one short-lived
 // wave per task (the dispatcher keeps the memory pipes fed best that way); beyond this
@@ -62,9 +66,9 @@ inline hb_status check_image(const void* in, const void* out, int H, int W,
     return HB_OK;
 }
 
-inline hb_status check_taps(const hb_half* taps, int ntaps, int anchor) {
+inline hb_status check_taps(const hb_half* taps, int ntaps, int anchor, int max_taps = HB_MAX_TAPS) {
     if (!taps) return HB_ERR_INVALID_ARG;
-    if (ntaps < 1 || ntaps > HB_MAX_TAPS) return HB_ERR_INVALID_ARG;
+    if (ntaps < 1 || ntaps > max_taps) return HB_ERR_INVALID_ARG;
     if (anchor < 0 || anchor >= ntaps) return HB_ERR_INVALID_ARG;
     return HB_OK;
 }
@@ -91,18 +95,20 @@ inline float half_bits_to_float(uint16_t h) {
     return out;
 }
 
-inline Taps pack_taps(const hb_half* taps, int ntaps) {
-    Taps t;
+template <int MAXT = HB_MAX_TAPS>
+inline TapsT<MAXT> pack_taps(const hb_half* taps, int ntaps) {
+    TapsT<MAXT> t;
     memset(&t, 0, sizeof(t));
     memcpy(t.tab + kTapPad, taps, sizeof(uint16_t) * (size_t)ntaps);
     return t;
 }
 
-inline FoldTables pack_fold_tables(const hb_half* taps, int ntaps) {
-    FoldTables ft;
+template <int MAXT = HB_MAX_TAPS>
+inline FoldTablesT<MAXT> pack_fold_tables(const hb_half* taps, int ntaps) {
+    FoldTablesT<MAXT> ft;
     memset(&ft, 0, sizeof(ft));
     float run = 0.f;
-    for (int i = 0; i <= 64; ++i) {
+    for (int i = 0; i <= MAXT; ++i) {
         ft.pfx[i] = run;
         if (i < ntaps) {
             ft.kf[i] = half_bits_to_float(taps[i]);

@@ -20,7 +20,8 @@ HB_ERR_INVALID_ARG = 1
 HB_ERR_UNSUPPORTED = 2
 HB_ERR_WORKSPACE = 3
 HB_ERR_HIP = 4
-HB_MAX_TAPS = 64
+HB_MAX_TAPS = 64            # per axis, hb_sepblur
+HB_MAX_TAPS_FIR1D = 256     # hb_fir1d
 
 # every symbol include/hb.h declares
 SYMBOLS = [

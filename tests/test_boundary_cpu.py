@@ -57,7 +57,7 @@ def test_fir_argument_validation(lib, fn):
     assert call(ip=15) == hb.HB_ERR_INVALID_ARG
     assert call(op=8) == hb.HB_ERR_INVALID_ARG
     assert call(n=0) == hb.HB_ERR_INVALID_ARG
-    assert call(n=65) == hb.HB_ERR_INVALID_ARG
+    assert call(n=257) == hb.HB_ERR_INVALID_ARG
     assert call(a=-1) == hb.HB_ERR_INVALID_ARG
     assert call(a=8) == hb.HB_ERR_INVALID_ARG
     assert call(i=ctypes.c_void_p(0x1001)) == hb.HB_ERR_INVALID_ARG

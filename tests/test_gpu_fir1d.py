@@ -15,10 +15,19 @@ CASES = [
     (5, 7, 5, 4),
     (130, 300, 16, 7),       # several tiles plus a ragged tail
     (64, 200, 16, 0),        # the paper's left-anchored form
-    (33, 129, 64, 63),       # maximum taps, rightmost anchor
+    (33, 129, 64, 63),
     (33, 129, 64, 0),
     (48, 96, 33, 16),
     (16, 70, 17, 1),
+    # the large-tap regime: 4 to 9 windows of 32 pixels per tile, fewer tiles per strip
+    (40, 700, 100, 50),
+    (40, 700, 128, 0),
+    (33, 640, 129, 128),
+    (20, 1000, 200, 99),
+    (48, 1200, 256, 127),    # maximum taps
+    (17, 600, 256, 255),     # rightmost anchor
+    (17, 600, 256, 0),
+    (9, 250, 256, 100),      # narrower than one window: falls to the vector-ALU kernel
 ]
 
 
@@ -53,6 +62,12 @@ def test_fir1d_pitched_and_misaligned_layouts(orc, fn, extra, offset):
     img, taps, got, obuf = run(fn, H, W, T, a, pitch_extra=extra, offset=offset)
     assert_close(got, orc.fir1d(img, taps, a), f"{fn} pitch+{extra} off {offset}")
     assert np.all(obuf[:, W:] == 7.0), "wrote past the row end"
+
+
+def test_fir1d_long_filter_at_blur_size(orc):
+    """256 taps on a 512-row slab of a 4096-wide image (the width of the blur benchmark)."""
+    img, taps, got, _ = run("hb_fir1d", 512, 4096, 256, 127, seed=9)
+    assert_close(got, orc.fir1d(img, taps, 127), "256 taps, 512 x 4096")
 
 
 @pytest.mark.parametrize("fn", ["hb_fir1d", "hb_fir1d_valu"])
