@@ -47,6 +47,8 @@ def _load():
         L.hbo_set_num_threads.argtypes = [I]
         L.hbo_fir1d.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I]
         L.hbo_sepblur.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, u16p, I, I]
+        L.hbo_conv2d.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, I, I]
+        L.hbo_conv2d.restype = None
         L.hbo_sat2d.argtypes = [u16p, f64p, I, I, Lg, Lg]
         L.hbo_conv3x3.argtypes = [u16p, u16p, f64p, I, I, I, I, I]
         L.hbo_conv3x3_rows.argtypes = [u16p, u16p, f64p, I, I, I, I, I, I, I]
@@ -87,6 +89,18 @@ def fir1d(img, taps, anchor):
     H, W = img.shape
     out = np.empty((H, W), dtype=np.float64)
     _load().hbo_fir1d(pi, _f64(out), H, W, W, W, pt, len(taps), int(anchor))
+    return out
+
+
+def conv2d(img, taps2d, anchor_y, anchor_x):
+    """out[y][x] = sum_{ry, rx} k[ry][rx] in[clampH(y + ry - ay)][clampW(x + rx - ax)]  (Sec. V-A 2-D form)."""
+    img, pi = _u16(img)
+    k = np.ascontiguousarray(taps2d)
+    assert k.ndim == 2
+    k, pk = _u16(k)
+    H, W = img.shape
+    out = np.empty((H, W), dtype=np.float64)
+    _load().hbo_conv2d(pi, _f64(out), H, W, W, W, pk, k.shape[0], k.shape[1], int(anchor_y), int(anchor_x))
     return out
 
 

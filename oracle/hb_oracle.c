@@ -119,6 +119,37 @@ void hbo_fir1d(const uint16_t *in, double *out, int H, int W,
     free(img);
 }
 
+/* ---- single-channel 2-D convolution, any kernel (Sec. V-A, 2-D form:
+ *      O(x, y) = sum_{rx, ry} I(x + rx, y + ry) K(rx, ry); correlation, explicit
+ *      anchors, same-size output, clamp-to-edge on both INPUT indices) -------- */
+/* taps is kh x kw, row-major: taps[ry * kw + rx] = K(rx, ry). */
+
+void hbo_conv2d(const uint16_t *in, double *out, int H, int W,
+                long in_pitch, long out_pitch,
+                const uint16_t *taps, int kh, int kw, int ay, int ax)
+{
+    double *img = decode_image(in, H, W, in_pitch);
+    double *k = (double *)malloc((size_t)kh * (size_t)kw * sizeof(double));
+    if (!img || !k) { free(img); free(k); return; }
+    for (int i = 0; i < kh * kw; ++i) k[i] = hbo_half_to_double(taps[i]);
+#pragma omp parallel for schedule(static)
+    for (int y = 0; y < H; ++y) {
+        for (int x = 0; x < W; ++x) {
+            double acc = 0.0;
+            for (int ry = 0; ry < kh; ++ry) {
+                long yi = clampl((long)y + ry - ay, 0, H - 1);
+                for (int rx = 0; rx < kw; ++rx) {
+                    long xi = clampl((long)x + rx - ax, 0, W - 1);
+                    acc += k[ry * kw + rx] * img[(size_t)yi * W + xi];
+                }
+            }
+            out[(long)y * out_pitch + x] = acc;
+        }
+    }
+    free(img);
+    free(k);
+}
+
 /* ---- separable blur: rows, then columns (Sec. V-A; the 2-D form with
  *      K(rx, ry) = kx[rx] * ky[ry]) ------------------------------------ */
 /* tmp[y][x] = sum_r kx[r] in[y][clampW(x + r - ax)]

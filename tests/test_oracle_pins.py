@@ -220,6 +220,77 @@ def test_sepblur_separates_into_two_dense_matrix_products(orc):
 
 
 # --------------------------------------------------------------------------
+# 2-D convolution with an arbitrary (non-separable) kernel
+# --------------------------------------------------------------------------
+
+def rand_kernel(seed, kh, kw):
+    """kh x kw taps on the fp16 grid (multiples of 1/64 in [-1, 1))."""
+    return h(np.round(d(synth.uniform_pm1_f16(seed, (kh, kw))) * 64) / 64)
+
+
+def test_conv2d_impulse_gives_mirrored_kernel_and_constant_gives_tap_sum(orc):
+    kh, kw, ay, ax = 5, 7, 1, 4
+    k = rand_kernel(81, kh, kw)
+    K = d(k)
+    img = np.zeros((30, 34))
+    y0, x0 = 14, 17
+    img[y0, x0] = 1.0
+    out = orc.conv2d(h(img), k, ay, ax)
+    expect = np.zeros_like(img)
+    for y in range(30):
+        for x in range(34):
+            ry, rx = y0 - y + ay, x0 - x + ax
+            if 0 <= ry < kh and 0 <= rx < kw:
+                expect[y, x] = K[ry, rx]
+    assert np.array_equal(out, expect)
+    out = orc.conv2d(h(np.full((9, 11), 0.25)), k, ay, ax)          # also on the clamped edges
+    assert np.allclose(out, 0.25 * K.sum(), atol=1e-15)
+
+
+def test_conv2d_equals_correlation_on_an_edge_replicated_array(orc):
+    """Second formulation: replicate-pad the image (numpy), then plain windows times the kernel."""
+    H, W, kh, kw, ay, ax = 13, 17, 6, 4, 5, 0
+    img, k = rand_img(82, H, W), rand_kernel(83, kh, kw)
+    out = orc.conv2d(img, k, ay, ax)
+    P = np.pad(d(img), ((ay, kh - 1 - ay), (ax, kw - 1 - ax)), mode="edge")
+    win = np.lib.stride_tricks.sliding_window_view(P, (kh, kw))      # [y][x][ry][rx]
+    assert np.allclose(out, np.einsum("yxab,ab->yx", win, d(k)), atol=1e-14)
+
+
+def test_conv2d_with_outer_product_kernel_equals_the_separable_blur(orc):
+    """K = ky (x) kx with power-of-two taps (products exact in fp16): the blur oracle, pinned above."""
+    ky = h([0.5, 0.25, 0.125, 0.0625, 0.0625])
+    kx = h([0.25, 0.5, 0.125, 0.125])
+    K = h(np.outer(d(ky), d(kx)))
+    img = rand_img(84, 21, 19)
+    assert np.allclose(orc.conv2d(img, K, 2, 1), orc.sepblur(img, kx, 1, ky, 2), atol=1e-15)
+
+
+def test_conv2d_single_row_kernel_is_the_fir_and_single_column_its_transpose(orc):
+    t = synth.random_taps_f16(85, 9)
+    img = rand_img(86, 10, 40)
+    assert np.allclose(orc.conv2d(img, t.reshape(1, 9), 0, 3), orc.fir1d(img, t, 3), atol=1e-15)
+    imgT = np.ascontiguousarray(img.T)
+    assert np.allclose(orc.conv2d(imgT, t.reshape(9, 1), 3, 0), orc.fir1d(img, t, 3).T, atol=1e-15)
+
+
+def test_conv2d_is_a_sum_of_row_shifted_toeplitz_products(orc):
+    """The paper's serial loop over r_y: out = sum_ry  shift_ry(I) * A_{K(., ry)}, written densely."""
+    H, W, kh, kw, ay, ax = 8, 12, 3, 5, 1, 2
+    img, k = rand_img(87, H, W), rand_kernel(88, kh, kw)
+    I, K = d(img), d(k)
+    Ipad = np.pad(I, ((0, 0), (ax, kw - 1 - ax)), mode="edge")      # W + kw - 1 samples per row
+    total = np.zeros((H, W))
+    for ry in range(kh):
+        A = np.zeros((W + kw - 1, W))                                # A_K(x, y) = K(y - x)
+        for x in range(W):
+            A[x:x + kw, x] = K[ry]
+        rows = np.clip(np.arange(H) + ry - ay, 0, H - 1)
+        total += Ipad[rows] @ A
+    assert np.allclose(orc.conv2d(img, k, ay, ax), total, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
 # summed-area table
 # --------------------------------------------------------------------------
 
