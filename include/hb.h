@@ -64,6 +64,7 @@ typedef void *hb_stream;      /* hipStream_t */
 
 #define HB_MAX_TAPS 64          /* per axis, hb_sepblur */
 #define HB_MAX_TAPS_FIR1D 256   /* hb_fir1d: the large-tap regime of Sec. V-A */
+#define HB_MAX_TAPS_CONV2D 32   /* per axis, hb_conv2d */
 
 /* Human-readable name of a status code (static storage). */
 const char *hb_status_string(hb_status s);
@@ -80,6 +81,28 @@ hb_status hb_fir1d(const hb_half *in, float *out, int H, int W,
 hb_status hb_fir1d_valu(const hb_half *in, float *out, int H, int W,
                         int64_t in_pitch, int64_t out_pitch,
                         const hb_half *taps_host, int ntaps, int anchor, hb_stream stream);
+
+/*
+ * Single-channel 2-D convolution with an arbitrary, non-separable kernel (Sec. V-A,
+ * the 2-D form; on the matrix units it runs as the serial loop over the kernel
+ * rows r_y, one Toeplitz product per kernel row into the same accumulator):
+ *     out[y][x] = sum_{ry < kh} sum_{rx < kw} taps[ry * kw + rx]
+ *                 * in[clampH(y + ry - anchor_y)][clampW(x + rx - anchor_x)]
+ * in: H x W fp16, out: H x W fp32.  taps_host: kh x kw fp16 bit patterns, row-major,
+ * HOST memory, read before the call returns.  1 <= kh, kw <= HB_MAX_TAPS_CONV2D,
+ * 0 <= anchor_y < kh, 0 <= anchor_x < kw; otherwise HB_ERR_INVALID_ARG.  Size
+ * limits as for hb_fir1d (HB_ERR_UNSUPPORTED beyond them).  Columns whose window
+ * reaches over the left or right image border are computed by the vector-ALU
+ * kernel in a second launch on the same stream.
+ */
+hb_status hb_conv2d(const hb_half *in, float *out, int H, int W,
+                    int64_t in_pitch, int64_t out_pitch,
+                    const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
+                    hb_stream stream);
+hb_status hb_conv2d_valu(const hb_half *in, float *out, int H, int W,
+                         int64_t in_pitch, int64_t out_pitch,
+                         const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
+                         hb_stream stream);
 
 /*
  * Separable 2-D blur (Sec. V-A, the 2-D form with K(rx, ry) = kx[rx] ky[ry]; the

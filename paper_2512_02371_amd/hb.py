@@ -22,11 +22,13 @@ HB_ERR_WORKSPACE = 3
 HB_ERR_HIP = 4
 HB_MAX_TAPS = 64            # per axis, hb_sepblur
 HB_MAX_TAPS_FIR1D = 256     # hb_fir1d
+HB_MAX_TAPS_CONV2D = 32     # per axis, hb_conv2d
 
 # every symbol include/hb.h declares
 SYMBOLS = [
     "hb_status_string",
     "hb_fir1d", "hb_fir1d_valu",
+    "hb_conv2d", "hb_conv2d_valu",
     "hb_sepblur", "hb_sepblur_valu",
     "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu",
     "hb_conv3x3", "hb_conv3x3_valu",
@@ -58,10 +60,11 @@ def load() -> ctypes.CDLL:
     L.hb_status_string.restype = ctypes.c_char_p
     fir = [vp, vp, I, I, I64, I64, vp, I, I, vp]
     sep = [vp, vp, I, I, I64, I64, vp, I, I, vp, I, I, vp]
+    c2d = [vp, vp, I, I, I64, I64, vp, I, I, I, I, vp]
     sat = [vp, vp, I, I, I64, I64, vp, ctypes.c_size_t, vp]
     conv = [vp, vp, vp, I, I, I, I, I, vp]
     pyr = [vp, vp, vp, I, I, I64, I64, I64, vp]
-    for name, sig in (("hb_fir1d", fir), ("hb_fir1d_valu", fir), ("hb_sepblur", sep), ("hb_sepblur_valu", sep),
+    for name, sig in (("hb_fir1d", fir), ("hb_fir1d_valu", fir), ("hb_conv2d", c2d), ("hb_conv2d_valu", c2d), ("hb_sepblur", sep), ("hb_sepblur_valu", sep),
                       ("hb_sat2d", sat), ("hb_sat2d_valu", sat), ("hb_conv3x3", conv), ("hb_conv3x3_valu", conv),
                       ("hb_pyr_level", pyr), ("hb_pyr_level_valu", pyr),
                       ("hb_copy_f16_f32", [vp, vp, I64, vp]), ("hb_mfma_probe", [I, vp, vp, vp, vp])):
@@ -119,6 +122,27 @@ def hb_fir1d(inp, out, taps, anchor):
 
 def hb_fir1d_valu(inp, out, taps, anchor):
     return _fir("hb_fir1d_valu", inp, out, taps, anchor)
+
+
+def _conv2d(name, inp, out, taps2d, anchor_y, anchor_x):
+    import torch
+    pi, H, W, ip = _img2d(inp, torch.float16)
+    po, Ho, Wo, op = _img2d(out, torch.float32)
+    assert (H, W) == (Ho, Wo)
+    k = np.asarray(taps2d)
+    assert k.ndim == 2, "kh x kw tap array expected"
+    keep, pt, n = _taps(k)
+    _check(name, getattr(load(), name)(pi, po, H, W, ip, op, pt, int(k.shape[0]), int(k.shape[1]),
+                                        int(anchor_y), int(anchor_x), _stream()))
+    return out
+
+
+def hb_conv2d(inp, out, taps2d, anchor_y, anchor_x):
+    return _conv2d("hb_conv2d", inp, out, taps2d, anchor_y, anchor_x)
+
+
+def hb_conv2d_valu(inp, out, taps2d, anchor_y, anchor_x):
+    return _conv2d("hb_conv2d_valu", inp, out, taps2d, anchor_y, anchor_x)
 
 
 def _sep(name, inp, out, tx, ax, ty, ay):

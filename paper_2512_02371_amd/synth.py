@@ -88,6 +88,14 @@ def random_taps_f16(seed: int, ntaps: int) -> np.ndarray:
     return _f16_bits(t / t.sum())
 
 
+def random_kernel2d_f16(seed: int, kh: int, kw: int) -> np.ndarray:
+    """kh x kw signed draws from (-1, 1), scaled to sum |k| = 1 in fp64, rounded once to fp16
+    (a generic non-separable filter: no rank-1 structure, both signs)."""
+    h = hash_u64(seed, 0, kh * kw) >> np.uint64(11)
+    t = (h.astype(np.float64) + 0.5) / 4503599627370496.0 - 1.0
+    return _f16_bits(t / np.abs(t).sum()).reshape(kh, kw)
+
+
 def gaussian_taps_f16(ntaps: int, sigma: float) -> np.ndarray:
     """Sampled Gaussian centred on (ntaps-1)/2, normalised in fp64, rounded once to fp16."""
     r = np.arange(ntaps, dtype=np.float64) - (ntaps - 1) / 2.0
