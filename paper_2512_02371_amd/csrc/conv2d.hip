@@ -2,16 +2,27 @@
 // vector-ALU twin (Sec. V-A, 2-D form: O(x, y) = sum_{rx, ry} I(x + rx, y + ry) K(rx, ry)).
 //
 // MFMA formulation: the serial loop over the kernel rows r_y of Sec. V-A.  For every r_y the
-// contribution is a row-wise FIR with taps K(., r_y) applied to the image shifted up by r_y rows,
-// i.e. one Toeplitz product per tile exactly as in hb_fir1d (transposed: D'[m][n] += A[m][k] P[k][n],
-// m = output column, n = image row in a 16-row group, k = pixel in the window), accumulated over
-// r_y in the same accumulator.  The kh Toeplitz fragments per 32-pixel window chunk are built once
-// per workgroup into LDS (one conflict-free 16-byte read per product); the image operand is read
-// straight from memory, 16 image rows (clamped) shifted by r_y.
+// contribution is a row-wise FIR with taps K(., r_y), i.e. one Toeplitz product per tile as in
+// hb_fir1d (transposed: D[m][n] = sum_k A_ry[m][k] P[k][n], m = output column, n = image row in a
+// 16-row group, k = pixel in the window).  The kh Toeplitz fragments per 32-pixel window chunk are
+// built once per workgroup into LDS.
 //
-// The clamp along x is not folded into the fragments here (there would be kh folded pairs per
-// border tile): strips that touch the left or right image border are computed by the vector-ALU
-// kernel in a second launch on the same stream; the matrix kernel covers the interior strips.
+// The image operand P of a product lives in registers, one image row per lane column n, so the
+// straightforward loop (rows shifted down by r_y for every r_y) would fetch a new operand for every
+// product.  Instead the kernel keeps the INPUT rows fixed: a wave walks down a strip of 64 columns
+// one group of 16 input rows at a time, loads that group's windows once, and multiplies them with
+// all kh Toeplitz matrices.  The product for kernel row r_y holds, in lane column n, the contribution
+// of input row r to output row r - r_y + anchor_y: the whole product tile is the output tile moved by
+// r_y rows.  With the input groups placed at rows 16 G - anchor_y the move is r_y = 16 a + b rows
+// exactly, so the tile is added into the accumulators of output groups G - a (rows n >= b) and
+// G - a - 1 (rows n < b) with two lane-shifted additions inside each row of 16 lanes (DPP row
+// shifts; lanes shifted out of the row are not written).  Three output groups are open at a time;
+// the oldest is complete after every step and is stored.
+//
+// The clamp along x needs no folded fragments here: the Toeplitz matrix is indexed by the window
+// position, so a strip whose windows reach over the left or right image border only loads its
+// windows pixel by pixel with the column clamped (once per 16 input rows, shared by all kh
+// products); the products themselves are the same.
 #include "hb_device.hpp"
 #include "hb_host.hpp"
 
@@ -26,23 +37,104 @@ struct Conv2dArgs {
     int H, W;
     int64_t in_pitch, out_pitch;
     int kh, kw, ay, ax;
-    // matrix kernel: interior strips [c0, c1) of 64 columns, 16-row groups, tasks = (c1 - c0) * rowgroups
-    int c0, c1, rowgroups, ntasks;
-    // vector-ALU kernel: computes the columns [0, xa) and [xb, W)
-    int xa, xb;
+    // matrix kernel: nstrips strips of 64 columns; a task = one strip x seg_len output row groups;
+    // ngroups = output row groups of the image
+    int nstrips, ngroups, seg_len, nseg, ntasks;
     uint16_t taps[HB_MAX_TAPS_CONV2D * HB_MAX_TAPS_CONV2D];   // kh x kw, row-major
 };
 
+// acc[c] += d[c + SH] for the lanes c of each row of 16 with 0 <= c + SH < 16 (SH in -15..15).
+template <int SH>
+__device__ __forceinline__ float c2_shift_add(float acc, float d) {
+    if constexpr (SH == 0) {
+        return acc + d;
+    } else {
+        constexpr int ctrl = SH > 0 ? 0x100 + SH : 0x110 - SH;        // row_shl:SH / row_shr:-SH
+        const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), ctrl, 0xf, 0xf, true);
+        return acc + __builtin_bit_cast(float, moved);
+    }
+}
+
+// Four kernel rows R4 .. R4+3 of one step: the windows `px` of one group of 16 input rows times the
+// rows' Toeplitz matrices, added into the three open output groups ring[0..2] = groups G-2, G-1, G.
+template <int NK, int R4>
+__device__ __forceinline__ void c2_rows4(const half8* s_frag, int lane, const half8 (&px)[kC2Tiles][NK],
+                                         floatx4 (&ring)[3][kC2Tiles]) {
+    half8 ahead[NK];                           // fragments of the next kernel row, read one row early
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) ahead[kk] = s_frag[(R4 * NK + kk) * 64 + lane];
+#pragma unroll
+    for (int ry = R4; ry < R4 + 4; ++ry) {
+        half8 coef[NK];
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) {
+            coef[kk] = ahead[kk];
+            if (ry + 1 < R4 + 4) ahead[kk] = s_frag[((ry + 1) * NK + kk) * 64 + lane];
+        }
+#pragma unroll
+        for (int w = 0; w < kC2Tiles; ++w) {
+            floatx4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) d = mfma16x16x32(coef[kk], px[w][kk], d);
+            const int a = ry >> 4, b = ry & 15;       // compile-time after unrolling
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // b is a constant per unrolled iteration; the switch folds to one case
+                switch (b) {
+#define HB_C2_CASE(B)                                                                              \
+    case B:                                                                                        \
+        ring[2 - a][w][j] = c2_shift_add<B>(ring[2 - a][w][j], d[j]);                              \
+        if (B != 0) ring[1 - a][w][j] = c2_shift_add<(B == 0 ? 0 : B - 16)>(ring[1 - a][w][j], d[j]); \
+        break;
+                    HB_C2_CASE(0) HB_C2_CASE(1) HB_C2_CASE(2) HB_C2_CASE(3) HB_C2_CASE(4) HB_C2_CASE(5)
+                    HB_C2_CASE(6) HB_C2_CASE(7) HB_C2_CASE(8) HB_C2_CASE(9) HB_C2_CASE(10) HB_C2_CASE(11)
+                    HB_C2_CASE(12) HB_C2_CASE(13) HB_C2_CASE(14) HB_C2_CASE(15)
+#undef HB_C2_CASE
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);    // keep the kernel rows in order: bounded register use
+    }
+}
+
+// Kernel rows R0 .. R1-1 in blocks of four; blocks at or beyond kh are skipped (uniform branch), rows
+// beyond kh inside a block have zero fragments.
+template <int NK, int R0, int R1>
+__device__ __forceinline__ void c2_blocks(const half8* s_frag, int lane, int kh, const half8 (&px)[kC2Tiles][NK],
+                                          floatx4 (&ring)[3][kC2Tiles]) {
+    if constexpr (R0 < R1) {
+        if (R0 < kh) c2_rows4<NK, R0>(s_frag, lane, px, ring);
+        c2_blocks<NK, R0 + 4, R1>(s_frag, lane, kh, px, ring);
+    }
+}
+
+// One step of the walk: kernel rows R0 .. R1-1 (multiples of four) against one input group.
+template <int NK, int R0, int R1>
+__device__ __forceinline__ void c2_step(const half8* s_frag, int lane, int kh, const half8 (&px)[kC2Tiles][NK],
+                                        floatx4 (&ring)[3][kC2Tiles]) {
+    c2_blocks<NK, R0, R1>(s_frag, lane, kh, px, ring);
+    // Pin the sums here: otherwise the additions are sunk below the caller's store and every
+    // shifted product stays live (and is spilled) until then.
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int w = 0; w < kC2Tiles; ++w)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(ring[r][w][j]));
+}
+
 // ---------------------------------------------------------------------------
 // Matrix-unit kernel.  NK = 32-pixel chunks of a tile's window (16 + kw - 1 pixels from x0 - ax on,
-// one more when the window is moved to an even pixel).
-template <int NK, bool STREAM>
+// one more when the window is moved to an even pixel); KH16 = kernel rows in units of 16 (the
+// fragment table is padded with zero rows up to 16 KH16).
+template <int NK, int KH16, bool STREAM>
 __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
     constexpr int NW = kC2Tiles;
+    constexpr int KR = 16 * KH16;
     extern __shared__ __attribute__((aligned(16))) char s_dyn[];
-    // [kh][NK][64 lanes] fragments, then one row patch per wave
+    // [KR][NK][64 lanes] fragments, then one row patch per wave
     half8* s_frag = reinterpret_cast<half8*>(s_dyn);
-    float* s_patch = reinterpret_cast<float*>(s_dyn + (size_t)p.kh * NK * 1024);
+    float* s_patch = reinterpret_cast<float*>(s_dyn + (size_t)KR * NK * 1024);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -51,75 +143,110 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
     const int aw = p.ax + e;                  // window start, left of the tile (even pixel)
 
     // Toeplitz fragments, A-operand layout: lane (c, g) holds A[c][32 kk + 8g + i] = K(32 kk + 8g + i - c - e, ry)
-    for (int idx = tid; idx < p.kh * NK * 64; idx += kC2Threads) {
+    for (int idx = tid; idx < KR * NK * 64; idx += kC2Threads) {
         const int l = idx & 63, kk = (idx >> 6) % NK, ry = idx / (64 * NK);
         const int t0 = 32 * kk + 8 * (l >> 4) - (l & 15) - e;
         half8 f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int t = t0 + i;
-            f[i] = (t >= 0 && t < p.kw) ? __builtin_bit_cast(half_t, p.taps[ry * p.kw + t]) : (half_t)0;
+            f[i] = (ry < p.kh && t >= 0 && t < p.kw) ? __builtin_bit_cast(half_t, p.taps[ry * p.kw + t]) : (half_t)0;
         }
         s_frag[idx] = f;
     }
     __syncthreads();
 
-    const int nstrips = p.c1 - p.c0;
-    const int wave0 = blockIdx.x * (kC2Threads / 64) + wv;
-    const int nwaves = gridDim.x * (kC2Threads / 64);
+    const int task = blockIdx.x * (kC2Threads / 64) + wv;
+    if (task >= p.ntasks) return;
+    const int sg = task / p.nstrips, ct = task - sg * p.nstrips;
+    const int x0 = 16 * NW * ct;
+    const int q0 = sg * p.seg_len, q1 = min(q0 + p.seg_len, p.ngroups);   // output groups of this task
     float* patch = s_patch + wv * RowPatch<NW>::kFloats;
     const uint32_t rowbytes = (uint32_t)p.in_pitch * 2u;
-    for (int task = wave0; task < p.ntasks; task += nwaves) {
-        const int rg = task / nstrips, ct = p.c0 + (task - rg * nstrips);
-        const int x0 = 16 * NW * ct, y0 = 16 * rg;
-        const half_t* src = p.in + (x0 - aw);             // uniform; lanes add row * pitch + 8g
-        floatx4 acc[NW];
-#pragma unroll
-        for (int w = 0; w < NW; ++w) acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // windows of the strip: pixels x0 - aw .. x0 - aw + 32 NK + 47; inside the row for interior strips
+    const bool inside = x0 - aw >= 0 && x0 - aw + 32 * NK + 48 <= p.W;
+    const bool whole = x0 + 16 * NW <= p.W;                // all 64 output columns exist
+    const half_t* src = p.in + (x0 - aw);                 // uniform; lanes add row * pitch + 8g
+    float* dst = p.out + x0;
 
-        auto load_rows = [&](int ry, half8 (&d)[NW][NK]) {
-            // image rows y0 + c + ry - ay, clamped; past the last kernel row: the last one again
-            const int yr = clampi(y0 + c + min(ry, p.kh - 1) - p.ay, 0, p.H - 1);
+    auto load_group = [&](int G, half8 (&d)[NW][NK]) {
+        // input rows 16 G - anchor_y + c, clamped into the image
+        const int yr = clampi(16 * G - p.ay + c, 0, p.H - 1);
+        if (inside) {
             const uint32_t off = (uint32_t)yr * rowbytes + 16u * g;
 #pragma unroll
             for (int w = 0; w < NW; ++w)
 #pragma unroll
                 for (int kk = 0; kk < NK; ++kk) d[w][kk] = ldg8(src, off + 2u * (16u * w + 32u * kk));
-        };
-        auto products = [&](int ry, const half8 (&d)[NW][NK]) {
-            half8 coef[NK];
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) coef[kk] = s_frag[(ry * NK + kk) * 64 + lane];
+        } else {
+            // pixel by pixel, column clamped; 32-bit byte offsets from the image base
+            const uint32_t rowoff = (uint32_t)yr * rowbytes;
+            const int xs = x0 - aw + 8 * g;
 #pragma unroll
             for (int w = 0; w < NW; ++w)
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) acc[w] = mfma16x16x32(coef[kk], d[w][kk], acc[w]);
-        };
-        // two window buffers used alternately; the next kernel row's windows are always requested
-        half8 bufa[NW][NK], bufb[NW][NK];
-        load_rows(0, bufa);
-        for (int ry = 0; ry < p.kh; ry += 2) {
-            load_rows(ry + 1, bufb);
-            products(ry, bufa);
-            if (ry + 1 >= p.kh) break;
-            load_rows(ry + 2, bufa);
-            products(ry + 1, bufb);
+                for (int kk = 0; kk < NK; ++kk)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int x = clampi(xs + 16 * w + 32 * kk + i, 0, p.W - 1);
+                        d[w][kk][i] = *reinterpret_cast<const half_t*>(reinterpret_cast<const char*>(p.in) + (rowoff + 2u * (uint32_t)x));
+                    }
         }
-        float* dst = p.out + x0;
-        if (y0 + 16 <= p.H) {
+    };
+    auto store_group = [&](int Q, const floatx4 (&acc)[NW]) {
+        const int y0 = 16 * Q;
+        if (whole && y0 + 16 <= p.H) {
             store_rows_via_lds<NW, STREAM>(patch, dst + (int64_t)y0 * p.out_pitch, (uint32_t)p.out_pitch, acc, lane);
         } else if (y0 + c < p.H) {
-            const uint32_t off = ((uint32_t)(y0 + c) * (uint32_t)p.out_pitch + 4u * g) * 4u;
+            float* row = p.out + (int64_t)(y0 + c) * p.out_pitch;
 #pragma unroll
-            for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
+            for (int w = 0; w < NW; ++w) store4_mask(row, x0 + 16 * w + 4 * g, p.W, acc[w]);
+        }
+    };
+
+    floatx4 ring[3][NW];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ring[r][w] = floatx4{0.f, 0.f, 0.f, 0.f};
+    half8 cur[NW][NK], nxt[NW][NK];
+    load_group(q0, cur);
+    // input groups q0 .. q1 + KH16 - 1 feed the output groups q0 .. q1 - 1
+    const int Gend = q1 + KH16;
+#pragma unroll 1
+    for (int G = q0; G < Gend; ++G) {
+        load_group(G + 1, nxt);               // clamped rows: always inside the image
+        // The fragment reads do not depend on G; left alone the compiler lifts all of them out of
+        // the loop and spills.  An opaque copy of the lane index keeps them inside.
+        int fl = lane;
+        asm volatile("" : "+v"(fl));
+        if (KH16 == 2 && G == Gend - 1) {
+            c2_step<NK, 16, KR>(s_frag, fl, p.kh, cur, ring);      // only kernel rows >= 16 still reach group q1 - 1
+        } else if (KH16 == 2 && G == q0) {
+            c2_step<NK, 0, 16>(s_frag, fl, p.kh, cur, ring);       // rows >= 16 would feed groups above q0
+        } else {
+            c2_step<NK, 0, KR>(s_frag, fl, p.kh, cur, ring);
+        }
+        const int Q = G - 2;                  // complete: no later input group reaches it
+        if (Q >= q0 && Q < q1) store_group(Q, ring[0]);
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            ring[0][w] = ring[1][w];
+            ring[1][w] = ring[2][w];
+            ring[2][w] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) cur[w][kk] = nxt[w][kk];
         }
     }
+    // KH16 == 1: the walk ends with input group q1, which completes output group q1 - 1; the last
+    // rotation moved it from ring[1] to ring[0]
+    if (KH16 == 1 && q1 > q0) store_group(q1 - 1, ring[0]);
 }
 
 // ---------------------------------------------------------------------------
 // Vector-ALU kernel: a 16 x 64 output tile per workgroup; the tile and its halo are staged in LDS
 // with both indices clamped (the definition's border rule verbatim), every thread slides the kernel
-// over 4 consecutive outputs with fp32 FMAs.  Tiles cover the column ranges [0, xa) and [xb, W).
+// over 4 consecutive outputs with fp32 FMAs.
 constexpr int kC2vW = 64;
 constexpr int kC2vRows = 16 + HB_MAX_TAPS_CONV2D - 1;                 // 47
 constexpr int kC2vPitch = kC2vW + HB_MAX_TAPS_CONV2D - 1 + 1;          // 96 halves
@@ -129,10 +256,10 @@ __global__ void __launch_bounds__(256) conv2d_valu_kernel(Conv2dArgs p) {
     __shared__ float s_k[HB_MAX_TAPS_CONV2D * HB_MAX_TAPS_CONV2D];
     for (int i = threadIdx.x; i < p.kh * p.kw; i += 256) s_k[i] = (float)__builtin_bit_cast(half_t, p.taps[i]);
 
-    const int nl = (p.xa + kC2vW - 1) / kC2vW, nr = (p.W - p.xb + kC2vW - 1) / kC2vW;
-    const int rg = blockIdx.x / (nl + nr), tc = blockIdx.x - rg * (nl + nr);
-    const int x0 = tc < nl ? kC2vW * tc : p.xb + kC2vW * (tc - nl);
-    const int xend = tc < nl ? min(x0 + kC2vW, p.xa) : min(x0 + kC2vW, p.W);
+    const int nt = (p.W + kC2vW - 1) / kC2vW;
+    const int rg = blockIdx.x / nt, tc = blockIdx.x - rg * nt;
+    const int x0 = kC2vW * tc;
+    const int xend = min(x0 + kC2vW, p.W);
     const int y0 = 16 * rg;
     const int nrows = 16 + p.kh - 1, ncols = kC2vW + p.kw - 1;   // ncols <= 95
     {
@@ -190,15 +317,13 @@ static hb_status conv2d_prepare(Conv2dArgs& a, const hb_half* in, float* out, in
     a.ax = ax;
     memset(a.taps, 0, sizeof(a.taps));
     memcpy(a.taps, taps_host, sizeof(uint16_t) * (size_t)kh * (size_t)kw);
-    a.rowgroups = ceil_div(H, 16);
-    a.c0 = a.c1 = 0;
-    a.ntasks = 0;
-    a.xa = a.xb = W;                          // vector-ALU kernel: everything
+    a.ngroups = ceil_div(H, 16);
+    a.nstrips = a.seg_len = a.nseg = a.ntasks = 0;
     return HB_OK;
 }
 
 static hb_status conv2d_launch_valu(const Conv2dArgs& a, hipStream_t st) {
-    const int64_t blocks = (int64_t)a.rowgroups * (ceil_div(a.xa, kC2vW) + ceil_div(a.W - a.xb, kC2vW));
+    const int64_t blocks = (int64_t)a.ngroups * ceil_div(a.W, kC2vW);
     if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
     if (blocks > 0) hipLaunchKernelGGL(conv2d_valu_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
     return launch_status();
@@ -215,39 +340,38 @@ extern "C" hb_status hb_conv2d(const hb_half* in, float* out, int H, int W,
     hb_status s = conv2d_prepare(a, in, out, H, W, in_pitch, out_pitch, taps_host, kh, kw, anchor_y, anchor_x);
     if (s != HB_OK) return s;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    // interior strips: the windows of all their tiles lie inside the row
-    const int e = anchor_x & 1, aw = anchor_x + e;
+    const int e = anchor_x & 1;
     const int nk = ceil_div(15 + kw + e, 32);                // 1 or 2
-    const int sw = 16 * kC2Tiles;
-    const int c0 = ceil_div(aw, sw);
-    const int last = W - (sw - 16) + aw - 32 * nk;           // x0 <= last keeps the last window inside
-    int c1 = last >= 0 ? last / sw + 1 : 0;
-    if (c1 > W / sw) c1 = W / sw;
-    if (c1 > c0) {
-        a.c0 = c0;
-        a.c1 = c1;
-        a.ntasks = (c1 - c0) * a.rowgroups;
-        a.xa = sw * c0;
-        a.xb = sw * c1;
-        const size_t lds = (size_t)kh * nk * 1024 + (kC2Threads / 64) * RowPatch<kC2Tiles>::kFloats * sizeof(float);
-        // fewer workgroups than tasks: every workgroup builds the fragment table once
-        const int per_cu = lds <= 48 * 1024 ? 3 : lds <= 80 * 1024 ? 2 : 1;
-        const int blocks = min(ceil_div(a.ntasks, kC2Threads / 64), kNumCU * per_cu);
-        const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
-#define HB_C2_LAUNCH(N, S)                                                                            \
+    const int kh16 = ceil_div(kh, 16);
+    a.nstrips = ceil_div(W, 16 * kC2Tiles);
+    // One task per wave: a strip times a run of output row groups.  Every task walks
+    // (kernel rows / 16) extra input groups, so runs are as long as filling the chip allows.
+    const int waves = kNumCU * (kC2Threads / 64);
+    int len = (int)(((int64_t)a.nstrips * a.ngroups + waves - 1) / waves);
+    if (len < 4) len = a.ngroups < 4 ? a.ngroups : 4;
+    a.seg_len = len;
+    a.nseg = ceil_div(a.ngroups, len);
+    const int64_t ntasks = (int64_t)a.nstrips * a.nseg;
+    if (ntasks > 0x7fffffff / 2) return HB_ERR_UNSUPPORTED;
+    a.ntasks = (int)ntasks;
+    const size_t lds = (size_t)(16 * kh16) * nk * 1024 + (kC2Threads / 64) * RowPatch<kC2Tiles>::kFloats * sizeof(float);
+    const int blocks = ceil_div(a.ntasks, kC2Threads / 64);
+    const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
+#define HB_C2_LAUNCH(N, K, S)                                                                         \
     {                                                                                                 \
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_mfma_kernel<N, S>),             \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_mfma_kernel<N, K, S>),          \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)  \
             return HB_ERR_HIP;                                                                        \
-        hipLaunchKernelGGL((conv2d_mfma_kernel<N, S>), dim3(blocks), dim3(kC2Threads), lds, st, a);   \
+        hipLaunchKernelGGL((conv2d_mfma_kernel<N, K, S>), dim3(blocks), dim3(kC2Threads), lds, st, a); \
     }
-        if (nk == 1) { if (ss) HB_C2_LAUNCH(1, true) else HB_C2_LAUNCH(1, false) }
-        else { if (ss) HB_C2_LAUNCH(2, true) else HB_C2_LAUNCH(2, false) }
+#define HB_C2_PICK(N, K) { if (ss) HB_C2_LAUNCH(N, K, true) else HB_C2_LAUNCH(N, K, false) }
+    if (nk == 1 && kh16 == 1) HB_C2_PICK(1, 1)
+    else if (nk == 1) HB_C2_PICK(1, 2)
+    else if (kh16 == 1) HB_C2_PICK(2, 1)
+    else HB_C2_PICK(2, 2)
+#undef HB_C2_PICK
 #undef HB_C2_LAUNCH
-        s = launch_status();
-        if (s != HB_OK) return s;
-    }
-    return conv2d_launch_valu(a, st);                         // border strips (everything if there is no interior)
+    return launch_status();
 }
 
 extern "C" hb_status hb_conv2d_valu(const hb_half* in, float* out, int H, int W,
@@ -258,7 +382,5 @@ extern "C" hb_status hb_conv2d_valu(const hb_half* in, float* out, int H, int W,
     Conv2dArgs a;
     hb_status s = conv2d_prepare(a, in, out, H, W, in_pitch, out_pitch, taps_host, kh, kw, anchor_y, anchor_x);
     if (s != HB_OK) return s;
-    a.xa = W;                                 // one range covers all columns
-    a.xb = W;
     return conv2d_launch_valu(a, reinterpret_cast<hipStream_t>(stream));
 }
