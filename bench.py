@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary stacked FIR run")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -245,6 +245,26 @@ def main():
         out["supplementary"]["fir1d_256taps_4096x4096"] = {
             "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
             "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
+        # ... and the paper's 2-D study (Sec. V-A): non-separable k x k kernels, k = 16 and 32, on
+        # the same image.  tflops counts the definition's 2 k^2 flops per pixel, not the Toeplitz zeros.
+        for k in (16, 32):
+            k2d = synth.random_kernel2d_f16(2300 + k, k, k)
+
+            def timed2(fn, iters):
+                for i in range(2):
+                    fn(lx[i % 4], lo[i % 4], k2d, k // 2, k // 2)
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for i in range(iters):
+                    fn(lx[i % 4], lo[i % 4], k2d, k // 2, k // 2)
+                a1.record()
+                torch.cuda.synchronize()
+                return a0.elapsed_time(a1) / iters
+            m_ms, v_ms = timed2(hb.hb_conv2d, 10), timed2(hb.hb_conv2d_valu, 3)
+            out["supplementary"]["conv2d_%dx%d_4096x4096" % (k, k)] = {
+                "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
+                "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms,
+                "mfma_tflops": 2.0 * k * k * npx / m_ms / 1e9}
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)

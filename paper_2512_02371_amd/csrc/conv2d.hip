@@ -57,44 +57,80 @@ __device__ __forceinline__ float c2_shift_add(float acc, float d) {
 
 // Four kernel rows R4 .. R4+3 of one step: the windows `px` of one group of 16 input rows times the
 // rows' Toeplitz matrices, added into the three open output groups ring[0..2] = groups G-2, G-1, G.
+// Adds the product tile of kernel row RY (moved by RY = 16 a + b rows) into tile W of its two output groups.
+template <int RY, int W>
+__device__ __forceinline__ void c2_add_tile(const floatx4& d, floatx4 (&ring)[3][kC2Tiles]) {
+    constexpr int a = RY >> 4, b = RY & 15;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        ring[2 - a][W][j] = c2_shift_add<b>(ring[2 - a][W][j], d[j]);
+        if constexpr (b != 0) ring[1 - a][W][j] = c2_shift_add<b - 16>(ring[1 - a][W][j], d[j]);
+    }
+}
+
+// A block of four kernel rows is 8 pairs of tiles: pair P = (row R4 + P / 2, tiles 2 (P % 2) and
+// 2 (P % 2) + 1).  The products of pair P + 1 are interleaved with the additions of pair P, so the
+// vector ALU adds two tiles while the matrix unit multiplies the next two; inside a pair the two
+// tiles' products alternate, so no product waits for the one it accumulates onto.
+template <int NK, int R4, int P>
+__device__ __forceinline__ void c2_pairs(const half8* s_frag, int lane, const half8 (&px)[kC2Tiles][NK],
+                                         floatx4 (&ring)[3][kC2Tiles], const half8 (&coef)[NK],
+                                         const half8 (&ahead_in)[NK], const floatx4& da, const floatx4& db) {
+    constexpr int ry = R4 + P / 2, w = 2 * (P % 2);
+    half8 ahead[NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) ahead[kk] = ahead_in[kk];
+    if constexpr (w == 0 && ry + 1 < R4 + 4) {
+        // first pair of a kernel row: request the next row's fragments
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) ahead[kk] = s_frag[((ry + 1) * NK + kk) * 64 + lane];
+    }
+    if constexpr (P + 1 < 8) {
+        constexpr int w1 = 2 * ((P + 1) % 2);
+        half8 cnext[NK];
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) cnext[kk] = w1 == 0 ? ahead[kk] : coef[kk];
+        floatx4 na = {0.f, 0.f, 0.f, 0.f}, nb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) {
+            na = mfma16x16x32(cnext[kk], px[w1][kk], na);
+            nb = mfma16x16x32(cnext[kk], px[w1 + 1][kk], nb);
+        }
+        c2_add_tile<ry, w>(da, ring);
+        c2_add_tile<ry, w + 1>(db, ring);
+        // One product, then its share of the additions: a product occupies the matrix unit for as
+        // long as four additions take to issue, so neither unit waits for the other.  (Products
+        // issued back to back would block the wave's instruction stream until the unit is free.)
+#pragma unroll
+        for (int i = 0; i < 2 * NK; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, ((ry & 15) ? 16 : 8) / (2 * NK), 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        c2_pairs<NK, R4, P + 1>(s_frag, lane, px, ring, cnext, ahead, na, nb);
+    } else {
+        c2_add_tile<ry, w>(da, ring);
+        c2_add_tile<ry, w + 1>(db, ring);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Four kernel rows R4 .. R4+3 of one step: the windows `px` of one group of 16 input rows times the
+// rows' Toeplitz matrices, added into the three open output groups ring[0..2] = groups G-2, G-1, G.
 template <int NK, int R4>
 __device__ __forceinline__ void c2_rows4(const half8* s_frag, int lane, const half8 (&px)[kC2Tiles][NK],
                                          floatx4 (&ring)[3][kC2Tiles]) {
-    half8 ahead[NK];                           // fragments of the next kernel row, read one row early
+    static_assert(kC2Tiles == 4, "pairs of tiles");
+    half8 coef[NK];
 #pragma unroll
-    for (int kk = 0; kk < NK; ++kk) ahead[kk] = s_frag[(R4 * NK + kk) * 64 + lane];
+    for (int kk = 0; kk < NK; ++kk) coef[kk] = s_frag[(R4 * NK + kk) * 64 + lane];
+    floatx4 da = {0.f, 0.f, 0.f, 0.f}, db = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ry = R4; ry < R4 + 4; ++ry) {
-        half8 coef[NK];
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) {
-            coef[kk] = ahead[kk];
-            if (ry + 1 < R4 + 4) ahead[kk] = s_frag[((ry + 1) * NK + kk) * 64 + lane];
-        }
-#pragma unroll
-        for (int w = 0; w < kC2Tiles; ++w) {
-            floatx4 d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) d = mfma16x16x32(coef[kk], px[w][kk], d);
-            const int a = ry >> 4, b = ry & 15;       // compile-time after unrolling
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                // b is a constant per unrolled iteration; the switch folds to one case
-                switch (b) {
-#define HB_C2_CASE(B)                                                                              \
-    case B:                                                                                        \
-        ring[2 - a][w][j] = c2_shift_add<B>(ring[2 - a][w][j], d[j]);                              \
-        if (B != 0) ring[1 - a][w][j] = c2_shift_add<(B == 0 ? 0 : B - 16)>(ring[1 - a][w][j], d[j]); \
-        break;
-                    HB_C2_CASE(0) HB_C2_CASE(1) HB_C2_CASE(2) HB_C2_CASE(3) HB_C2_CASE(4) HB_C2_CASE(5)
-                    HB_C2_CASE(6) HB_C2_CASE(7) HB_C2_CASE(8) HB_C2_CASE(9) HB_C2_CASE(10) HB_C2_CASE(11)
-                    HB_C2_CASE(12) HB_C2_CASE(13) HB_C2_CASE(14) HB_C2_CASE(15)
-#undef HB_C2_CASE
-                }
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);    // keep the kernel rows in order: bounded register use
+    for (int kk = 0; kk < NK; ++kk) {
+        da = mfma16x16x32(coef[kk], px[0][kk], da);
+        db = mfma16x16x32(coef[kk], px[1][kk], db);
     }
+    c2_pairs<NK, R4, 0>(s_frag, lane, px, ring, coef, coef, da, db);
 }
 
 // Kernel rows R0 .. R1-1 in blocks of four; blocks at or beyond kh are skipped (uniform branch), rows
@@ -210,11 +246,18 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
 #pragma unroll
         for (int w = 0; w < NW; ++w) ring[r][w] = floatx4{0.f, 0.f, 0.f, 0.f};
     half8 cur[NW][NK], nxt[NW][NK];
+    floatx4 done[NW];                         // the output group completed by the previous step
+#pragma unroll
+    for (int w = 0; w < NW; ++w) done[w] = floatx4{0.f, 0.f, 0.f, 0.f};
     load_group(q0, cur);
     // input groups q0 .. q1 + KH16 - 1 feed the output groups q0 .. q1 - 1
     const int Gend = q1 + KH16;
 #pragma unroll 1
     for (int G = q0; G < Gend; ++G) {
+        // The finished group leaves before this step's loads are issued: loads and stores share one
+        // counter, and a wait for the loads at the end of the step would otherwise also wait for
+        // the write acknowledgements of stores issued just before it.
+        if (G - 3 >= q0 && G - 3 < q1) store_group(G - 3, done);
         load_group(G + 1, nxt);               // clamped rows: always inside the image
         // The fragment reads do not depend on G; left alone the compiler lifts all of them out of
         // the loop and spills.  An opaque copy of the lane index keeps them inside.
@@ -227,10 +270,10 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
         } else {
             c2_step<NK, 0, KR>(s_frag, fl, p.kh, cur, ring);
         }
-        const int Q = G - 2;                  // complete: no later input group reaches it
-        if (Q >= q0 && Q < q1) store_group(Q, ring[0]);
+        // ring[0] = group G - 2 is complete: no later input group reaches it
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
+            done[w] = ring[0][w];
             ring[0][w] = ring[1][w];
             ring[1][w] = ring[2][w];
             ring[2][w] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -238,6 +281,7 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
             for (int kk = 0; kk < NK; ++kk) cur[w][kk] = nxt[w][kk];
         }
     }
+    if (Gend - 3 >= q0 && Gend - 3 < q1) store_group(Gend - 3, done);
     // KH16 == 1: the walk ends with input group q1, which completes output group q1 - 1; the last
     // rotation moved it from ring[1] to ring[0]
     if (KH16 == 1 && q1 > q0) store_group(q1 - 1, ring[0]);

@@ -63,6 +63,31 @@ def test_fir_argument_validation(lib, fn):
     assert call(i=ctypes.c_void_p(0x1001)) == hb.HB_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("fn", ["hb_conv2d", "hb_conv2d_valu"])
+def test_conv2d_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    k = np.zeros(32 * 32, dtype=np.uint16)
+    kp = k.ctypes.data_as(ctypes.c_void_p)
+    ok = dict(i=FAKE, o=FAKE, H=16, W=16, ip=16, op=16, t=kp, kh=5, kw=7, ay=2, ax=3)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["H"], p["W"], p["ip"], p["op"], p["t"], p["kh"], p["kw"], p["ay"], p["ax"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(t=None) == hb.HB_ERR_INVALID_ARG
+    assert call(H=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=15) == hb.HB_ERR_INVALID_ARG
+    assert call(kh=0) == hb.HB_ERR_INVALID_ARG
+    assert call(kw=33) == hb.HB_ERR_INVALID_ARG
+    assert call(kh=33) == hb.HB_ERR_INVALID_ARG
+    assert call(ay=5) == hb.HB_ERR_INVALID_ARG
+    assert call(ax=-1) == hb.HB_ERR_INVALID_ARG
+    assert call(ax=7) == hb.HB_ERR_INVALID_ARG
+    # rows are addressed with 32-bit byte offsets: larger images are reported, not wrapped
+    assert call(H=1 << 16, W=1 << 15, ip=1 << 15, op=1 << 15) == hb.HB_ERR_UNSUPPORTED
+
+
 def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
