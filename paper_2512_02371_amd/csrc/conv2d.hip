@@ -13,11 +13,15 @@
 // one group of 16 input rows at a time, loads that group's windows once, and multiplies them with
 // all kh Toeplitz matrices.  The product for kernel row r_y holds, in lane column n, the contribution
 // of input row r to output row r - r_y + anchor_y: the whole product tile is the output tile moved by
-// r_y rows.  With the input groups placed at rows 16 G - anchor_y the move is r_y = 16 a + b rows
-// exactly, so the tile is added into the accumulators of output groups G - a (rows n >= b) and
-// G - a - 1 (rows n < b) with two lane-shifted additions inside each row of 16 lanes (DPP row
-// shifts; lanes shifted out of the row are not written).  Three output groups are open at a time;
-// the oldest is complete after every step and is stored.
+// r_y rows.  With the input groups placed at rows 16 G - anchor_y, kernel row b < 16 applied to input
+// group G and kernel row b + 16 applied to input group G + 1 are moved by the same b rows relative
+// to output group G, so their products are accumulated in one tile by the matrix unit (the second
+// product takes the first as its addend) and the tile is then added into the accumulators of output
+// groups G (rows n >= b) and G - 1 (rows n < b) with two lane-shifted additions inside each row of
+// 16 lanes (DPP row shifts; lanes shifted out of the row are not written).  Two output groups are
+// open at a time; the older one is complete after every step and is stored.  The lane-shifted
+// additions are what bounds the kernel (they issue at half the rate of plain additions), which is
+// why sharing one shift between two kernel rows matters.
 //
 // The clamp along x needs no folded fragments here: the Toeplitz matrix is indexed by the window
 // position, so a strip whose windows reach over the left or right image border only loads its
@@ -55,108 +59,130 @@ __device__ __forceinline__ float c2_shift_add(float acc, float d) {
     }
 }
 
-// Four kernel rows R4 .. R4+3 of one step: the windows `px` of one group of 16 input rows times the
-// rows' Toeplitz matrices, added into the three open output groups ring[0..2] = groups G-2, G-1, G.
-// Adds the product tile of kernel row RY (moved by RY = 16 a + b rows) into tile W of its two output groups.
-template <int RY, int W>
-__device__ __forceinline__ void c2_add_tile(const floatx4& d, floatx4 (&ring)[3][kC2Tiles]) {
-    constexpr int a = RY >> 4, b = RY & 15;
+// Adds a product tile moved by B rows into tile W of the two open output groups
+// ring[1] = group G (rows n >= B) and ring[0] = group G - 1 (rows n < B).
+template <int B, int W>
+__device__ __forceinline__ void c2_add_tile(const floatx4& d, floatx4 (&ring)[2][kC2Tiles]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        ring[2 - a][W][j] = c2_shift_add<b>(ring[2 - a][W][j], d[j]);
-        if constexpr (b != 0) ring[1 - a][W][j] = c2_shift_add<b - 16>(ring[1 - a][W][j], d[j]);
+        ring[1][W][j] = c2_shift_add<B>(ring[1][W][j], d[j]);
+        if constexpr (B != 0) ring[0][W][j] = c2_shift_add<B - 16>(ring[0][W][j], d[j]);
     }
 }
 
-// A block of four kernel rows is 8 pairs of tiles: pair P = (row R4 + P / 2, tiles 2 (P % 2) and
-// 2 (P % 2) + 1).  The products of pair P + 1 are interleaved with the additions of pair P, so the
-// vector ALU adds two tiles while the matrix unit multiplies the next two; inside a pair the two
-// tiles' products alternate, so no product waits for the one it accumulates onto.
-template <int NK, int R4, int P>
-__device__ __forceinline__ void c2_pairs(const half8* s_frag, int lane, const half8 (&px)[kC2Tiles][NK],
-                                         floatx4 (&ring)[3][kC2Tiles], const half8 (&coef)[NK],
-                                         const half8 (&ahead_in)[NK], const floatx4& da, const floatx4& db) {
-    constexpr int ry = R4 + P / 2, w = 2 * (P % 2);
-    half8 ahead[NK];
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) ahead[kk] = ahead_in[kk];
-    if constexpr (w == 0 && ry + 1 < R4 + 4) {
-        // first pair of a kernel row: request the next row's fragments
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) ahead[kk] = s_frag[((ry + 1) * NK + kk) * 64 + lane];
-    }
-    if constexpr (P + 1 < 8) {
-        constexpr int w1 = 2 * ((P + 1) % 2);
-        half8 cnext[NK];
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) cnext[kk] = w1 == 0 ? ahead[kk] : coef[kk];
-        floatx4 na = {0.f, 0.f, 0.f, 0.f}, nb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) {
-            na = mfma16x16x32(cnext[kk], px[w1][kk], na);
-            nb = mfma16x16x32(cnext[kk], px[w1 + 1][kk], nb);
-        }
-        c2_add_tile<ry, w>(da, ring);
-        c2_add_tile<ry, w + 1>(db, ring);
-        // One product, then its share of the additions: a product occupies the matrix unit for as
-        // long as four additions take to issue, so neither unit waits for the other.  (Products
-        // issued back to back would block the wave's instruction stream until the unit is free.)
-#pragma unroll
-        for (int i = 0; i < 2 * NK; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, ((ry & 15) ? 16 : 8) / (2 * NK), 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        c2_pairs<NK, R4, P + 1>(s_frag, lane, px, ring, cnext, ahead, na, nb);
-    } else {
-        c2_add_tile<ry, w>(da, ring);
-        c2_add_tile<ry, w + 1>(db, ring);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
-
-// Four kernel rows R4 .. R4+3 of one step: the windows `px` of one group of 16 input rows times the
-// rows' Toeplitz matrices, added into the three open output groups ring[0..2] = groups G-2, G-1, G.
-template <int NK, int R4>
-__device__ __forceinline__ void c2_rows4(const half8* s_frag, int lane, const half8 (&px)[kC2Tiles][NK],
-                                         floatx4 (&ring)[3][kC2Tiles]) {
-    static_assert(kC2Tiles == 4, "pairs of tiles");
-    half8 coef[NK];
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) coef[kk] = s_frag[(R4 * NK + kk) * 64 + lane];
-    floatx4 da = {0.f, 0.f, 0.f, 0.f}, db = {0.f, 0.f, 0.f, 0.f};
+// The fragments of kernel rows B (and, with UP, B + 16): [0][kk] lower row, [1][kk] upper row.
+template <int NK, bool UP>
+__device__ __forceinline__ void c2_read_frags(const half8* s_frag, int lane, int b, half8 (&f)[2][NK]) {
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) {
-        da = mfma16x16x32(coef[kk], px[0][kk], da);
-        db = mfma16x16x32(coef[kk], px[1][kk], db);
-    }
-    c2_pairs<NK, R4, 0>(s_frag, lane, px, ring, coef, coef, da, db);
-}
-
-// Kernel rows R0 .. R1-1 in blocks of four; blocks at or beyond kh are skipped (uniform branch), rows
-// beyond kh inside a block have zero fragments.
-template <int NK, int R0, int R1>
-__device__ __forceinline__ void c2_blocks(const half8* s_frag, int lane, int kh, const half8 (&px)[kC2Tiles][NK],
-                                          floatx4 (&ring)[3][kC2Tiles]) {
-    if constexpr (R0 < R1) {
-        if (R0 < kh) c2_rows4<NK, R0>(s_frag, lane, px, ring);
-        c2_blocks<NK, R0 + 4, R1>(s_frag, lane, kh, px, ring);
+        f[0][kk] = s_frag[(b * NK + kk) * 64 + lane];
+        if (UP) f[1][kk] = s_frag[((b + 16) * NK + kk) * 64 + lane];
     }
 }
 
-// One step of the walk: kernel rows R0 .. R1-1 (multiples of four) against one input group.
-template <int NK, int R0, int R1>
-__device__ __forceinline__ void c2_step(const half8* s_frag, int lane, int kh, const half8 (&px)[kC2Tiles][NK],
-                                        floatx4 (&ring)[3][kC2Tiles]) {
-    c2_blocks<NK, R0, R1>(s_frag, lane, kh, px, ring);
-    // Pin the sums here: otherwise the additions are sunk below the caller's store and every
-    // shifted product stays live (and is spilled) until then.
+// The product tiles of two neighbouring strip tiles W, W + 1 for the shift of `f`: lower kernel row
+// times input group G, plus (UP) upper kernel row times input group G + 1.  The two tiles' products
+// alternate, so no product waits for the one it accumulates onto.
+template <int NK, bool UP, int W>
+__device__ __forceinline__ void c2_products(const half8 (&f)[2][NK], const half8 (&x0)[kC2Tiles][NK],
+                                            const half8 (&x1)[kC2Tiles][NK], floatx4& da, floatx4& db) {
+    da = floatx4{0.f, 0.f, 0.f, 0.f};
+    db = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
+    for (int kk = 0; kk < NK; ++kk) {
+        da = mfma16x16x32(f[0][kk], x0[W][kk], da);
+        db = mfma16x16x32(f[0][kk], x0[W + 1][kk], db);
+    }
+    if (UP) {
 #pragma unroll
-        for (int w = 0; w < kC2Tiles; ++w)
+        for (int kk = 0; kk < NK; ++kk) {
+            da = mfma16x16x32(f[1][kk], x1[W][kk], da);
+            db = mfma16x16x32(f[1][kk], x1[W + 1][kk], db);
+        }
+    }
+}
+
+// A block of four shifts B4 .. B4+3 is 8 pairs of tiles: pair P = (shift B4 + P / 2, tiles 2 (P % 2)
+// and 2 (P % 2) + 1).  The products of pair P + 1 are interleaved with the additions of pair P, so
+// the vector ALU adds two tiles while the matrix unit multiplies the next two.
+template <int NK, bool UP, int B4, int P>
+__device__ __forceinline__ void c2_pairs(const half8* s_frag, int lane, const half8 (&x0)[kC2Tiles][NK],
+                                         const half8 (&x1)[kC2Tiles][NK], floatx4 (&ring)[2][kC2Tiles],
+                                         const half8 (&frag)[2][NK], const half8 (&ahead_in)[2][NK],
+                                         const floatx4& da, const floatx4& db) {
+    constexpr int b = B4 + P / 2, w = 2 * (P % 2);
+    half8 ahead[2][NK];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(ring[r][w][j]));
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) ahead[u][kk] = ahead_in[u][kk];
+    // first pair of a shift: request the next shift's fragments
+    if constexpr (w == 0 && b + 1 < B4 + 4) c2_read_frags<NK, UP>(s_frag, lane, b + 1, ahead);
+    if constexpr (P + 1 < 8) {
+        constexpr int w1 = 2 * ((P + 1) % 2);
+        half8 fnext[2][NK];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) fnext[u][kk] = w1 == 0 ? ahead[u][kk] : frag[u][kk];
+        floatx4 na, nb;
+        c2_products<NK, UP, w1>(fnext, x0, x1, na, nb);
+        c2_add_tile<b, w>(da, ring);
+        c2_add_tile<b, w + 1>(db, ring);
+        // One product, then its share of the additions, so that both units stay busy.  (Products
+        // issued back to back block the wave's instruction stream until the matrix unit is free.)
+        constexpr int nprod = 2 * NK * (UP ? 2 : 1), nadd = b ? 16 : 8;
+#pragma unroll
+        for (int i = 0; i < nprod; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, nadd / nprod, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        c2_pairs<NK, UP, B4, P + 1>(s_frag, lane, x0, x1, ring, fnext, ahead, na, nb);
+    } else {
+        c2_add_tile<b, w>(da, ring);
+        c2_add_tile<b, w + 1>(db, ring);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Four shifts B4 .. B4+3 of one step.
+template <int NK, bool UP, int B4>
+__device__ __forceinline__ void c2_rows4(const half8* s_frag, int lane, const half8 (&x0)[kC2Tiles][NK],
+                                         const half8 (&x1)[kC2Tiles][NK], floatx4 (&ring)[2][kC2Tiles]) {
+    static_assert(kC2Tiles == 4, "pairs of tiles");
+    half8 frag[2][NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) frag[1][kk] = half8{};
+    c2_read_frags<NK, UP>(s_frag, lane, B4, frag);
+    floatx4 da, db;
+    c2_products<NK, UP, 0>(frag, x0, x1, da, db);
+    c2_pairs<NK, UP, B4, 0>(s_frag, lane, x0, x1, ring, frag, frag, da, db);
+}
+
+// One step of the walk: input groups G (windows x0) and G + 1 (windows x1) against the kernel rows
+// b and b + 16 for every shift b < 16, in blocks of four shifts.  Blocks at or beyond kh are skipped
+// and the upper rows of a block are left out when they all lie at or beyond kh (uniform branches);
+// single rows beyond kh inside a block have zero fragments.
+template <int NK, int KH16, int B4 = 0>
+__device__ __forceinline__ void c2_step(const half8* s_frag, int lane, int kh, const half8 (&x0)[kC2Tiles][NK],
+                                        const half8 (&x1)[kC2Tiles][NK], floatx4 (&ring)[2][kC2Tiles]) {
+    if constexpr (B4 < 16) {
+        if (B4 < kh) {
+            if (KH16 == 2 && B4 + 16 < kh) c2_rows4<NK, true, B4>(s_frag, lane, x0, x1, ring);
+            else c2_rows4<NK, false, B4>(s_frag, lane, x0, x1, ring);
+        }
+        c2_step<NK, KH16, B4 + 4>(s_frag, lane, kh, x0, x1, ring);
+    } else {
+        // Pin the sums here: otherwise the additions are sunk below the caller's store and every
+        // shifted product stays live (and is spilled) until then.
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int w = 0; w < kC2Tiles; ++w)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(ring[r][w][j]));
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -240,51 +266,44 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
         }
     };
 
-    floatx4 ring[3][NW];
+    floatx4 ring[2][NW], done[NW];            // open groups G - 1 and G; the group completed by the previous step
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
-#pragma unroll
-        for (int w = 0; w < NW; ++w) ring[r][w] = floatx4{0.f, 0.f, 0.f, 0.f};
-    half8 cur[NW][NK], nxt[NW][NK];
-    floatx4 done[NW];                         // the output group completed by the previous step
-#pragma unroll
-    for (int w = 0; w < NW; ++w) done[w] = floatx4{0.f, 0.f, 0.f, 0.f};
-    load_group(q0, cur);
-    // input groups q0 .. q1 + KH16 - 1 feed the output groups q0 .. q1 - 1
-    const int Gend = q1 + KH16;
+    for (int w = 0; w < NW; ++w) {
+        ring[0][w] = floatx4{0.f, 0.f, 0.f, 0.f};
+        ring[1][w] = floatx4{0.f, 0.f, 0.f, 0.f};
+        done[w] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    half8 wa[NW][NK], wb[NW][NK], wc[NW][NK];
+    load_group(q0, wa);
+    load_group(q0 + 1, wb);
+    // Output group Q takes its rows n >= b parts in step Q and its rows n < b parts in step Q + 1:
+    // steps q0 .. q1 complete the groups q0 .. q1 - 1.
 #pragma unroll 1
-    for (int G = q0; G < Gend; ++G) {
+    for (int G = q0; G <= q1; ++G) {
         // The finished group leaves before this step's loads are issued: loads and stores share one
-        // counter, and a wait for the loads at the end of the step would otherwise also wait for
-        // the write acknowledgements of stores issued just before it.
-        if (G - 3 >= q0 && G - 3 < q1) store_group(G - 3, done);
-        load_group(G + 1, nxt);               // clamped rows: always inside the image
+        // counter, and a wait for the loads would otherwise also wait for the write
+        // acknowledgements of stores issued just before it.
+        if (G - 2 >= q0) store_group(G - 2, done);
+        load_group(G + 2, wc);                // clamped rows: always inside the image
         // The fragment reads do not depend on G; left alone the compiler lifts all of them out of
         // the loop and spills.  An opaque copy of the lane index keeps them inside.
         int fl = lane;
         asm volatile("" : "+v"(fl));
-        if (KH16 == 2 && G == Gend - 1) {
-            c2_step<NK, 16, KR>(s_frag, fl, p.kh, cur, ring);      // only kernel rows >= 16 still reach group q1 - 1
-        } else if (KH16 == 2 && G == q0) {
-            c2_step<NK, 0, 16>(s_frag, fl, p.kh, cur, ring);       // rows >= 16 would feed groups above q0
-        } else {
-            c2_step<NK, 0, KR>(s_frag, fl, p.kh, cur, ring);
-        }
-        // ring[0] = group G - 2 is complete: no later input group reaches it
+        c2_step<NK, KH16>(s_frag, fl, p.kh, wa, wb, ring);
+        // ring[0] = group G - 1 is complete: no later input group reaches it
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             done[w] = ring[0][w];
             ring[0][w] = ring[1][w];
-            ring[1][w] = ring[2][w];
-            ring[2][w] = floatx4{0.f, 0.f, 0.f, 0.f};
+            ring[1][w] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) cur[w][kk] = nxt[w][kk];
+            for (int kk = 0; kk < NK; ++kk) {
+                wa[w][kk] = wb[w][kk];
+                wb[w][kk] = wc[w][kk];
+            }
         }
     }
-    if (Gend - 3 >= q0 && Gend - 3 < q1) store_group(Gend - 3, done);
-    // KH16 == 1: the walk ends with input group q1, which completes output group q1 - 1; the last
-    // rotation moved it from ring[1] to ring[0]
-    if (KH16 == 1 && q1 > q0) store_group(q1 - 1, ring[0]);
+    if (q1 > q0) store_group(q1 - 1, done);
 }
 
 // ---------------------------------------------------------------------------
