@@ -49,6 +49,9 @@ def _load():
         L.hbo_sepblur.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, u16p, I, I]
         L.hbo_conv2d.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, I, I]
         L.hbo_conv2d.restype = None
+        for f in (L.hbo_down2, L.hbo_up2):
+            f.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, I, I]
+            f.restype = None
         L.hbo_sat2d.argtypes = [u16p, f64p, I, I, Lg, Lg]
         L.hbo_conv3x3.argtypes = [u16p, u16p, f64p, I, I, I, I, I]
         L.hbo_conv3x3_rows.argtypes = [u16p, u16p, f64p, I, I, I, I, I, I, I]
@@ -101,6 +104,32 @@ def conv2d(img, taps2d, anchor_y, anchor_x):
     H, W = img.shape
     out = np.empty((H, W), dtype=np.float64)
     _load().hbo_conv2d(pi, _f64(out), H, W, W, W, pk, k.shape[0], k.shape[1], int(anchor_y), int(anchor_x))
+    return out
+
+
+def down2(img, taps2d, anchor_y, anchor_x):
+    """out[y][x] = sum_{ry, rx} k[ry][rx] in[clampH(2y + ry - ay)][clampW(2x + rx - ax)]  (Sec. V-B, strided form)."""
+    img, pi = _u16(img)
+    k = np.ascontiguousarray(taps2d)
+    assert k.ndim == 2
+    k, pk = _u16(k)
+    H, W = img.shape
+    Ho, Wo = (H + 1) // 2, (W + 1) // 2
+    out = np.empty((Ho, Wo), dtype=np.float64)
+    _load().hbo_down2(pi, _f64(out), H, W, W, Wo, pk, k.shape[0], k.shape[1], int(anchor_y), int(anchor_x))
+    return out
+
+
+def up2(img, taps2d, anchor_y, anchor_x):
+    """out[y][x] = sum_{ry < kh/2, rx < kw/2} k[2ry + y%2][2rx + x%2] in[clampH(y//2 + ry - ay)][clampW(x//2 + rx - ax)]
+    (Sec. V-B, multiphase form)."""
+    img, pi = _u16(img)
+    k = np.ascontiguousarray(taps2d)
+    assert k.ndim == 2 and k.shape[0] % 2 == 0 and k.shape[1] % 2 == 0
+    k, pk = _u16(k)
+    H, W = img.shape
+    out = np.empty((2 * H, 2 * W), dtype=np.float64)
+    _load().hbo_up2(pi, _f64(out), H, W, W, 2 * W, pk, k.shape[0], k.shape[1], int(anchor_y), int(anchor_x))
     return out
 
 

@@ -150,6 +150,68 @@ void hbo_conv2d(const uint16_t *in, double *out, int H, int W,
     free(k);
 }
 
+/* ---- resampling by a factor of two with an arbitrary kernel (Sec. V-B) ----
+ * Downsampling (strided convolution): O(x, y) = sum_{rx, ry} I(2x + rx, 2y + ry) K(rx, ry),
+ * here with explicit anchors and clamp-to-edge on both INPUT indices; the
+ * output has ceil(H/2) x ceil(W/2) samples.  taps[ry * kw + rx] = K(rx, ry). */
+
+void hbo_down2(const uint16_t *in, double *out, int H, int W,
+               long in_pitch, long out_pitch,
+               const uint16_t *taps, int kh, int kw, int ay, int ax)
+{
+    double *img = decode_image(in, H, W, in_pitch);
+    double *k = (double *)malloc((size_t)kh * (size_t)kw * sizeof(double));
+    if (!img || !k) { free(img); free(k); return; }
+    for (int i = 0; i < kh * kw; ++i) k[i] = hbo_half_to_double(taps[i]);
+    int Ho = (H + 1) / 2, Wo = (W + 1) / 2;
+#pragma omp parallel for schedule(static)
+    for (int y = 0; y < Ho; ++y) {
+        for (int x = 0; x < Wo; ++x) {
+            double acc = 0.0;
+            for (int ry = 0; ry < kh; ++ry) {
+                long yi = clampl(2L * y + ry - ay, 0, H - 1);
+                for (int rx = 0; rx < kw; ++rx) {
+                    long xi = clampl(2L * x + rx - ax, 0, W - 1);
+                    acc += k[ry * kw + rx] * img[(size_t)yi * W + xi];
+                }
+            }
+            out[(long)y * out_pitch + x] = acc;
+        }
+    }
+    free(img);
+    free(k);
+}
+
+/* Upsampling: O(x, y) = sum_{rx, ry} I(floor(x/2) + rx, floor(y/2) + ry) K(2 rx + x%2, 2 ry + y%2),
+ * rx < kw/2, ry < kh/2 (kh, kw even), anchors in input pixels, clamp-to-edge on
+ * both INPUT indices; the output has 2H x 2W samples. */
+
+void hbo_up2(const uint16_t *in, double *out, int H, int W,
+             long in_pitch, long out_pitch,
+             const uint16_t *taps, int kh, int kw, int ay, int ax)
+{
+    double *img = decode_image(in, H, W, in_pitch);
+    double *k = (double *)malloc((size_t)kh * (size_t)kw * sizeof(double));
+    if (!img || !k) { free(img); free(k); return; }
+    for (int i = 0; i < kh * kw; ++i) k[i] = hbo_half_to_double(taps[i]);
+#pragma omp parallel for schedule(static)
+    for (int y = 0; y < 2 * H; ++y) {
+        for (int x = 0; x < 2 * W; ++x) {
+            double acc = 0.0;
+            for (int ry = 0; ry < kh / 2; ++ry) {
+                long yi = clampl((long)(y / 2) + ry - ay, 0, H - 1);
+                for (int rx = 0; rx < kw / 2; ++rx) {
+                    long xi = clampl((long)(x / 2) + rx - ax, 0, W - 1);
+                    acc += k[(2 * ry + y % 2) * kw + 2 * rx + x % 2] * img[(size_t)yi * W + xi];
+                }
+            }
+            out[(long)y * out_pitch + x] = acc;
+        }
+    }
+    free(img);
+    free(k);
+}
+
 /* ---- separable blur: rows, then columns (Sec. V-A; the 2-D form with
  *      K(rx, ry) = kx[rx] * ky[ry]) ------------------------------------ */
 /* tmp[y][x] = sum_r kx[r] in[y][clampW(x + r - ax)]

@@ -526,3 +526,93 @@ def test_pyr_brute_force_8x8(orc):
         col = up1(lambda q, x=x: Ux[q][x], H)
         for y in range(H):
             assert res[y, x] == pytest.approx(I[y, x] - col[y], abs=1e-15)
+
+
+# --------------------------------------------------------------------------
+# down2 / up2: resampling by two with an arbitrary kernel (Sec. V-B)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("H,W,kh,kw,ay,ax", [(14, 18, 6, 8, 2, 3), (9, 7, 5, 3, 4, 0), (8, 8, 1, 1, 0, 0)])
+def test_down2_is_the_full_resolution_convolution_sampled_at_even_positions(orc, H, W, kh, kw, ay, ax):
+    """Strided convolution = plain convolution (pinned above), every second row and column."""
+    img, k = rand_img(121, H, W), rand_kernel(122, kh, kw)
+    assert np.allclose(orc.down2(img, k, ay, ax), orc.conv2d(img, k, ay, ax)[::2, ::2], atol=1e-14)
+
+
+def test_down2_impulse_and_constant(orc):
+    kh, kw, ay, ax = 6, 7, 2, 3
+    k = rand_kernel(123, kh, kw)
+    K = d(k)
+    img = np.zeros((20, 24))
+    r0, c0 = 9, 13
+    img[r0, c0] = 1.0
+    out = orc.down2(h(img), k, ay, ax)
+    expect = np.zeros((10, 12))
+    for y in range(10):
+        for x in range(12):
+            ry, rx = r0 - 2 * y + ay, c0 - 2 * x + ax
+            if 0 <= ry < kh and 0 <= rx < kw:
+                expect[y, x] = K[ry, rx]
+    assert np.array_equal(out, expect)
+    assert np.allclose(orc.down2(h(np.full((11, 13), 0.5)), k, ay, ax), 0.5 * K.sum(), atol=1e-15)
+
+
+def test_down2_with_the_binomial_kernel_is_the_pyramid_down_step(orc):
+    """K = w (x) w, w = [1,4,6,4,1]/16 (products exact in fp16), anchor 2: the pyramid oracle's D, pinned above."""
+    w = np.array([1, 4, 6, 4, 1]) / 16.0
+    img = rand_img(124, 16, 20)
+    _, D = orc.pyr_level(img, want_down=True)
+    assert np.allclose(orc.down2(img, h(np.outer(w, w)), 2, 2), D, atol=1e-15)
+
+
+@pytest.mark.parametrize("H,W,kh,kw,ay,ax", [(7, 9, 6, 8, 1, 2), (5, 6, 2, 2, 0, 0), (6, 5, 4, 10, 1, 4)])
+def test_up2_phases_are_four_plain_convolutions(orc, H, W, kh, kw, ay, ax):
+    """O(2x+dx, 2y+dy) = convolution of I with K^phase(., ., dx, dy) = K[dy::2, dx::2] (Sec. V-B)."""
+    img, k = rand_img(125, H, W), rand_kernel(126, kh, kw)
+    out = orc.up2(img, k, ay, ax)
+    assert out.shape == (2 * H, 2 * W)
+    for dy in range(2):
+        for dx in range(2):
+            ph = orc.conv2d(img, np.ascontiguousarray(k[dy::2, dx::2]), ay, ax)
+            assert np.allclose(out[dy::2, dx::2], ph, atol=1e-14)
+
+
+def test_up2_as_a_scatter_of_input_pixels(orc):
+    """Second formulation: every (edge-padded) input pixel times every tap lands on exactly one output."""
+    H, W, kh, kw, ay, ax = 6, 7, 6, 4, 2, 1
+    img, k = rand_img(127, H, W), rand_kernel(128, kh, kw)
+    I, K = d(img), d(k)
+    P = np.pad(I, ((ay, kh // 2 - 1 - ay), (ax, kw // 2 - 1 - ax)), mode="edge")
+    expect = np.zeros((2 * H, 2 * W))
+    for i in range(P.shape[0]):
+        for j in range(P.shape[1]):
+            for u in range(kh):
+                for v in range(kw):
+                    # padded pixel (i, j) is input row i - ay; tap u = 2 ry + dy reads row y//2 + ry - ay
+                    y, x = 2 * (i - u // 2) + u % 2, 2 * (j - v // 2) + v % 2
+                    if 0 <= y < 2 * H and 0 <= x < 2 * W:
+                        expect[y, x] += K[u, v] * P[i, j]
+    assert np.allclose(orc.up2(img, k, ay, ax), expect, atol=1e-14)
+
+
+def test_up2_constant_image_gives_the_phase_sums(orc):
+    kh, kw = 8, 6
+    k = rand_kernel(129, kh, kw)
+    K = d(k)
+    out = orc.up2(h(np.full((5, 6), 0.25)), k, 1, 2)
+    for dy in range(2):
+        for dx in range(2):
+            assert np.allclose(out[dy::2, dx::2], 0.25 * K[dy::2, dx::2].sum(), atol=1e-15)
+
+
+def test_up2_with_the_pyramid_phases_interpolates_a_ramp(orc):
+    """The pyramid's 1-D phases (1,6,1)/8 and (1,1)/2 as K = [1,0,6,4,1,4]/8 per axis, anchor 1:
+    a linear ramp is reproduced at x/2 (even outputs) and (x+1)/2 - 1/2 + 1/2 (odd outputs: the mean
+    of two neighbours), away from the borders."""
+    w = np.array([1, 0, 6, 4, 1, 4]) / 8.0
+    H, W = 8, 12
+    ramp = np.add.outer(np.arange(H) * 4.0, np.arange(W) * 2.0)            # exact in fp16
+    out = orc.up2(h(ramp), h(np.outer(w, w)), 1, 1)
+    yy, xx = np.meshgrid(np.arange(2 * H), np.arange(2 * W), indexing="ij")
+    expect = 4.0 * (yy / 2.0) + 2.0 * (xx / 2.0)
+    assert np.allclose(out[2:-2, 2:-2], expect[2:-2, 2:-2], atol=1e-12)
