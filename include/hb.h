@@ -64,7 +64,7 @@ typedef void *hb_stream;      /* hipStream_t */
 
 #define HB_MAX_TAPS 64          /* per axis, hb_sepblur */
 #define HB_MAX_TAPS_FIR1D 256   /* hb_fir1d: the large-tap regime of Sec. V-A */
-#define HB_MAX_TAPS_CONV2D 32   /* per axis, hb_conv2d */
+#define HB_MAX_TAPS_CONV2D 32   /* per axis, hb_conv2d, hb_down2, hb_up2 */
 
 /* Human-readable name of a status code (static storage). */
 const char *hb_status_string(hb_status s);
@@ -103,6 +103,44 @@ hb_status hb_conv2d_valu(const hb_half *in, float *out, int H, int W,
                          int64_t in_pitch, int64_t out_pitch,
                          const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
                          hb_stream stream);
+
+/*
+ * Resampling by a factor of two with an arbitrary 2-D kernel (Sec. V-B).
+ *
+ * hb_down2, the strided convolution (per kernel row a product with the
+ * Toeplitz-like matrix A^down_K(x, y) = K(y - 2x)):
+ *     out[y][x] = sum_{ry < kh} sum_{rx < kw} taps[ry * kw + rx]
+ *                 * in[clampH(2y + ry - anchor_y)][clampW(2x + rx - anchor_x)]
+ * in: H x W fp16, out: ceil(H/2) x ceil(W/2) fp32; 0 <= anchor_y < kh, 0 <= anchor_x < kw.
+ *
+ * hb_up2, the multiphase filter K^phase(x, y, dx, dy) = K(2x + dx, 2y + dy):
+ *     out[y][x] = sum_{ry < kh/2} sum_{rx < kw/2} taps[(2 ry + y%2) * kw + 2 rx + x%2]
+ *                 * in[clampH(y/2 + ry - anchor_y)][clampW(x/2 + rx - anchor_x)]
+ * in: H x W fp16, out: 2H x 2W fp32; kh and kw even; anchors count input pixels:
+ * 0 <= anchor_y < kh/2, 0 <= anchor_x < kw/2.
+ *
+ * Both: taps_host is kh x kw fp16 bit patterns, row-major, HOST memory, read
+ * before the call returns; 1 <= kh, kw <= HB_MAX_TAPS_CONV2D; pitches in elements
+ * of the respective image; HB_ERR_INVALID_ARG for bad shapes, taps or anchors,
+ * HB_ERR_UNSUPPORTED beyond the size limits of hb_fir1d (applied to the input and
+ * to the output image).
+ */
+hb_status hb_down2(const hb_half *in, float *out, int H, int W,
+                   int64_t in_pitch, int64_t out_pitch,
+                   const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
+                   hb_stream stream);
+hb_status hb_down2_valu(const hb_half *in, float *out, int H, int W,
+                        int64_t in_pitch, int64_t out_pitch,
+                        const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
+                        hb_stream stream);
+hb_status hb_up2(const hb_half *in, float *out, int H, int W,
+                 int64_t in_pitch, int64_t out_pitch,
+                 const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
+                 hb_stream stream);
+hb_status hb_up2_valu(const hb_half *in, float *out, int H, int W,
+                      int64_t in_pitch, int64_t out_pitch,
+                      const hb_half *taps_host, int kh, int kw, int anchor_y, int anchor_x,
+                      hb_stream stream);
 
 /*
  * Separable 2-D blur (Sec. V-A, the 2-D form with K(rx, ry) = kx[rx] ky[ry]; the

@@ -29,6 +29,7 @@ SYMBOLS = [
     "hb_status_string",
     "hb_fir1d", "hb_fir1d_valu",
     "hb_conv2d", "hb_conv2d_valu",
+    "hb_down2", "hb_down2_valu", "hb_up2", "hb_up2_valu",
     "hb_sepblur", "hb_sepblur_valu",
     "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu",
     "hb_conv3x3", "hb_conv3x3_valu",
@@ -64,7 +65,8 @@ def load() -> ctypes.CDLL:
     sat = [vp, vp, I, I, I64, I64, vp, ctypes.c_size_t, vp]
     conv = [vp, vp, vp, I, I, I, I, I, vp]
     pyr = [vp, vp, vp, I, I, I64, I64, I64, vp]
-    for name, sig in (("hb_fir1d", fir), ("hb_fir1d_valu", fir), ("hb_conv2d", c2d), ("hb_conv2d_valu", c2d), ("hb_sepblur", sep), ("hb_sepblur_valu", sep),
+    for name, sig in (("hb_fir1d", fir), ("hb_fir1d_valu", fir), ("hb_conv2d", c2d), ("hb_conv2d_valu", c2d),
+                      ("hb_down2", c2d), ("hb_down2_valu", c2d), ("hb_up2", c2d), ("hb_up2_valu", c2d), ("hb_sepblur", sep), ("hb_sepblur_valu", sep),
                       ("hb_sat2d", sat), ("hb_sat2d_valu", sat), ("hb_conv3x3", conv), ("hb_conv3x3_valu", conv),
                       ("hb_pyr_level", pyr), ("hb_pyr_level_valu", pyr),
                       ("hb_copy_f16_f32", [vp, vp, I64, vp]), ("hb_mfma_probe", [I, vp, vp, vp, vp])):
@@ -124,11 +126,11 @@ def hb_fir1d_valu(inp, out, taps, anchor):
     return _fir("hb_fir1d_valu", inp, out, taps, anchor)
 
 
-def _conv2d(name, inp, out, taps2d, anchor_y, anchor_x):
+def _conv2d(name, inp, out, taps2d, anchor_y, anchor_x, shape=lambda H, W: (H, W)):
     import torch
     pi, H, W, ip = _img2d(inp, torch.float16)
     po, Ho, Wo, op = _img2d(out, torch.float32)
-    assert (H, W) == (Ho, Wo)
+    assert shape(H, W) == (Ho, Wo), "output shape"
     k = np.asarray(taps2d)
     assert k.ndim == 2, "kh x kw tap array expected"
     keep, pt, n = _taps(k)
@@ -143,6 +145,30 @@ def hb_conv2d(inp, out, taps2d, anchor_y, anchor_x):
 
 def hb_conv2d_valu(inp, out, taps2d, anchor_y, anchor_x):
     return _conv2d("hb_conv2d_valu", inp, out, taps2d, anchor_y, anchor_x)
+
+
+def _half_shape(H, W):
+    return (H + 1) // 2, (W + 1) // 2
+
+
+def _double_shape(H, W):
+    return 2 * H, 2 * W
+
+
+def hb_down2(inp, out, taps2d, anchor_y, anchor_x):
+    return _conv2d("hb_down2", inp, out, taps2d, anchor_y, anchor_x, _half_shape)
+
+
+def hb_down2_valu(inp, out, taps2d, anchor_y, anchor_x):
+    return _conv2d("hb_down2_valu", inp, out, taps2d, anchor_y, anchor_x, _half_shape)
+
+
+def hb_up2(inp, out, taps2d, anchor_y, anchor_x):
+    return _conv2d("hb_up2", inp, out, taps2d, anchor_y, anchor_x, _double_shape)
+
+
+def hb_up2_valu(inp, out, taps2d, anchor_y, anchor_x):
+    return _conv2d("hb_up2_valu", inp, out, taps2d, anchor_y, anchor_x, _double_shape)
 
 
 def _sep(name, inp, out, tx, ax, ty, ay):
