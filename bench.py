@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -265,6 +265,27 @@ def main():
                 "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
                 "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms,
                 "mfma_tflops": 2.0 * k * k * npx / m_ms / 1e9}
+        # ... and the paper's resampling study (Sec. V-B): 2x down (4096^2 -> 2048^2) and 2x up
+        # (2048^2 -> 4096^2) with k x k kernels.  Pixels are counted on the larger image.
+        half_out = [torch.empty((2048, 2048), dtype=torch.float32, device=dev) for _ in range(4)]
+        half_in = [t[:2048, :2048] for t in lx]              # row pitch 4096
+        for k in (16, 32):
+            k2d = synth.random_kernel2d_f16(2400 + k, k, k)
+            for name, src, dst, anc in (("down2", lx, half_out, k // 2), ("up2", half_in, lo, k // 4)):
+                def timed3(fn, iters):
+                    for i in range(2):
+                        fn(src[i % 4], dst[i % 4], k2d, anc, anc)
+                    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a0.record()
+                    for i in range(iters):
+                        fn(src[i % 4], dst[i % 4], k2d, anc, anc)
+                    a1.record()
+                    torch.cuda.synchronize()
+                    return a0.elapsed_time(a1) / iters
+                m_ms, v_ms = timed3(getattr(hb, "hb_" + name), 10), timed3(getattr(hb, "hb_" + name + "_valu"), 3)
+                out["supplementary"]["%s_%dx%d_4096x4096" % (name, k, k)] = {
+                    "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
+                    "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)

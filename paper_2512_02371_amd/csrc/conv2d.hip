@@ -271,7 +271,7 @@ extern "C" hb_status hb_conv2d(const hb_half* in, float* out, int H, int W,
     // (kernel rows / 16) extra input groups, so runs are as long as filling the chip allows.
     const int waves = kNumCU * (kC2Threads / 64);
     int len = (int)(((int64_t)a.nstrips * a.ngroups + waves - 1) / waves);
-    if (len < 4) len = a.ngroups < 4 ? a.ngroups : 4;
+    if (len < 2) len = a.ngroups < 2 ? a.ngroups : 2;
     a.seg_len = len;
     a.nseg = ceil_div(a.ngroups, len);
     const int64_t ntasks = (int64_t)a.nstrips * a.nseg;
@@ -282,8 +282,7 @@ extern "C" hb_status hb_conv2d(const hb_half* in, float* out, int H, int W,
     const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
 #define HB_C2_LAUNCH(N, K, S)                                                                         \
     {                                                                                                 \
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_mfma_kernel<N, K, S>),          \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)  \
+        if (allow_dynamic_lds(reinterpret_cast<const void*>(&conv2d_mfma_kernel<N, K, S>), lds) != HB_OK) \
             return HB_ERR_HIP;                                                                        \
         hipLaunchKernelGGL((conv2d_mfma_kernel<N, K, S>), dim3(blocks), dim3(kC2Threads), lds, st, a); \
     }

@@ -5,6 +5,10 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "hb.h"
 
 namespace hb {
@@ -119,6 +123,21 @@ inline FoldTablesT<MAXT> pack_fold_tables(const hb_half* taps, int ntaps) {
 }
 
 inline hb_status launch_status() { return hipGetLastError() == hipSuccess ? HB_OK : HB_ERR_HIP; }
+
+// Raises a kernel's dynamic LDS limit to `bytes`.  The runtime call costs about ten microseconds of
+// host time, so it is made once per kernel and device (and again only for a larger size).
+inline hb_status allow_dynamic_lds(const void* kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, size_t> raised;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return HB_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t& have = raised[std::make_pair(kernel, dev)];
+    if (have >= bytes) return HB_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return HB_ERR_HIP;
+    have = bytes;
+    return HB_OK;
+}
 
 inline int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

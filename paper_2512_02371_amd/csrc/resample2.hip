@@ -399,7 +399,7 @@ static hb_status rs2_prepare(Rs2Args& a, bool up, const hb_half* in, float* out,
     // one task per wave: a strip times a run of groups, as long as filling the chip allows
     const int waves = kNumCU * (kC2Threads / 64);
     int len = (int)(((int64_t)a.nstrips * a.ngroups + waves - 1) / waves);
-    if (len < 4) len = a.ngroups < 4 ? a.ngroups : 4;
+    if (len < 2) len = a.ngroups < 2 ? a.ngroups : 2;
     a.seg_len = len;
     a.nseg = ceil_div(a.ngroups, len);
     const int64_t ntasks = (int64_t)a.nstrips * a.nseg;
@@ -411,8 +411,7 @@ static hb_status rs2_prepare(Rs2Args& a, bool up, const hb_half* in, float* out,
 template <class K>
 static hb_status rs2_launch_mfma(K kernel, const Rs2Args& a, size_t table_bytes, hipStream_t st) {
     const size_t lds = table_bytes + (kC2Threads / 64) * RowPatch<kC2Tiles>::kFloats * sizeof(float);
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return HB_ERR_HIP;
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds) != HB_OK) return HB_ERR_HIP;
     hipLaunchKernelGGL(kernel, dim3(ceil_div(a.ntasks, kC2Threads / 64)), dim3(kC2Threads), lds, st, a);
     return launch_status();
 }

@@ -88,6 +88,38 @@ def test_conv2d_argument_validation(lib, fn):
     assert call(H=1 << 16, W=1 << 15, ip=1 << 15, op=1 << 15) == hb.HB_ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("fn", ["hb_down2", "hb_down2_valu", "hb_up2", "hb_up2_valu"])
+def test_resample2_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    k = np.zeros(32 * 32, dtype=np.uint16)
+    kp = k.ctypes.data_as(ctypes.c_void_p)
+    upsample = "up2" in fn
+    # 16 x 16 input; the output pitch must cover 8 (down) or 32 (up) samples
+    ok = dict(i=FAKE, o=FAKE, H=16, W=16, ip=16, op=32, t=kp, kh=6, kw=8, ay=2, ax=3)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["H"], p["W"], p["ip"], p["op"], p["t"], p["kh"], p["kw"], p["ay"], p["ax"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(t=None) == hb.HB_ERR_INVALID_ARG
+    assert call(W=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=15) == hb.HB_ERR_INVALID_ARG
+    assert call(op=31 if upsample else 7) == hb.HB_ERR_INVALID_ARG
+    assert call(kh=0) == hb.HB_ERR_INVALID_ARG
+    assert call(kw=34) == hb.HB_ERR_INVALID_ARG
+    assert call(ay=-1) == hb.HB_ERR_INVALID_ARG
+    if upsample:
+        assert call(kh=5) == hb.HB_ERR_INVALID_ARG          # odd kernel sizes have no two phases
+        assert call(kw=7) == hb.HB_ERR_INVALID_ARG
+        assert call(ay=3) == hb.HB_ERR_INVALID_ARG          # anchors count input pixels: < kh / 2
+        assert call(ax=4) == hb.HB_ERR_INVALID_ARG
+    else:
+        assert call(ay=6) == hb.HB_ERR_INVALID_ARG
+        assert call(ax=8) == hb.HB_ERR_INVALID_ARG
+    assert call(H=1 << 16, W=1 << 15, ip=1 << 15, op=1 << 16) == hb.HB_ERR_UNSUPPORTED
+
+
 def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
