@@ -49,6 +49,8 @@ def _load():
         L.hbo_sepblur.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, u16p, I, I]
         L.hbo_conv2d.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, I, I]
         L.hbo_conv2d.restype = None
+        L.hbo_band_resize.argtypes = [u16p, f64p, I, I, I, I, Lg, Lg, i32p, u16p, I, i32p, u16p, I]
+        L.hbo_band_resize.restype = None
         for f in (L.hbo_down2, L.hbo_up2):
             f.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, I, I]
             f.restype = None
@@ -131,6 +133,55 @@ def up2(img, taps2d, anchor_y, anchor_x):
     out = np.empty((2 * H, 2 * W), dtype=np.float64)
     _load().hbo_up2(pi, _f64(out), H, W, W, 2 * W, pk, k.shape[0], k.shape[1], int(anchor_y), int(anchor_x))
     return out
+
+
+def band_resize(img, start_y, coef_y, start_x, coef_x):
+    """One plane resized with two banded matrices (Sec. V-C): row o of a matrix holds `band` fp16
+    coefficients for the input indices start[o] .. start[o] + band - 1 (clamped into the image)."""
+    img, pi = _u16(img)
+    H, W = img.shape
+    cy, pcy = _u16(np.ascontiguousarray(coef_y))
+    cx, pcx = _u16(np.ascontiguousarray(coef_x))
+    sy = np.ascontiguousarray(start_y, dtype=np.int32)
+    sx = np.ascontiguousarray(start_x, dtype=np.int32)
+    Ho, by = cy.shape
+    Wo, bx = cx.shape
+    assert sy.shape == (Ho,) and sx.shape == (Wo,)
+    i32p = ctypes.POINTER(ctypes.c_int)
+    out = np.empty((Ho, Wo), dtype=np.float64)
+    _load().hbo_band_resize(pi, _f64(out), H, W, Ho, Wo, W, Wo, sy.ctypes.data_as(i32p), pcy, by,
+                            sx.ctypes.data_as(i32p), pcx, bx)
+    return out
+
+
+def lanczos3(x):
+    """The three-lobed Lanczos window sinc(x) sinc(x/3) on [-3, 3], 0 outside (Sec. V-C)."""
+    x = np.asarray(x, dtype=np.float64)
+    return np.where(np.abs(x) < 3.0, np.sinc(x) * np.sinc(x / 3.0), 0.0)
+
+
+def lanczos3_matrix(n_in: int, n_out: int):
+    """Banded matrix (start, coef) that resamples n_in samples to n_out <= n_in (Sec. V-C): output o
+    sits at input position (o + 1/2) n_in/n_out - 1/2; the pre-filter is the Lanczos window stretched
+    by the factor n_in/n_out; every row is normalised to sum 1 in fp64.  Returned in fp64, unrounded."""
+    assert 1 <= n_out <= n_in
+    scale = n_in / n_out
+    band = lanczos3_band(n_in, n_out)
+    start = np.empty(n_out, dtype=np.int32)
+    coef = np.zeros((n_out, band), dtype=np.float64)
+    for o in range(n_out):
+        centre = (o + 0.5) * scale - 0.5
+        first = int(np.ceil(centre - 3.0 * scale))
+        idx = first + np.arange(band)
+        w = lanczos3((idx - centre) / scale)
+        start[o] = first
+        coef[o] = w / w.sum()
+    return start, coef
+
+
+def lanczos3_band(n_in: int, n_out: int) -> int:
+    """Entries per row: the stretched window covers at most floor(6 n_in/n_out) + 1 input samples."""
+    return int(np.floor(6.0 * n_in / n_out)) + 1
 
 
 def sepblur(img, taps_x, anchor_x, taps_y, anchor_y):

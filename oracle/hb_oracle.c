@@ -212,6 +212,45 @@ void hbo_up2(const uint16_t *in, double *out, int H, int W,
     free(k);
 }
 
+/* ---- resampling by a non-integer factor with precomputed banded matrices
+ *      (Sec. V-C): each axis is one sparse matrix whose row o has `band`
+ *      entries starting at input index start[o]; vertical and horizontal
+ *      resizing are separable.  One plane:
+ *        out[yo][xo] = sum_i sum_j cy[yo][i] cx[xo][j]
+ *                      * in[clampH(sy[yo] + i)][clampW(sx[xo] + j)]        */
+
+void hbo_band_resize(const uint16_t *in, double *out, int H, int W, int Ho, int Wo,
+                     long in_pitch, long out_pitch,
+                     const int *sy, const uint16_t *cy, int by,
+                     const int *sx, const uint16_t *cx, int bx)
+{
+    double *img = decode_image(in, H, W, in_pitch);
+    double *ky = (double *)malloc((size_t)Ho * (size_t)by * sizeof(double));
+    double *kx = (double *)malloc((size_t)Wo * (size_t)bx * sizeof(double));
+    if (!img || !ky || !kx) { free(img); free(ky); free(kx); return; }
+    for (long i = 0; i < (long)Ho * by; ++i) ky[i] = hbo_half_to_double(cy[i]);
+    for (long i = 0; i < (long)Wo * bx; ++i) kx[i] = hbo_half_to_double(cx[i]);
+#pragma omp parallel for schedule(static)
+    for (int yo = 0; yo < Ho; ++yo) {
+        for (int xo = 0; xo < Wo; ++xo) {
+            double acc = 0.0;
+            for (int i = 0; i < by; ++i) {
+                long yi = clampl((long)sy[yo] + i, 0, H - 1);
+                double row = 0.0;
+                for (int j = 0; j < bx; ++j) {
+                    long xi = clampl((long)sx[xo] + j, 0, W - 1);
+                    row += kx[(size_t)xo * bx + j] * img[(size_t)yi * W + xi];
+                }
+                acc += ky[(size_t)yo * by + i] * row;
+            }
+            out[(long)yo * out_pitch + xo] = acc;
+        }
+    }
+    free(img);
+    free(ky);
+    free(kx);
+}
+
 /* ---- separable blur: rows, then columns (Sec. V-A; the 2-D form with
  *      K(rx, ry) = kx[rx] * ky[ry]) ------------------------------------ */
 /* tmp[y][x] = sum_r kx[r] in[y][clampW(x + r - ax)]

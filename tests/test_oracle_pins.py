@@ -616,3 +616,86 @@ def test_up2_with_the_pyramid_phases_interpolates_a_ramp(orc):
     yy, xx = np.meshgrid(np.arange(2 * H), np.arange(2 * W), indexing="ij")
     expect = 4.0 * (yy / 2.0) + 2.0 * (xx / 2.0)
     assert np.allclose(out[2:-2, 2:-2], expect[2:-2, 2:-2], atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# band_resize / lanczos3: resampling by a non-integer factor (Sec. V-C)
+# --------------------------------------------------------------------------
+
+def test_lanczos3_closed_form_values(orc):
+    L = orc.lanczos3
+    assert L(0.0) == 1.0
+    assert np.allclose(L([1.0, -1.0, 2.0, -2.0, 3.0, -3.0, 3.5, -7.0]), 0.0, atol=1e-16)
+    assert L(0.5) == pytest.approx(6.0 / np.pi ** 2, abs=1e-15)            # sinc(1/2) sinc(1/6) = (2/pi)(3/pi)
+    assert L(1.5) == pytest.approx(-4.0 / (3.0 * np.pi ** 2), abs=1e-15)   # sinc(3/2) sinc(1/2)
+    assert L(-2.5) == pytest.approx(L(2.5), abs=0)
+
+
+def test_lanczos3_matrix_same_size_is_the_identity(orc):
+    start, coef = orc.lanczos3_matrix(37, 37)
+    assert coef.shape == (37, 7) and np.array_equal(start, np.arange(37) - 3)
+    assert np.allclose(coef, np.eye(7)[3], atol=1e-15)
+
+
+def test_lanczos3_matrix_rows_are_normalised_mirrored_and_centred(orc):
+    n_in, n_out = 2048, 143
+    start, coef = orc.lanczos3_matrix(n_in, n_out)
+    assert coef.shape[1] == orc.lanczos3_band(n_in, n_out) == 86
+    assert np.allclose(coef.sum(axis=1), 1.0, atol=1e-14)
+    # the sampling grid is symmetric about the middle of the signal: row n_out-1-o is row o mirrored
+    dense = np.zeros((n_out, n_in + 400))
+    for o in range(n_out):
+        dense[o, 200 + start[o]:200 + start[o] + coef.shape[1]] = coef[o]
+    assert np.allclose(dense, dense[::-1, ::-1], atol=1e-14)
+    # nothing of the window is cut off: the neighbours just outside the band lie outside [-3, 3] scales
+    scale = n_in / n_out
+    for o in (0, 71, 142):
+        centre = (o + 0.5) * scale - 0.5
+        assert start[o] - 1 < centre - 3 * scale <= start[o]
+        assert start[o] + coef.shape[1] > centre + 3 * scale - 1
+
+
+def test_lanczos3_matrix_factor_two_reproduces_a_ramp(orc):
+    """n_in = 2 n_out: the taps sit symmetrically about the output position 2o + 1/2, so a linear
+    signal is reproduced exactly (interior rows)."""
+    start, coef = orc.lanczos3_matrix(64, 32)
+    ramp = 3.0 * np.arange(64) + 1.0
+    for o in range(4, 28):
+        assert (coef[o] * ramp[start[o]:start[o] + coef.shape[1]]).sum() == pytest.approx(3.0 * (2 * o + 0.5) + 1.0, abs=1e-12)
+
+
+def test_band_resize_with_identity_matrices_returns_the_image(orc):
+    img = rand_img(131, 9, 11)
+    sy, sx = np.arange(9), np.arange(11)
+    one = lambda n: h(np.ones((n, 1)))
+    assert np.array_equal(orc.band_resize(img, sy, one(9), sx, one(11)), d(img))
+
+
+def test_band_resize_with_box_rows_is_the_strided_convolution(orc):
+    """start[o] = 2o, coefficients (1/2, 1/2) on both axes = down2 (pinned above) with the 2 x 2 box."""
+    img = rand_img(132, 12, 16)
+    half = h(np.full((1, 2), 0.5))
+    out = orc.band_resize(img, 2 * np.arange(6), np.repeat(half, 6, 0), 2 * np.arange(8), np.repeat(half, 8, 0))
+    assert np.allclose(out, orc.down2(img, h(np.full((2, 2), 0.25)), 0, 0), atol=1e-15)
+
+
+def test_band_resize_with_shifted_fixed_rows_is_the_separable_blur(orc):
+    """start[o] = o - anchor and the same taps in every row: the blur oracle (pinned above), incl. its clamp."""
+    H, W = 10, 13
+    img = rand_img(133, H, W)
+    ty, tx = rand_kernel(134, 1, 5)[0], rand_kernel(135, 1, 4)[0]
+    out = orc.band_resize(img, np.arange(H) - 3, np.tile(ty, (H, 1)), np.arange(W) - 1, np.tile(tx, (W, 1)))
+    assert np.allclose(out, orc.sepblur(img, tx, 1, ty, 3), atol=1e-14)
+
+
+def test_band_resize_brute_force_with_irregular_starts(orc):
+    H, W, Ho, Wo, by, bx = 9, 8, 4, 5, 3, 4
+    img = rand_img(136, H, W)
+    cy, cx = rand_kernel(137, Ho, by), rand_kernel(138, Wo, bx)
+    sy, sx = np.array([-2, 1, 5, 8]), np.array([-1, 0, 3, 3, 6])
+    I, Cy, Cx = d(img), d(cy), d(cx)
+    cl = lambda v, n: min(max(v, 0), n - 1)
+    for yo in range(Ho):
+        for xo in range(Wo):
+            e = sum(Cy[yo, i] * Cx[xo, j] * I[cl(sy[yo] + i, H), cl(sx[xo] + j, W)] for i in range(by) for j in range(bx))
+            assert orc.band_resize(img, sy, cy, sx, cx)[yo, xo] == pytest.approx(e, abs=1e-14)
