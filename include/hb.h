@@ -65,6 +65,7 @@ typedef void *hb_stream;      /* hipStream_t */
 #define HB_MAX_TAPS 64          /* per axis, hb_sepblur */
 #define HB_MAX_TAPS_FIR1D 256   /* hb_fir1d: the large-tap regime of Sec. V-A */
 #define HB_MAX_TAPS_CONV2D 32   /* per axis, hb_conv2d, hb_down2, hb_up2 */
+#define HB_RESIZE_MAX_SPAN 512   /* hb_resize: input samples one group of 16 outputs may span */
 
 /* Human-readable name of a status code (static storage). */
 const char *hb_status_string(hb_status s);
@@ -158,6 +159,50 @@ hb_status hb_sepblur_valu(const hb_half *in, float *out, int H, int W,
                           int64_t in_pitch, int64_t out_pitch,
                           const hb_half *taps_x_host, int ntaps_x, int anchor_x,
                           const hb_half *taps_y_host, int ntaps_y, int anchor_y, hb_stream stream);
+
+/*
+ * Resampling by a non-integer factor with precomputed banded matrices (Sec. V-C:
+ * vertical and horizontal resizing are separate sparse matrices with a band of
+ * known width; groups of 16 rows are treated as one dense block):
+ *     out[c][yo][xo] = sum_{i < band_y} sum_{j < band_x} coef_y[yo * band_y + i] * coef_x[xo * band_x + j]
+ *                      * in[c][clampH(start_y[yo] + i)][clampW(start_x[xo] + j)]
+ * The horizontal pass runs first; its result is rounded to fp16 and kept, transposed,
+ * in `workspace`.  in: C planes of H x W fp16 (row pitch in_pitch, plane stride in_plane,
+ * in elements); out: C planes of Ho x Wo fp32 (out_pitch, out_plane).
+ * start_y / start_x: Ho / Wo int32; coef_y / coef_x: Ho x band_y / Wo x band_x fp16,
+ * row-major.  All four are DEVICE pointers, read by the kernels on `stream`.
+ * `workspace`: device scratch of at least hb_resize_workspace_size(C, H, Wo) bytes,
+ * 256-byte aligned; contents undefined on exit; concurrent calls need their own.
+ * 1 <= band <= HB_RESIZE_MAX_SPAN.  Every read is clamped into the image whatever
+ * the matrices hold; of an aligned group of 16 outputs only the first
+ * HB_RESIZE_MAX_SPAN input samples from its smallest (even) start are used, so
+ * matrices whose groups span more lose those coefficients (hb_lanczos3_matrix
+ * never builds such a matrix when it succeeds for factors up to 24).
+ */
+size_t hb_resize_workspace_size(int C, int H, int Wo);
+hb_status hb_resize(const hb_half *in, float *out, void *workspace, size_t workspace_bytes,
+                    int C, int H, int W, int Ho, int Wo,
+                    int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                    const int32_t *start_y, const hb_half *coef_y, int band_y,
+                    const int32_t *start_x, const hb_half *coef_x, int band_x, hb_stream stream);
+hb_status hb_resize_valu(const hb_half *in, float *out, void *workspace, size_t workspace_bytes,
+                         int C, int H, int W, int Ho, int Wo,
+                         int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                         const int32_t *start_y, const hb_half *coef_y, int band_y,
+                         const int32_t *start_x, const hb_half *coef_x, int band_x, hb_stream stream);
+
+/*
+ * The banded matrix of a three-lobed Lanczos pre-filter, sinc(x) sinc(x/3) on [-3, 3]
+ * (Sec. V-C), that resamples n_in samples to n_out <= n_in: output o sits at input
+ * position (o + 1/2) n_in/n_out - 1/2, the window is stretched by n_in/n_out, every
+ * row is normalised to sum 1 (in double) and rounded once to fp16.  HOST function and
+ * HOST arrays: start_host[n_out], coef_host[n_out * hb_lanczos3_band(n_in, n_out)].
+ * hb_lanczos3_band returns the entries per row, floor(6 n_in/n_out) + 1, or 0 for
+ * bad sizes; hb_lanczos3_matrix returns HB_ERR_UNSUPPORTED if that exceeds
+ * HB_RESIZE_MAX_SPAN.
+ */
+int hb_lanczos3_band(int n_in, int n_out);
+hb_status hb_lanczos3_matrix(int n_in, int n_out, int32_t *start_host, hb_half *coef_host);
 
 /*
  * Summed-area table (inclusive prefix sum over rows and columns; a product

@@ -1,0 +1,353 @@
+// hb_resize: separable resampling by a non-integer factor with precomputed banded matrices, and
+// its vector-ALU twin (Sec. V-C); hb_lanczos3_matrix builds such a matrix on the host.
+//
+// Each axis is one sparse matrix: row o holds `band` coefficients for the input samples
+// start[o] .. start[o] + band - 1.  As in the paper the matrix is treated as block-sparse: the 16
+// rows of an aligned group share one starting index (the smallest of theirs, moved to an even
+// sample) and the band is widened to cover all of them, at the price of some multiplications by
+// zero.  A group of 16 outputs is then a dense 16 x (32 NK) coefficient block, and 16 image rows
+// times that block is NK products of the usual kind: the image operand is 8 consecutive samples of
+// one row per lane, straight from memory.
+//
+// One kernel does both axes.  It contracts over the memory-contiguous index of its input and writes
+// its result TRANSPOSED, Z[o][r] = sum_j X[r][start[o] + j] coef[o][j]: the horizontal pass turns the
+// image into T^T[xo][y] (rounded to fp16, kept in the workspace), so the vertical pass finds its
+// contraction index y contiguous again and its transposed result is the output in its natural
+// orientation.  The accumulators leave with a lane owning four consecutive r of one o, which is four
+// consecutive elements of a row of Z.
+#include <math.h>
+
+#include "hb_device.hpp"
+#include "hb_host.hpp"
+
+namespace hb {
+
+constexpr int kRzTiles = 4;                   // 16-row tiles of X per wave (64 rows r)
+constexpr int kRzWaves = 4;                   // waves per workgroup: 4 strips of 64 rows, one group of 16 outputs
+constexpr int kRzMaxChunks = HB_RESIZE_MAX_SPAN / 32;
+
+struct BandArgs {
+    const half_t* x;                          // [planes][rows][len], row pitch x_pitch, plane stride x_plane
+    void* z;                                  // [planes][nout][rows] transposed result, fp16 or fp32
+    const int* start;                         // device: nout first input indices
+    const half_t* coef;                       // device: nout x band coefficients
+    int rows, len, nout, band, planes;
+    int64_t x_pitch, x_plane, z_pitch, z_plane;
+    int ngroups, nruns;                       // groups of 16 outputs; runs of 4 strips per plane
+};
+
+// Sixteen rows of 64 floats from the accumulators (lane (c, g): row c, columns 16 w + 4 g ..) to
+// fp16 rows in memory, through the wave's LDS patch so that a row leaves as one 128-byte run.
+template <int NW>
+__device__ __forceinline__ void rz_store_rows_half(float* patch, half_t* dst, uint32_t pitch_elems,
+                                                   const floatx4 (&acc)[NW], int lane) {
+    const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+        *reinterpret_cast<floatx4*>(patch + c * RowPatch<NW>::kPitch + 16 * w + 4 * g) = acc[w];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int kLanesPerRow = 4 * NW, kRowsPerPass = 64 / kLanesPerRow;
+    const int rr = lane / kLanesPerRow, xq = lane - rr * kLanesPerRow;
+#pragma unroll
+    for (int s = 0; s < 16 / kRowsPerPass; ++s) {
+        const int row = s * kRowsPerPass + rr;
+        const floatx4 v = *reinterpret_cast<const floatx4*>(patch + row * RowPatch<NW>::kPitch + 4 * xq);
+        const half4 h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
+        *reinterpret_cast<half4_u*>(dst + (size_t)row * pitch_elems + 4 * xq) = h;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <bool OUT_HALF>
+__global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
+    constexpr int NW = kRzTiles;
+    __shared__ __attribute__((aligned(16))) half8 s_frag[kRzMaxChunks * 64];
+    __shared__ __attribute__((aligned(16))) float s_patch[kRzWaves * RowPatch<NW>::kFloats];
+    __shared__ int s_geom[2];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    int wg = blockIdx.x;
+    const int run = wg % p.nruns;
+    wg /= p.nruns;
+    const int grp = wg % p.ngroups, plane = wg / p.ngroups;
+    const int o0 = 16 * grp;
+
+    // geometry of the group: first sample (even) and number of 32-sample chunks, capped
+    if (tid == 0) {
+        int lo = 0x7fffffff, hi = -0x7fffffff;
+        for (int i = 0; i < 16 && o0 + i < p.nout; ++i) {
+            const int st = clampi(p.start[o0 + i], -(1 << 24), 1 << 24);
+            lo = min(lo, st);
+            hi = max(hi, st + p.band);
+        }
+        lo &= ~1;
+        s_geom[0] = lo;
+        s_geom[1] = min((hi - lo + 31) / 32, kRzMaxChunks);
+    }
+    __syncthreads();
+    const int first = s_geom[0], nk = s_geom[1];
+    // coefficient block, B-operand layout: lane (c = o, g) holds B[8g + i][o] = coef[o][first + 32 kk + 8g + i - start[o]]
+    for (int idx = tid; idx < nk * 64; idx += 64 * kRzWaves) {
+        const int l = idx & 63, kk = idx >> 6;
+        const int o = o0 + (l & 15);
+        half8 f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (half_t)0;
+        if (o < p.nout) {
+            const int t0 = first + 32 * kk + 8 * (l >> 4) - clampi(p.start[o], -(1 << 24), 1 << 24);
+            const half_t* row = p.coef + (size_t)o * p.band;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (t0 + i >= 0 && t0 + i < p.band) f[i] = row[t0 + i];
+        }
+        s_frag[idx] = f;
+    }
+    __syncthreads();
+
+    const int r0 = 64 * (kRzWaves * run + wv);            // this wave's strip of rows
+    if (r0 >= p.rows) return;
+    const half_t* xpl = p.x + (size_t)plane * p.x_plane;
+    const uint32_t rowbytes = (uint32_t)p.x_pitch * 2u;
+    uint32_t rowoff[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) rowoff[w] = (uint32_t)min(r0 + 16 * w + c, p.rows - 1) * rowbytes;
+
+    auto load_chunk = [&](int kk, half8 (&d)[NW]) {
+        const int xs = first + 32 * kk;                   // uniform
+        if (xs >= 0 && xs + 32 <= p.len) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) d[w] = ldg8(xpl, rowoff[w] + 2u * (uint32_t)(xs + 8 * g));
+        } else {
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int x = clampi(xs + 8 * g + i, 0, p.len - 1);
+                    d[w][i] = *reinterpret_cast<const half_t*>(reinterpret_cast<const char*>(xpl) + (rowoff[w] + 2u * (uint32_t)x));
+                }
+        }
+    };
+
+    floatx4 acc[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
+    half8 bufa[NW], bufb[NW];
+    load_chunk(0, bufa);
+    // two window buffers used alternately; the next chunk is always requested (the last one twice)
+    for (int kk = 0; kk < nk; kk += 2) {
+        load_chunk(min(kk + 1, nk - 1), bufb);
+        {
+            const half8 f = s_frag[kk * 64 + lane];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(bufa[w], f, acc[w]);
+        }
+        if (kk + 1 >= nk) break;
+        load_chunk(min(kk + 2, nk - 1), bufa);
+        {
+            const half8 f = s_frag[(kk + 1) * 64 + lane];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(bufb[w], f, acc[w]);
+        }
+    }
+
+    // D[m = r][n = o]: lane (c = o, g) holds rows r0 + 16 w + 4 g .. + 3 = four consecutive elements of Z's row o
+    float* patch = s_patch + wv * RowPatch<NW>::kFloats;
+    const bool whole = o0 + 16 <= p.nout && r0 + 64 <= p.rows;
+    if (OUT_HALF) {
+        half_t* z = reinterpret_cast<half_t*>(p.z) + (size_t)plane * p.z_plane;
+        if (whole) {
+            rz_store_rows_half<NW>(patch, z + (size_t)o0 * p.z_pitch + r0, (uint32_t)p.z_pitch, acc, lane);
+        } else if (o0 + c < p.nout) {
+            half_t* row = z + (size_t)(o0 + c) * p.z_pitch;
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = r0 + 16 * w + 4 * g + j;
+                    if (r < p.rows) row[r] = (half_t)acc[w][j];
+                }
+        }
+    } else {
+        float* z = reinterpret_cast<float*>(p.z) + (size_t)plane * p.z_plane;
+        if (whole) {
+            store_rows_via_lds<NW, true>(patch, z + (size_t)o0 * p.z_pitch + r0, (uint32_t)p.z_pitch, acc, lane);
+        } else if (o0 + c < p.nout) {
+            float* row = z + (size_t)(o0 + c) * p.z_pitch;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) store4_mask(row, r0 + 16 * w + 4 * g, p.rows, acc[w]);
+        }
+    }
+}
+
+// Vector-ALU twin of one pass: a thread per (o, r), r fastest; plain loop over the band.
+template <bool OUT_HALF>
+__global__ void __launch_bounds__(256) band_valu_kernel(BandArgs p) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t per_plane = (int64_t)p.nout * p.rows;
+    if (idx >= per_plane * p.planes) return;
+    const int plane = (int)(idx / per_plane);
+    const int64_t rem = idx - (int64_t)plane * per_plane;
+    const int o = (int)(rem / p.rows), r = (int)(rem - (int64_t)o * p.rows);
+    const half_t* row = p.x + (size_t)plane * p.x_plane + (size_t)r * p.x_pitch;
+    const half_t* k = p.coef + (size_t)o * p.band;
+    const int st = clampi(p.start[o], -(1 << 24), 1 << 24);
+    float acc = 0.f;
+    for (int j = 0; j < p.band; ++j) acc = fmaf((float)k[j], (float)row[clampi(st + j, 0, p.len - 1)], acc);
+    if (OUT_HALF) (reinterpret_cast<half_t*>(p.z) + (size_t)plane * p.z_plane)[(size_t)o * p.z_pitch + r] = (half_t)acc;
+    else (reinterpret_cast<float*>(p.z) + (size_t)plane * p.z_plane)[(size_t)o * p.z_pitch + r] = acc;
+}
+
+static int64_t rz_pitch(int H) { return ((int64_t)H + 7) & ~(int64_t)7; }
+
+static hb_status resize_run(bool valu, const hb_half* in, float* out, void* workspace, size_t workspace_bytes,
+                            int C, int H, int W, int Ho, int Wo,
+                            int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                            const int32_t* start_y, const hb_half* coef_y, int band_y,
+                            const int32_t* start_x, const hb_half* coef_x, int band_x, hb_stream stream) {
+    if (!in || !out || !start_y || !coef_y || !start_x || !coef_x) return HB_ERR_INVALID_ARG;
+    if (C < 1 || H < 1 || W < 1 || Ho < 1 || Wo < 1) return HB_ERR_INVALID_ARG;
+    if (band_y < 1 || band_x < 1 || band_y > HB_RESIZE_MAX_SPAN || band_x > HB_RESIZE_MAX_SPAN) return HB_ERR_INVALID_ARG;
+    if (in_pitch < W || out_pitch < Wo) return HB_ERR_INVALID_ARG;
+    if (C > 1 && (in_plane < (int64_t)H * in_pitch || out_plane < (int64_t)Ho * out_pitch)) return HB_ERR_INVALID_ARG;
+    if (!aligned_to(in, 2) || !aligned_to(out, 4) || !aligned_to(start_y, 4) || !aligned_to(start_x, 4) ||
+        !aligned_to(coef_y, 2) || !aligned_to(coef_x, 2))
+        return HB_ERR_INVALID_ARG;
+    const int64_t hp = rz_pitch(H);
+    // lanes address the rows of a plane with 32-bit byte offsets
+    if ((int64_t)H * in_pitch >= ((int64_t)1 << 31) || (int64_t)Wo * hp >= ((int64_t)1 << 31) ||
+        (int64_t)Ho * out_pitch >= ((int64_t)1 << 30) || C > 65535)
+        return HB_ERR_UNSUPPORTED;
+    const size_t need = hb_resize_workspace_size(C, H, Wo);
+    if (!workspace || workspace_bytes < need || !aligned_to(workspace, 256)) return HB_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+    BandArgs a;
+    // horizontal: image rows y, contraction over x, result T^T[xo][y] in fp16
+    a.x = reinterpret_cast<const half_t*>(in);
+    a.z = workspace;
+    a.start = start_x;
+    a.coef = reinterpret_cast<const half_t*>(coef_x);
+    a.rows = H;
+    a.len = W;
+    a.nout = Wo;
+    a.band = band_x;
+    a.planes = C;
+    a.x_pitch = in_pitch;
+    a.x_plane = in_plane;
+    a.z_pitch = hp;
+    a.z_plane = (int64_t)Wo * hp;
+    BandArgs b;
+    // vertical: rows of T^T, contraction over y, result out[yo][xo] in fp32
+    b.x = reinterpret_cast<const half_t*>(workspace);
+    b.z = out;
+    b.start = start_y;
+    b.coef = reinterpret_cast<const half_t*>(coef_y);
+    b.rows = Wo;
+    b.len = H;
+    b.nout = Ho;
+    b.band = band_y;
+    b.planes = C;
+    b.x_pitch = hp;
+    b.x_plane = (int64_t)Wo * hp;
+    b.z_pitch = out_pitch;
+    b.z_plane = out_plane;
+    for (BandArgs* q : {&a, &b}) {
+        q->ngroups = ceil_div(q->nout, 16);
+        q->nruns = ceil_div(q->rows, 64 * kRzWaves);
+        if (valu) {
+            const int64_t blocks = ((int64_t)q->planes * q->nout * q->rows + 255) / 256;
+            if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
+            if (q == &a) hipLaunchKernelGGL(band_valu_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, *q);
+            else hipLaunchKernelGGL(band_valu_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, *q);
+        } else {
+            const int64_t blocks = (int64_t)q->planes * q->ngroups * q->nruns;
+            if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
+            if (q == &a) hipLaunchKernelGGL(band_mfma_kernel<true>, dim3((unsigned)blocks), dim3(64 * kRzWaves), 0, st, *q);
+            else hipLaunchKernelGGL(band_mfma_kernel<false>, dim3((unsigned)blocks), dim3(64 * kRzWaves), 0, st, *q);
+        }
+        const hb_status s = launch_status();
+        if (s != HB_OK) return s;
+    }
+    return HB_OK;
+}
+
+// float -> fp16 bit pattern, round to nearest even (finite inputs of moderate size only).
+static uint16_t float_to_half_bits(float v) {
+    uint32_t b;
+    memcpy(&b, &v, sizeof(b));
+    const uint32_t sign = (b >> 16) & 0x8000u;
+    const int32_t e = (int32_t)((b >> 23) & 0xff) - 127 + 15;
+    uint32_t m = b & 0x7fffffu;
+    if (e >= 31) return (uint16_t)(sign | 0x7c00u);                       // overflow -> inf
+    if (e <= 0) {                                                         // subnormal or zero
+        if (e < -10) return (uint16_t)sign;
+        m |= 0x800000u;
+        const int shift = 14 - e;
+        uint32_t h = m >> shift;
+        const uint32_t rest = m & ((1u << shift) - 1), halfway = 1u << (shift - 1);
+        if (rest > halfway || (rest == halfway && (h & 1))) ++h;
+        return (uint16_t)(sign | h);
+    }
+    uint32_t h = ((uint32_t)e << 10) | (m >> 13);
+    const uint32_t rest = m & 0x1fffu;
+    if (rest > 0x1000u || (rest == 0x1000u && (h & 1))) ++h;             // may carry into the exponent: still right
+    return (uint16_t)(sign | h);
+}
+
+}  // namespace hb
+
+extern "C" size_t hb_resize_workspace_size(int C, int H, int Wo) {
+    if (C < 1 || H < 1 || Wo < 1) return 0;
+    return (size_t)C * (size_t)Wo * (size_t)hb::rz_pitch(H) * sizeof(uint16_t);
+}
+
+extern "C" hb_status hb_resize(const hb_half* in, float* out, void* workspace, size_t workspace_bytes,
+                               int C, int H, int W, int Ho, int Wo,
+                               int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                               const int32_t* start_y, const hb_half* coef_y, int band_y,
+                               const int32_t* start_x, const hb_half* coef_x, int band_x, hb_stream stream) {
+    return hb::resize_run(false, in, out, workspace, workspace_bytes, C, H, W, Ho, Wo, in_pitch, in_plane, out_pitch,
+                          out_plane, start_y, coef_y, band_y, start_x, coef_x, band_x, stream);
+}
+
+extern "C" hb_status hb_resize_valu(const hb_half* in, float* out, void* workspace, size_t workspace_bytes,
+                                    int C, int H, int W, int Ho, int Wo,
+                                    int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                                    const int32_t* start_y, const hb_half* coef_y, int band_y,
+                                    const int32_t* start_x, const hb_half* coef_x, int band_x, hb_stream stream) {
+    return hb::resize_run(true, in, out, workspace, workspace_bytes, C, H, W, Ho, Wo, in_pitch, in_plane, out_pitch,
+                          out_plane, start_y, coef_y, band_y, start_x, coef_x, band_x, stream);
+}
+
+extern "C" int hb_lanczos3_band(int n_in, int n_out) {
+    if (n_in < 1 || n_out < 1 || n_out > n_in) return 0;
+    return (int)floor(6.0 * (double)n_in / (double)n_out) + 1;
+}
+
+extern "C" hb_status hb_lanczos3_matrix(int n_in, int n_out, int32_t* start_host, hb_half* coef_host) {
+    const int band = hb_lanczos3_band(n_in, n_out);
+    if (band == 0 || !start_host || !coef_host) return HB_ERR_INVALID_ARG;
+    if (band > HB_RESIZE_MAX_SPAN) return HB_ERR_UNSUPPORTED;
+    const double pi = 3.14159265358979323846, scale = (double)n_in / (double)n_out;
+    double w[HB_RESIZE_MAX_SPAN];
+    for (int o = 0; o < n_out; ++o) {
+        const double centre = (o + 0.5) * scale - 0.5;
+        const int first = (int)ceil(centre - 3.0 * scale);
+        double sum = 0.0;
+        for (int j = 0; j < band; ++j) {
+            const double x = ((double)(first + j) - centre) / scale;
+            double v = 0.0;
+            if (fabs(x) < 3.0) v = x == 0.0 ? 1.0 : (sin(pi * x) / (pi * x)) * (sin(pi * x / 3.0) / (pi * x / 3.0));
+            w[j] = v;
+            sum += v;
+        }
+        start_host[o] = first;
+        for (int j = 0; j < band; ++j) coef_host[(size_t)o * band + j] = hb::float_to_half_bits((float)(w[j] / sum));
+    }
+    return HB_OK;
+}

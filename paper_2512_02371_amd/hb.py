@@ -30,6 +30,7 @@ SYMBOLS = [
     "hb_fir1d", "hb_fir1d_valu",
     "hb_conv2d", "hb_conv2d_valu",
     "hb_down2", "hb_down2_valu", "hb_up2", "hb_up2_valu",
+    "hb_resize_workspace_size", "hb_resize", "hb_resize_valu", "hb_lanczos3_band", "hb_lanczos3_matrix",
     "hb_sepblur", "hb_sepblur_valu",
     "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu",
     "hb_conv3x3", "hb_conv3x3_valu",
@@ -55,6 +56,9 @@ def load() -> ctypes.CDLL:
         raise RuntimeError(
             f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`. "
             "There is no CPU fallback.")
+    # torch first: it ships its own copy of the HIP runtime, and libhb.so must bind to that copy (the
+    # one that owns torch's streams and allocations), not load a second runtime from the system path
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     L.hb_status_string.argtypes = [I]
@@ -73,6 +77,16 @@ def load() -> ctypes.CDLL:
         f = getattr(L, name)
         f.argtypes = sig
         f.restype = I
+    rsz = [vp, vp, vp, ctypes.c_size_t, I, I, I, I, I, I64, I64, I64, I64, vp, vp, I, vp, vp, I, vp]
+    for name in ("hb_resize", "hb_resize_valu"):
+        getattr(L, name).argtypes = rsz
+        getattr(L, name).restype = I
+    L.hb_resize_workspace_size.argtypes = [I, I, I]
+    L.hb_resize_workspace_size.restype = ctypes.c_size_t
+    L.hb_lanczos3_band.argtypes = [I, I]
+    L.hb_lanczos3_band.restype = I
+    L.hb_lanczos3_matrix.argtypes = [I, I, vp, vp]
+    L.hb_lanczos3_matrix.restype = I
     L.hb_sat2d_workspace_size.argtypes = [I, I]
     L.hb_sat2d_workspace_size.restype = ctypes.c_size_t
     _lib = L
@@ -169,6 +183,54 @@ def hb_up2(inp, out, taps2d, anchor_y, anchor_x):
 
 def hb_up2_valu(inp, out, taps2d, anchor_y, anchor_x):
     return _conv2d("hb_up2_valu", inp, out, taps2d, anchor_y, anchor_x, _double_shape)
+
+
+def hb_resize_workspace_size(C, H, Wo):
+    return int(load().hb_resize_workspace_size(int(C), int(H), int(Wo)))
+
+
+def hb_lanczos3_band(n_in, n_out):
+    return int(load().hb_lanczos3_band(int(n_in), int(n_out)))
+
+
+def hb_lanczos3_matrix(n_in, n_out):
+    """Host arrays (start int32 [n_out], coef fp16 bit patterns [n_out, band]) built by the library."""
+    band = hb_lanczos3_band(n_in, n_out)
+    if band <= 0:
+        raise HbError("hb_lanczos3_band", HB_ERR_INVALID_ARG)
+    start = np.empty(n_out, dtype=np.int32)
+    coef = np.empty((n_out, band), dtype=np.uint16)
+    _check("hb_lanczos3_matrix", load().hb_lanczos3_matrix(int(n_in), int(n_out), start.ctypes.data_as(ctypes.c_void_p),
+                                                          coef.ctypes.data_as(ctypes.c_void_p)))
+    return start, coef
+
+
+def _resize(name, inp, out, workspace, start_y, coef_y, start_x, coef_x):
+    import torch
+    assert inp.is_cuda and inp.dim() == 3 and inp.dtype == torch.float16 and inp.stride(2) == 1
+    assert out.is_cuda and out.dim() == 3 and out.dtype == torch.float32 and out.stride(2) == 1
+    C, H, W = (int(v) for v in inp.shape)
+    Co, Ho, Wo = (int(v) for v in out.shape)
+    assert C == Co
+    for st, cf, n in ((start_y, coef_y, Ho), (start_x, coef_x, Wo)):
+        assert st.is_cuda and st.dtype == torch.int32 and st.is_contiguous() and tuple(st.shape) == (n,)
+        assert cf.is_cuda and cf.dtype == torch.float16 and cf.is_contiguous() and cf.dim() == 2 and cf.shape[0] == n
+    assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+    _check(name, getattr(load(), name)(
+        ctypes.c_void_p(inp.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+        ctypes.c_void_p(workspace.data_ptr()), int(workspace.numel()), C, H, W, Ho, Wo,
+        int(inp.stride(1)), int(inp.stride(0)), int(out.stride(1)), int(out.stride(0)),
+        ctypes.c_void_p(start_y.data_ptr()), ctypes.c_void_p(coef_y.data_ptr()), int(coef_y.shape[1]),
+        ctypes.c_void_p(start_x.data_ptr()), ctypes.c_void_p(coef_x.data_ptr()), int(coef_x.shape[1]), _stream()))
+    return out
+
+
+def hb_resize(inp, out, workspace, start_y, coef_y, start_x, coef_x):
+    return _resize("hb_resize", inp, out, workspace, start_y, coef_y, start_x, coef_x)
+
+
+def hb_resize_valu(inp, out, workspace, start_y, coef_y, start_x, coef_x):
+    return _resize("hb_resize_valu", inp, out, workspace, start_y, coef_y, start_x, coef_x)
 
 
 def _sep(name, inp, out, tx, ax, ty, ay):

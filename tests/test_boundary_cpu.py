@@ -120,6 +120,54 @@ def test_resample2_argument_validation(lib, fn):
     assert call(H=1 << 16, W=1 << 15, ip=1 << 15, op=1 << 16) == hb.HB_ERR_UNSUPPORTED
 
 
+def test_lanczos3_matrix_matches_the_oracle_definition(lib):
+    """The library's host-side matrix against the oracle's own fp64 construction rounded to fp16:
+    same starts, same band, coefficients equal up to one fp16 step (the two evaluate sin() and round
+    through different paths)."""
+    import oracle
+    for n_in, n_out in ((2048, 143), (2048, 921), (300, 31), (64, 64), (7, 1)):
+        start, coef = hb.hb_lanczos3_matrix(n_in, n_out)
+        o_start, o_coef = oracle.lanczos3_matrix(n_in, n_out)
+        assert coef.shape[1] == oracle.lanczos3_band(n_in, n_out) == hb.hb_lanczos3_band(n_in, n_out)
+        assert np.array_equal(start, o_start)
+        want = o_coef.astype(np.float16)
+        got = coef.view(np.float16)
+        step = np.maximum(np.spacing(np.abs(want)), np.float16(6e-8)).astype(np.float64)
+        assert np.all(np.abs(got.astype(np.float64) - want.astype(np.float64)) <= step)
+        assert np.mean(got == want) > 0.99
+    assert hb.hb_lanczos3_band(10, 11) == 0            # upsampling is not this function's job
+    assert lib.hb_lanczos3_matrix(4096, 40, FAKE, FAKE) == hb.HB_ERR_UNSUPPORTED    # band 615 > 512
+    assert lib.hb_lanczos3_matrix(10, 5, None, FAKE) == hb.HB_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("fn", ["hb_resize", "hb_resize_valu"])
+def test_resize_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    WS = ctypes.c_void_p(0x10000)
+    ok = dict(i=FAKE, o=FAKE, ws=WS, wsb=1 << 20, C=3, H=64, W=64, Ho=20, Wo=20, ip=64, ipl=64 * 64, op=20, opl=400,
+              sy=FAKE, cy=FAKE, by=20, sx=FAKE, cx=FAKE, bx=20)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["ws"], p["wsb"], p["C"], p["H"], p["W"], p["Ho"], p["Wo"], p["ip"], p["ipl"],
+                 p["op"], p["opl"], p["sy"], p["cy"], p["by"], p["sx"], p["cx"], p["bx"], None)
+    for k in ("i", "o", "sy", "cy", "sx", "cx"):
+        assert call(**{k: None}) == hb.HB_ERR_INVALID_ARG
+    assert call(C=0) == hb.HB_ERR_INVALID_ARG
+    assert call(Ho=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=63) == hb.HB_ERR_INVALID_ARG
+    assert call(op=19) == hb.HB_ERR_INVALID_ARG
+    assert call(ipl=64 * 63) == hb.HB_ERR_INVALID_ARG
+    assert call(opl=399) == hb.HB_ERR_INVALID_ARG
+    assert call(by=0) == hb.HB_ERR_INVALID_ARG
+    assert call(bx=513) == hb.HB_ERR_INVALID_ARG
+    assert call(ws=None) == hb.HB_ERR_WORKSPACE
+    assert call(wsb=lib.hb_resize_workspace_size(3, 64, 20) - 1) == hb.HB_ERR_WORKSPACE
+    assert call(ws=ctypes.c_void_p(0x10010)) == hb.HB_ERR_WORKSPACE
+    assert lib.hb_resize_workspace_size(3, 64, 20) == 3 * 20 * 64 * 2
+    assert lib.hb_resize_workspace_size(1, 61, 20) == 20 * 64 * 2      # rows padded to 8 samples
+
+
 def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
