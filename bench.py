@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling, Lanczos resize)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -286,6 +286,31 @@ def main():
                 out["supplementary"]["%s_%dx%d_4096x4096" % (name, k, k)] = {
                     "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
                     "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
+        # ... and the paper's non-integer resize (Sec. V-C, Table II): a 2048 x 2048 RGB image (three
+        # planes) down to 143 / 245 / 450 / 921 squared with Lanczos-3 matrices built by the library.
+        del half_out, half_in
+        rgb = (torch.rand((3, 2048, 2048), device=dev)).half()
+        for n in (143, 245, 450, 921):
+            st_h, cf_h = hb.hb_lanczos3_matrix(2048, n)
+            st_d = torch.from_numpy(st_h).to(dev)
+            cf_d = torch.from_numpy(cf_h.view(np.int16)).to(dev).view(torch.float16)
+            ro = torch.empty((3, n, n), dtype=torch.float32, device=dev)
+            rws = torch.empty(hb.hb_resize_workspace_size(3, 2048, n), dtype=torch.uint8, device=dev)
+
+            def timed4(fn, iters):
+                for i in range(2):
+                    fn(rgb, ro, rws, st_d, cf_d, st_d, cf_d)
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for i in range(iters):
+                    fn(rgb, ro, rws, st_d, cf_d, st_d, cf_d)
+                a1.record()
+                torch.cuda.synchronize()
+                return a0.elapsed_time(a1) / iters
+            m_ms, v_ms = timed4(hb.hb_resize, 10), timed4(hb.hb_resize_valu, 3)
+            out["supplementary"]["resize_lanczos3_3x2048x2048_to_%d" % n] = {
+                "mfma_ms": m_ms, "valu_ms": v_ms, "band": int(cf_h.shape[1]),
+                "mfma_input_gpixels_per_s": 3 * 2048 * 2048 / m_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)

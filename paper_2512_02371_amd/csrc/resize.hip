@@ -71,10 +71,11 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    int wg = blockIdx.x;
-    const int run = wg % p.nruns;
-    wg /= p.nruns;
-    const int grp = wg % p.ngroups, plane = wg / p.ngroups;
+    // neighbouring groups read neighbouring pieces of the same rows: walk them back to back inside one XCD
+    int wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int grp = wg % p.ngroups;
+    wg /= p.ngroups;
+    const int run = wg % p.nruns, plane = wg / p.nruns;
     const int o0 = 16 * grp;
 
     // geometry of the group: first sample (even) and number of 32-sample chunks, capped
@@ -136,23 +137,20 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
     floatx4 acc[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // two window buffers used alternately: the next chunk is in flight while this one is multiplied
     half8 bufa[NW], bufb[NW];
+    auto use_chunk = [&](int kk, const half8 (&d)[NW]) {
+        const half8 f = s_frag[kk * 64 + lane];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(d[w], f, acc[w]);
+    };
     load_chunk(0, bufa);
-    // two window buffers used alternately; the next chunk is always requested (the last one twice)
     for (int kk = 0; kk < nk; kk += 2) {
-        load_chunk(min(kk + 1, nk - 1), bufb);
-        {
-            const half8 f = s_frag[kk * 64 + lane];
-#pragma unroll
-            for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(bufa[w], f, acc[w]);
-        }
+        if (kk + 1 < nk) load_chunk(kk + 1, bufb);
+        use_chunk(kk, bufa);
         if (kk + 1 >= nk) break;
-        load_chunk(min(kk + 2, nk - 1), bufa);
-        {
-            const half8 f = s_frag[(kk + 1) * 64 + lane];
-#pragma unroll
-            for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(bufb[w], f, acc[w]);
-        }
+        if (kk + 2 < nk) load_chunk(kk + 2, bufa);
+        use_chunk(kk + 1, bufb);
     }
 
     // D[m = r][n = o]: lane (c = o, g) holds rows r0 + 16 w + 4 g .. + 3 = four consecutive elements of Z's row o
