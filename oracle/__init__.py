@@ -51,6 +51,8 @@ def _load():
         L.hbo_conv2d.restype = None
         L.hbo_band_resize.argtypes = [u16p, f64p, I, I, I, I, Lg, Lg, i32p, u16p, I, i32p, u16p, I]
         L.hbo_band_resize.restype = None
+        L.hbo_iir2.argtypes = [u16p, f64p, I, Lg, Lg, Lg, ctypes.c_double, ctypes.c_double]
+        L.hbo_iir2.restype = None
         for f in (L.hbo_down2, L.hbo_up2):
             f.argtypes = [u16p, f64p, I, I, Lg, Lg, u16p, I, I, I, I]
             f.restype = None
@@ -132,6 +134,15 @@ def up2(img, taps2d, anchor_y, anchor_x):
     H, W = img.shape
     out = np.empty((2 * H, 2 * W), dtype=np.float64)
     _load().hbo_up2(pi, _f64(out), H, W, W, 2 * W, pk, k.shape[0], k.shape[1], int(anchor_y), int(anchor_x))
+    return out
+
+
+def iir2(sig, alpha, beta):
+    """y[c][t] = x[c][t] + alpha y[c][t-1] + beta y[c][t-2], zero initial state (Sec. V-D); sig is [C, T] fp16."""
+    sig, ps = _u16(sig)
+    C, T = sig.shape
+    out = np.empty((C, T), dtype=np.float64)
+    _load().hbo_iir2(ps, _f64(out), C, T, T, T, float(alpha), float(beta))
     return out
 
 

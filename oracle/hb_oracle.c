@@ -251,6 +251,24 @@ void hbo_band_resize(const uint16_t *in, double *out, int H, int W, int Ho, int 
     free(kx);
 }
 
+/* ---- second-order recursive filter (Sec. V-D):
+ *        Y_t = X_t + alpha Y_{t-1} + beta Y_{t-2},  Y_{-1} = Y_{-2} = 0,
+ *      one independent recursion per channel, written as the serial loop it is. */
+
+void hbo_iir2(const uint16_t *in, double *out, int C, long T, long in_pitch, long out_pitch,
+              double alpha, double beta)
+{
+    for (int c = 0; c < C; ++c) {
+        double y1 = 0.0, y2 = 0.0;
+        for (long t = 0; t < T; ++t) {
+            double y = hbo_half_to_double(in[(long)c * in_pitch + t]) + alpha * y1 + beta * y2;
+            out[(long)c * out_pitch + t] = y;
+            y2 = y1;
+            y1 = y;
+        }
+    }
+}
+
 /* ---- separable blur: rows, then columns (Sec. V-A; the 2-D form with
  *      K(rx, ry) = kx[rx] * ky[ry]) ------------------------------------ */
 /* tmp[y][x] = sum_r kx[r] in[y][clampW(x + r - ax)]

@@ -699,3 +699,46 @@ def test_band_resize_brute_force_with_irregular_starts(orc):
         for xo in range(Wo):
             e = sum(Cy[yo, i] * Cx[xo, j] * I[cl(sy[yo] + i, H), cl(sx[xo] + j, W)] for i in range(by) for j in range(bx))
             assert orc.band_resize(img, sy, cy, sx, cx)[yo, xo] == pytest.approx(e, abs=1e-14)
+
+
+# --------------------------------------------------------------------------
+# iir2: second-order recursive filter (Sec. V-D)
+# --------------------------------------------------------------------------
+
+def test_iir2_impulse_response_is_the_closed_form_in_the_poles(orc):
+    """h_k = (p1^(k+1) - p2^(k+1)) / (p1 - p2) with p1, p2 the roots of z^2 - alpha z - beta (complex here)."""
+    alpha, beta = 1.6, -0.8
+    p1, p2 = np.roots([1.0, -alpha, -beta])
+    x = np.zeros((1, 40))
+    x[0, 3] = 1.0
+    y = orc.iir2(h(x), alpha, beta)[0]
+    k = np.arange(37)
+    assert np.allclose(y[3:], ((p1 ** (k + 1) - p2 ** (k + 1)) / (p1 - p2)).real, atol=1e-12)
+    assert np.all(y[:3] == 0.0)
+
+
+def test_iir2_special_cases_are_the_running_sum_and_the_geometric_filter(orc):
+    x = rand_img(141, 2, 50)
+    assert np.allclose(orc.iir2(x, 1.0, 0.0), np.cumsum(d(x), axis=1), atol=1e-13)
+    a = 0.75
+    y = orc.iir2(x, a, 0.0)
+    for t in (0, 1, 17, 49):
+        assert y[1, t] == pytest.approx(sum(a ** k * d(x)[1, t - k] for k in range(t + 1)), abs=1e-13)
+
+
+def test_iir2_matches_the_library_filter_and_the_step_response_limit(orc):
+    from scipy.signal import lfilter
+    alpha, beta = 1.2, -0.52
+    x = rand_img(142, 2, 300)
+    assert np.allclose(orc.iir2(x, alpha, beta), lfilter([1.0], [1.0, -alpha, -beta], d(x), axis=1), atol=1e-11)
+    step = orc.iir2(h(np.ones((1, 400))), alpha, beta)[0]
+    assert step[-1] == pytest.approx(1.0 / (1.0 - alpha - beta), abs=1e-9)
+
+
+def test_iir2_channels_are_independent_and_the_recursion_holds_pointwise(orc):
+    alpha, beta = 0.9, -0.3
+    x = rand_img(143, 3, 64)
+    y = orc.iir2(x, alpha, beta)
+    X = d(x)
+    assert np.allclose(y[:, 2:], X[:, 2:] + alpha * y[:, 1:-1] + beta * y[:, :-2], atol=1e-14)
+    assert np.array_equal(orc.iir2(x[1:2], alpha, beta)[0], y[1])
