@@ -205,6 +205,24 @@ int hb_lanczos3_band(int n_in, int n_out);
 hb_status hb_lanczos3_matrix(int n_in, int n_out, int32_t *start_host, hb_half *coef_host);
 
 /*
+ * Second-order recursive filter over C independent channels (Sec. V-D):
+ *     out[c][t] = in[c][t] + alpha * out[c][t-1] + beta * out[c][t-2],   out[c][-1] = out[c][-2] = 0
+ * computed in tiles with a fix-up from the preceding tiles; inside a tile the
+ * recursion over a block of 32 samples is a product with the triangular Toeplitz
+ * matrix of the impulse response.  in: C x T fp16, out: C x T fp32 (row pitches in
+ * elements, >= T).  |alpha|, |beta| <= 4; filters whose 32-sample impulse response
+ * leaves the fp16 range, or whose tile-to-tile state maps overflow, are
+ * HB_ERR_UNSUPPORTED (stable filters never are).  `workspace`: device scratch of at
+ * least hb_iir2_workspace_size(C, T) bytes, 256-byte aligned; contents undefined on
+ * exit; concurrent calls need their own.
+ */
+size_t hb_iir2_workspace_size(int C, int64_t T);
+hb_status hb_iir2(const hb_half *in, float *out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
+                  float alpha, float beta, void *workspace, size_t workspace_bytes, hb_stream stream);
+hb_status hb_iir2_valu(const hb_half *in, float *out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
+                       float alpha, float beta, void *workspace, size_t workspace_bytes, hb_stream stream);
+
+/*
  * Summed-area table (inclusive prefix sum over rows and columns; a product
  * L * X * U with triangular all-ones matrices per tile plus inter-tile carries --
  * the tile-then-fix-up structure of Sec. V-D applied to a first-order recursion):

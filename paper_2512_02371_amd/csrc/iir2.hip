@@ -1,0 +1,362 @@
+// hb_iir2: second-order recursive filter Y_t = X_t + alpha Y_{t-1} + beta Y_{t-2} over long signals,
+// and its vector-ALU twin (Sec. V-D).
+//
+// The paper tiles the signal, runs the filter on every tile in parallel and fixes the tiles up with
+// the contribution of their predecessors; inside a tile it trades the serial recursion for a
+// convolution on the matrix units plus a dilated recursion.  Here the part inside a tile is taken
+// one step further: the filter restricted to a block of 32 samples with zero initial state is the
+// lower-triangular Toeplitz matrix of its impulse response, T(i, j) = h_{i-j}, so 16 blocks are one
+// product T * X^T (K = 32) per half of the outputs, and the recursion survives only as the
+// propagation of a two-number state (Y_{t-1}, Y_{t-2}) from block to block: the state after a block
+// is M32 * (state before) + (last two local outputs), M32 the 32nd power of the companion matrix.
+// Three launches, like the summed-area table: (1) local products, end state of every 512-sample
+// tile; (2) scan of the tile states along the signal; (3) local products again, block states from
+// the true tile state, outputs = local outputs + response of the block's initial state.
+//
+// The impulse response is not an fp16 number: T is split into a rounded part and the rounded
+// remainder (two products), which leaves a relative coefficient error of about 2^-22.
+#include <math.h>
+
+#include "hb_device.hpp"
+#include "hb_host.hpp"
+
+namespace hb {
+
+constexpr int kIirBlock = 32;                 // samples per block (the K of one product)
+constexpr int kIirTile = 16 * kIirBlock;      // samples per wave tile: 16 blocks
+
+struct IirArgs {
+    const half_t* in;
+    float* out;
+    int C, ntiles, chunk;                     // chunk = tiles per lane in the scan
+    int64_t T, in_pitch, out_pitch;
+    float* end;                               // [C][ntiles][2] state after each tile if it started from zero
+    float* start;                             // [C][ntiles][2] true state before each tile
+    float m32[4], m512[4], mchunk[4];         // state maps over a block, a tile, a scan chunk (row-major 2x2)
+    float ca[kIirBlock], cb[kIirBlock];       // response of output i to the initial state (Y_-1, Y_-2)
+    uint16_t thi[kIirBlock], tlo[kIirBlock];  // impulse response h_0..h_31 as rounded fp16 + rounded remainder
+    float alpha, beta;
+};
+
+struct State2 {
+    float a, b;                               // (Y_{t-1}, Y_{t-2})
+};
+
+__device__ __forceinline__ State2 iir_step(const float (&m)[4], State2 s, float l1, float l0) {
+    return State2{fmaf(m[0], s.a, fmaf(m[1], s.b, l1)), fmaf(m[2], s.a, fmaf(m[3], s.b, l0))};
+}
+
+// A-operand fragment of the triangular Toeplitz matrix for output rows 16 hh + c: lane (c, g) holds
+// T(16 hh + c, 8g + i) = h_{16 hh + c - 8g - i} (0 above the diagonal).
+__device__ __forceinline__ half8 iir_fragment(const uint16_t (&t)[kIirBlock], int hh, int lane) {
+    const int d0 = 16 * hh + (lane & 15) - 8 * (lane >> 4);
+    half8 f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (d0 - i >= 0 && d0 - i < kIirBlock) ? __builtin_bit_cast(half_t, t[d0 - i]) : (half_t)0;
+    return f;
+}
+
+// The 512 samples of a tile as the B operand X^T: lane (c = block, g) holds samples 32 c + 8 g .. + 7
+// (zeros past the end of the signal).
+__device__ __forceinline__ half8 iir_load_tile(const half_t* sig, int64_t t0, int64_t T, int lane) {
+    const int64_t t = t0 + 32 * (lane & 15) + 8 * (lane >> 4);
+    if (t + 8 <= T) return *reinterpret_cast<const half8_u*>(sig + t);
+    half8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = t + i < T ? sig[t + i] : (half_t)0;
+    return r;
+}
+
+// Last two local outputs (Y_31, Y_30) of the tile's 16 blocks: elements 3 and 2 of the upper-half
+// accumulator in lanes 48 .. 63.  The two elements are first copied into plain registers behind an
+// opaque statement: reading a lane straight out of an element of the accumulator vector was
+// compiled into a read of element 0.
+struct IirTails {
+    float y31, y30;
+};
+__device__ __forceinline__ IirTails iir_tails(const floatx4& d1) {
+    IirTails t{d1[3], d1[2]};
+    asm volatile("" : "+v"(t.y31), "+v"(t.y30));
+    return t;
+}
+__device__ __forceinline__ void iir_block_tail(const IirTails& t, int b, float& l1, float& l0) {
+    l1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t.y31), 48 + b));
+    l0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t.y30), 48 + b));
+}
+
+// 1  end state of every tile started from zero
+__global__ void __launch_bounds__(256) iir2_state_mfma_kernel(IirArgs p) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    if (wave >= (int64_t)p.C * p.ntiles) return;
+    const int ch = (int)(wave / p.ntiles), tile = (int)(wave - (int64_t)ch * p.ntiles);
+    const half8 x = iir_load_tile(p.in + (int64_t)ch * p.in_pitch, (int64_t)tile * kIirTile, p.T, lane);
+    floatx4 d1 = {0.f, 0.f, 0.f, 0.f};
+    d1 = mfma16x16x32(iir_fragment(p.thi, 1, lane), x, d1);
+    d1 = mfma16x16x32(iir_fragment(p.tlo, 1, lane), x, d1);
+    State2 s{0.f, 0.f};
+    const IirTails tails = iir_tails(d1);
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+        float l1, l0;
+        iir_block_tail(tails, b, l1, l0);
+        s = iir_step(p.m32, s, l1, l0);
+    }
+    if (lane == 0) {
+        float* e = p.end + 2 * ((int64_t)ch * p.ntiles + tile);
+        e[0] = s.a;
+        e[1] = s.b;
+    }
+}
+
+// 2  true state before every tile: one wave per channel, a lane owns `chunk` consecutive tiles
+__global__ void __launch_bounds__(64) iir2_scan_kernel(IirArgs p) {
+    const int lane = threadIdx.x, ch = blockIdx.x;
+    const float* e = p.end + 2 * (int64_t)ch * p.ntiles;
+    float* st = p.start + 2 * (int64_t)ch * p.ntiles;
+    const int lo = min(lane * p.chunk, p.ntiles), hi = min(lo + p.chunk, p.ntiles);
+    State2 q{0.f, 0.f};                                    // effect of the lane's tiles on a zero state
+    for (int t = lo; t < hi; ++t) q = iir_step(p.m512, q, e[2 * t], e[2 * t + 1]);
+    State2 run{0.f, 0.f}, mine{0.f, 0.f};                  // state before lane l's first tile
+    for (int l = 0; l < 64; ++l) {
+        if (lane == l) mine = run;
+        const float qa = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q.a), l));
+        const float qb = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q.b), l));
+        run = iir_step(p.mchunk, run, qa, qb);
+    }
+    for (int t = lo; t < hi; ++t) {
+        st[2 * t] = mine.a;
+        st[2 * t + 1] = mine.b;
+        mine = iir_step(p.m512, mine, e[2 * t], e[2 * t + 1]);
+    }
+}
+
+// 3  outputs
+__global__ void __launch_bounds__(256) iir2_apply_mfma_kernel(IirArgs p) {
+    __shared__ __attribute__((aligned(16))) float s_patch[4 * RowPatch<2>::kFloats];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    if (wave >= (int64_t)p.C * p.ntiles) return;
+    const int ch = (int)(wave / p.ntiles), tile = (int)(wave - (int64_t)ch * p.ntiles);
+    const int64_t t0 = (int64_t)tile * kIirTile;
+    const half8 x = iir_load_tile(p.in + (int64_t)ch * p.in_pitch, t0, p.T, lane);
+    floatx4 d[2];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        d[hh] = floatx4{0.f, 0.f, 0.f, 0.f};
+        d[hh] = mfma16x16x32(iir_fragment(p.thi, hh, lane), x, d[hh]);
+        d[hh] = mfma16x16x32(iir_fragment(p.tlo, hh, lane), x, d[hh]);
+    }
+    // block states from the true tile state; lane (c, g) keeps the state before block c
+    const float* st = p.start + 2 * ((int64_t)ch * p.ntiles + tile);
+    State2 s{st[0], st[1]}, mine{0.f, 0.f};
+    const IirTails tails = iir_tails(d[1]);
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+        if (c == b) mine = s;
+        float l1, l0;
+        iir_block_tail(tails, b, l1, l0);
+        s = iir_step(p.m32, s, l1, l0);
+    }
+    // lane (c = block, g) holds outputs i = 16 hh + 4 g + j of its block: add the response to the block's state
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = 16 * hh + 4 * g + j;
+            d[hh][j] += p.ca[i] * mine.a + p.cb[i] * mine.b;
+        }
+    float* dst = p.out + (int64_t)ch * p.out_pitch + t0;
+    if (t0 + kIirTile <= p.T) {
+        // the tile is 16 rows (blocks) of 32 consecutive samples
+        store_rows_via_lds<2, true>(s_patch + wv * RowPatch<2>::kFloats, dst, kIirBlock, d, lane);
+    } else {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = 32 * c + 16 * hh + 4 * g + j;
+                if (t0 + i < p.T) dst[i] = d[hh][j];
+            }
+    }
+}
+
+// Vector-ALU twin of launches 1 and 3: a lane owns one block of 32 samples and runs the recursion
+// itself; a wave covers four tiles.  WRITE = false: end states of the tiles started from zero;
+// WRITE = true: outputs, every block started from its true state.
+template <bool WRITE>
+__global__ void __launch_bounds__(256) iir2_blocks_valu_kernel(IirArgs p) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int groups = (p.ntiles + 3) / 4;                // waves per channel
+    if (wave >= (int64_t)p.C * groups) return;
+    const int ch = (int)(wave / groups), tile0 = 4 * (int)(wave - (int64_t)ch * groups);
+    const half_t* sig = p.in + (int64_t)ch * p.in_pitch;
+    const int64_t t0 = (int64_t)tile0 * kIirTile + (int64_t)kIirBlock * lane;
+    // local pass from a zero state: the block's last two outputs
+    float y1 = 0.f, y2 = 0.f;
+    for (int i = 0; i < kIirBlock; ++i) {
+        const float xv = t0 + i < p.T ? (float)sig[t0 + i] : 0.f;
+        const float y = fmaf(p.alpha, y1, fmaf(p.beta, y2, xv));
+        y2 = y1;
+        y1 = y;
+    }
+    // state before every block, tile by tile
+    State2 mine{0.f, 0.f};
+    for (int q = 0; q < 4; ++q) {
+        const int tile = tile0 + q;
+        if (tile >= p.ntiles) break;
+        State2 s{0.f, 0.f};
+        if (WRITE) {
+            const float* st = p.start + 2 * ((int64_t)ch * p.ntiles + tile);
+            s = State2{st[0], st[1]};
+        }
+        for (int b = 0; b < 16; ++b) {
+            if (lane == 16 * q + b) mine = s;
+            const float l1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, y1), 16 * q + b));
+            const float l0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, y2), 16 * q + b));
+            s = iir_step(p.m32, s, l1, l0);
+        }
+        if (!WRITE && lane == 0) {
+            float* e = p.end + 2 * ((int64_t)ch * p.ntiles + tile);
+            e[0] = s.a;
+            e[1] = s.b;
+        }
+    }
+    if (WRITE) {
+        float* dst = p.out + (int64_t)ch * p.out_pitch;
+        y1 = mine.a;
+        y2 = mine.b;
+        for (int i = 0; i < kIirBlock; ++i) {
+            if (t0 + i >= p.T) break;
+            const float y = fmaf(p.alpha, y1, fmaf(p.beta, y2, (float)sig[t0 + i]));
+            dst[t0 + i] = y;
+            y2 = y1;
+            y1 = y;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host: coefficient tables in double
+
+struct Mat2 {
+    double v[4];
+};
+static Mat2 mat2_mul(const Mat2& x, const Mat2& y) {
+    return Mat2{{x.v[0] * y.v[0] + x.v[1] * y.v[2], x.v[0] * y.v[1] + x.v[1] * y.v[3],
+                 x.v[2] * y.v[0] + x.v[3] * y.v[2], x.v[2] * y.v[1] + x.v[3] * y.v[3]}};
+}
+static Mat2 mat2_pow(Mat2 m, int64_t n) {
+    Mat2 r{{1.0, 0.0, 0.0, 1.0}};
+    while (n > 0) {
+        if (n & 1) r = mat2_mul(r, m);
+        m = mat2_mul(m, m);
+        n >>= 1;
+    }
+    return r;
+}
+
+static uint16_t iir_float_to_half_bits(float v) {
+    // round to nearest even; |v| is below the fp16 range limit here (checked by the caller)
+    uint32_t b;
+    memcpy(&b, &v, sizeof(b));
+    const uint32_t sign = (b >> 16) & 0x8000u;
+    const int32_t e = (int32_t)((b >> 23) & 0xff) - 127 + 15;
+    uint32_t m = b & 0x7fffffu;
+    if (e >= 31) return (uint16_t)(sign | 0x7bffu);
+    if (e <= 0) {
+        if (e < -10) return (uint16_t)sign;
+        m |= 0x800000u;
+        const int shift = 14 - e;
+        uint32_t h = m >> shift;
+        const uint32_t rest = m & ((1u << shift) - 1), halfway = 1u << (shift - 1);
+        if (rest > halfway || (rest == halfway && (h & 1))) ++h;
+        return (uint16_t)(sign | h);
+    }
+    uint32_t h = ((uint32_t)e << 10) | (m >> 13);
+    const uint32_t rest = m & 0x1fffu;
+    if (rest > 0x1000u || (rest == 0x1000u && (h & 1))) ++h;
+    return (uint16_t)(sign | h);
+}
+
+static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
+                          float alpha, float beta, void* workspace, size_t workspace_bytes, hb_stream stream) {
+    if (!in || !out) return HB_ERR_INVALID_ARG;
+    if (C < 1 || T < 1 || in_pitch < T || out_pitch < T) return HB_ERR_INVALID_ARG;
+    if (!aligned_to(in, 2) || !aligned_to(out, 4)) return HB_ERR_INVALID_ARG;
+    if (!(fabsf(alpha) <= 4.f) || !(fabsf(beta) <= 4.f)) return HB_ERR_INVALID_ARG;     // also rejects NaN
+    if (C > 65535 || T > ((int64_t)1 << 40)) return HB_ERR_UNSUPPORTED;
+    const int64_t ntiles64 = (T + kIirTile - 1) / kIirTile;
+    if (ntiles64 * C > ((int64_t)1 << 30)) return HB_ERR_UNSUPPORTED;
+    const size_t need = hb_iir2_workspace_size(C, T);
+    if (!workspace || workspace_bytes < need || !aligned_to(workspace, 256)) return HB_ERR_WORKSPACE;
+
+    IirArgs a;
+    a.in = reinterpret_cast<const half_t*>(in);
+    a.out = out;
+    a.C = C;
+    a.T = T;
+    a.in_pitch = in_pitch;
+    a.out_pitch = out_pitch;
+    a.ntiles = (int)ntiles64;
+    a.chunk = (a.ntiles + 63) / 64;
+    a.end = reinterpret_cast<float*>(workspace);
+    a.start = a.end + 2 * (size_t)C * a.ntiles;
+    a.alpha = alpha;
+    a.beta = beta;
+    const double al = alpha, be = beta;
+    // impulse response and the response to the initial state, 32 samples each
+    double h[kIirBlock], ca[kIirBlock], cb[kIirBlock];
+    for (int i = 0; i < kIirBlock; ++i) {
+        h[i] = i == 0 ? 1.0 : al * h[i - 1] + (i >= 2 ? be * h[i - 2] : 0.0);
+        const double ca1 = i >= 1 ? ca[i - 1] : 1.0, ca2 = i >= 2 ? ca[i - 2] : (i == 1 ? 1.0 : 0.0);
+        const double cb1 = i >= 1 ? cb[i - 1] : 0.0, cb2 = i >= 2 ? cb[i - 2] : (i == 1 ? 0.0 : 1.0);
+        ca[i] = al * ca1 + be * ca2;
+        cb[i] = al * cb1 + be * cb2;
+    }
+    for (int i = 0; i < kIirBlock; ++i) {
+        if (!(fabs(h[i]) < 3.0e4) || !(fabs(ca[i]) < 1.0e30) || !(fabs(cb[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
+        a.thi[i] = iir_float_to_half_bits((float)h[i]);
+        a.tlo[i] = iir_float_to_half_bits((float)(h[i] - (double)half_bits_to_float(a.thi[i])));
+        a.ca[i] = (float)ca[i];
+        a.cb[i] = (float)cb[i];
+    }
+    const Mat2 m32{{ca[31], cb[31], ca[30], cb[30]}};
+    const Mat2 m512 = mat2_pow(m32, 16), mchunk = mat2_pow(m512, a.chunk);
+    for (int i = 0; i < 4; ++i) {
+        if (!(fabs(m512.v[i]) < 1.0e30) || !(fabs(mchunk.v[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
+        a.m32[i] = (float)m32.v[i];
+        a.m512[i] = (float)m512.v[i];
+        a.mchunk[i] = (float)mchunk.v[i];
+    }
+
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int64_t waves = (int64_t)C * (valu ? (a.ntiles + 3) / 4 : a.ntiles);
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    if (valu) hipLaunchKernelGGL(iir2_blocks_valu_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(iir2_state_mfma_kernel, dim3(blocks), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(iir2_scan_kernel, dim3(C), dim3(64), 0, st, a);
+    if (valu) hipLaunchKernelGGL(iir2_blocks_valu_kernel<true>, dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(iir2_apply_mfma_kernel, dim3(blocks), dim3(256), 0, st, a);
+    return launch_status();
+}
+
+}  // namespace hb
+
+extern "C" size_t hb_iir2_workspace_size(int C, int64_t T) {
+    if (C < 1 || T < 1) return 0;
+    const size_t ntiles = (size_t)((T + hb::kIirTile - 1) / hb::kIirTile);
+    return 2 * 2 * sizeof(float) * (size_t)C * ntiles;
+}
+
+extern "C" hb_status hb_iir2(const hb_half* in, float* out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
+                             float alpha, float beta, void* workspace, size_t workspace_bytes, hb_stream stream) {
+    return hb::iir2_run(false, in, out, C, T, in_pitch, out_pitch, alpha, beta, workspace, workspace_bytes, stream);
+}
+
+extern "C" hb_status hb_iir2_valu(const hb_half* in, float* out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
+                                  float alpha, float beta, void* workspace, size_t workspace_bytes, hb_stream stream) {
+    return hb::iir2_run(true, in, out, C, T, in_pitch, out_pitch, alpha, beta, workspace, workspace_bytes, stream);
+}

@@ -31,6 +31,7 @@ SYMBOLS = [
     "hb_conv2d", "hb_conv2d_valu",
     "hb_down2", "hb_down2_valu", "hb_up2", "hb_up2_valu",
     "hb_resize_workspace_size", "hb_resize", "hb_resize_valu", "hb_lanczos3_band", "hb_lanczos3_matrix",
+    "hb_iir2_workspace_size", "hb_iir2", "hb_iir2_valu",
     "hb_sepblur", "hb_sepblur_valu",
     "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu",
     "hb_conv3x3", "hb_conv3x3_valu",
@@ -87,6 +88,12 @@ def load() -> ctypes.CDLL:
     L.hb_lanczos3_band.restype = I
     L.hb_lanczos3_matrix.argtypes = [I, I, vp, vp]
     L.hb_lanczos3_matrix.restype = I
+    iir = [vp, vp, I, I64, I64, I64, ctypes.c_float, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    for name in ("hb_iir2", "hb_iir2_valu"):
+        getattr(L, name).argtypes = iir
+        getattr(L, name).restype = I
+    L.hb_iir2_workspace_size.argtypes = [I, I64]
+    L.hb_iir2_workspace_size.restype = ctypes.c_size_t
     L.hb_sat2d_workspace_size.argtypes = [I, I]
     L.hb_sat2d_workspace_size.restype = ctypes.c_size_t
     _lib = L
@@ -183,6 +190,29 @@ def hb_up2(inp, out, taps2d, anchor_y, anchor_x):
 
 def hb_up2_valu(inp, out, taps2d, anchor_y, anchor_x):
     return _conv2d("hb_up2_valu", inp, out, taps2d, anchor_y, anchor_x, _double_shape)
+
+
+def hb_iir2_workspace_size(C, T):
+    return int(load().hb_iir2_workspace_size(int(C), int(T)))
+
+
+def _iir2(name, inp, out, alpha, beta, workspace):
+    import torch
+    pi, C, T, ip = _img2d(inp, torch.float16)
+    po, Co, To, op = _img2d(out, torch.float32)
+    assert (C, T) == (Co, To)
+    assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+    _check(name, getattr(load(), name)(pi, po, C, T, ip, op, float(alpha), float(beta),
+                                        ctypes.c_void_p(workspace.data_ptr()), int(workspace.numel()), _stream()))
+    return out
+
+
+def hb_iir2(inp, out, alpha, beta, workspace):
+    return _iir2("hb_iir2", inp, out, alpha, beta, workspace)
+
+
+def hb_iir2_valu(inp, out, alpha, beta, workspace):
+    return _iir2("hb_iir2_valu", inp, out, alpha, beta, workspace)
 
 
 def hb_resize_workspace_size(C, H, Wo):

@@ -168,6 +168,29 @@ def test_resize_argument_validation(lib, fn):
     assert lib.hb_resize_workspace_size(1, 61, 20) == 20 * 64 * 2      # rows padded to 8 samples
 
 
+@pytest.mark.parametrize("fn", ["hb_iir2", "hb_iir2_valu"])
+def test_iir2_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    WS = ctypes.c_void_p(0x10000)
+    ok = dict(i=FAKE, o=FAKE, C=2, T=5000, ip=5000, op=5000, a=1.6, b=-0.8, ws=WS, wsb=1 << 20)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["C"], p["T"], p["ip"], p["op"], p["a"], p["b"], p["ws"], p["wsb"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(C=0) == hb.HB_ERR_INVALID_ARG
+    assert call(T=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=4999) == hb.HB_ERR_INVALID_ARG
+    assert call(op=10) == hb.HB_ERR_INVALID_ARG
+    assert call(a=float("nan")) == hb.HB_ERR_INVALID_ARG
+    assert call(b=5.0) == hb.HB_ERR_INVALID_ARG
+    assert call(a=3.0, b=2.0) == hb.HB_ERR_UNSUPPORTED          # impulse response leaves the fp16 range within 32 samples
+    assert call(ws=None) == hb.HB_ERR_WORKSPACE
+    assert call(wsb=lib.hb_iir2_workspace_size(2, 5000) - 1) == hb.HB_ERR_WORKSPACE
+    assert lib.hb_iir2_workspace_size(2, 5000) == 2 * 10 * 16     # 10 tiles of 512 samples, two states of two floats
+
+
 def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
