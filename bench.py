@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling, Lanczos resize)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling, Lanczos resize, recursive filter)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -311,6 +311,26 @@ def main():
             out["supplementary"]["resize_lanczos3_3x2048x2048_to_%d" % n] = {
                 "mfma_ms": m_ms, "valu_ms": v_ms, "band": int(cf_h.shape[1]),
                 "mfma_input_gpixels_per_s": 3 * 2048 * 2048 / m_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
+        # ... and the paper's recursive filter (Sec. V-D): 2^21 stereo samples, a resonant second-order filter.
+        del rgb
+        aud = (torch.rand((2, 1 << 21), device=dev) * 2 - 1).half()
+        aout = torch.empty((2, 1 << 21), dtype=torch.float32, device=dev)
+        aws = torch.empty(hb.hb_iir2_workspace_size(2, 1 << 21), dtype=torch.uint8, device=dev)
+
+        def timed5(fn, iters):
+            for i in range(2):
+                fn(aud, aout, 1.6, -0.8, aws)
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for i in range(iters):
+                fn(aud, aout, 1.6, -0.8, aws)
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) / iters
+        m_ms, v_ms = timed5(hb.hb_iir2, 10), timed5(hb.hb_iir2_valu, 3)
+        out["supplementary"]["iir2_2x2097152"] = {
+            "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gsamples_per_s": 2 * (1 << 21) / m_ms / 1e6,
+            "mfma_over_valu": v_ms / m_ms}
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)

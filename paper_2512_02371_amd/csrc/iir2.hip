@@ -32,7 +32,8 @@ struct IirArgs {
     int64_t T, in_pitch, out_pitch;
     float* end;                               // [C][ntiles][2] state after each tile if it started from zero
     float* start;                             // [C][ntiles][2] true state before each tile
-    float m32[4], m512[4], mchunk[4];         // state maps over a block, a tile, a scan chunk (row-major 2x2)
+    float m32[4], m512[4], mwave[4];          // state maps over a block, a tile, a wave's tiles in the scan (row-major 2x2)
+    float mpow[6][4];                         // ... and over 2^j lanes' tiles, j = 0..5
     float ca[kIirBlock], cb[kIirBlock];       // response of output i to the initial state (Y_-1, Y_-2)
     uint16_t thi[kIirBlock], tlo[kIirBlock];  // impulse response h_0..h_31 as rounded fp16 + rounded remainder
     float alpha, beta;
@@ -109,26 +110,65 @@ __global__ void __launch_bounds__(256) iir2_state_mfma_kernel(IirArgs p) {
     }
 }
 
-// 2  true state before every tile: one wave per channel, a lane owns `chunk` consecutive tiles
-__global__ void __launch_bounds__(64) iir2_scan_kernel(IirArgs p) {
-    const int lane = threadIdx.x, ch = blockIdx.x;
+// 2  true state before every tile: one workgroup of 16 waves per channel, a lane owns `chunk`
+// consecutive tiles.  Lanes are scanned in doubling steps, waves chained serially; only the last
+// lanes may own fewer tiles, and nothing depends on what follows them.
+constexpr int kIirScanWaves = 16;
+
+__device__ __forceinline__ State2 iir_scan_tiles(const IirArgs& p, const float* e, float* st, int lo, int hi, State2 s) {
+    // eight tiles at a time: their end states are requested together, then chained
+    for (int t0 = lo; t0 < hi; t0 += 8) {
+        float ea[8], eb[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            ea[k] = t0 + k < hi ? e[2 * (t0 + k)] : 0.f;
+            eb[k] = t0 + k < hi ? e[2 * (t0 + k) + 1] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (t0 + k < hi) {
+                if (st) {
+                    st[2 * (t0 + k)] = s.a;
+                    st[2 * (t0 + k) + 1] = s.b;
+                }
+                s = iir_step(p.m512, s, ea[k], eb[k]);
+            }
+    }
+    return s;
+}
+
+__global__ void __launch_bounds__(64 * kIirScanWaves) iir2_scan_kernel(IirArgs p) {
+    __shared__ float s_tot[kIirScanWaves][2];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, ch = blockIdx.x;
     const float* e = p.end + 2 * (int64_t)ch * p.ntiles;
     float* st = p.start + 2 * (int64_t)ch * p.ntiles;
-    const int lo = min(lane * p.chunk, p.ntiles), hi = min(lo + p.chunk, p.ntiles);
-    State2 q{0.f, 0.f};                                    // effect of the lane's tiles on a zero state
-    for (int t = lo; t < hi; ++t) q = iir_step(p.m512, q, e[2 * t], e[2 * t + 1]);
-    State2 run{0.f, 0.f}, mine{0.f, 0.f};                  // state before lane l's first tile
-    for (int l = 0; l < 64; ++l) {
-        if (lane == l) mine = run;
-        const float qa = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q.a), l));
-        const float qb = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q.b), l));
-        run = iir_step(p.mchunk, run, qa, qb);
+    const int lo = (int)min((int64_t)threadIdx.x * p.chunk, (int64_t)p.ntiles), hi = min(lo + p.chunk, p.ntiles);
+    const State2 q = iir_scan_tiles(p, e, nullptr, lo, hi, State2{0.f, 0.f});   // the lane's tiles applied to a zero state
+    // Inclusive scan over the lanes of a wave in six doubling steps: after step j a lane holds the
+    // effect of up to 2^(j+1) lanes ending with itself; the left half of a merge is carried across
+    // the 2^j lanes of the right half by the matching power of the lane map.
+    auto scan_lanes = [&](State2 v) {
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            const float la = __shfl_up(v.a, 1 << j, 64), lb = __shfl_up(v.b, 1 << j, 64);
+            if (lane >= (1 << j)) v = iir_step(p.mpow[j], State2{la, lb}, v.a, v.b);
+        }
+        return v;
+    };
+    const State2 incl = scan_lanes(q);                                // lanes 0..l applied to a zero state
+    if (lane == 63) {
+        s_tot[wv][0] = incl.a;                                        // the wave's tiles applied to a zero state
+        s_tot[wv][1] = incl.b;
     }
-    for (int t = lo; t < hi; ++t) {
-        st[2 * t] = mine.a;
-        st[2 * t + 1] = mine.b;
-        mine = iir_step(p.m512, mine, e[2 * t], e[2 * t + 1]);
-    }
+    __syncthreads();
+    State2 ws{0.f, 0.f};                                              // state before the wave's first tile
+    for (int w = 0; w < wv; ++w) ws = iir_step(p.mwave, ws, s_tot[w][0], s_tot[w][1]);
+    // the wave's start enters through lane 0; the scan then gives the state AFTER every lane
+    const State2 q0 = lane == 0 ? iir_step(p.mpow[0], ws, q.a, q.b) : q;
+    const State2 after = scan_lanes(q0);
+    const float pa = __shfl_up(after.a, 1, 64), pb = __shfl_up(after.b, 1, 64);
+    const State2 mine = lane == 0 ? ws : State2{pa, pb};              // state before the lane's first tile
+    iir_scan_tiles(p, e, st, lo, hi, mine);
 }
 
 // 3  outputs
@@ -301,7 +341,7 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
     a.in_pitch = in_pitch;
     a.out_pitch = out_pitch;
     a.ntiles = (int)ntiles64;
-    a.chunk = (a.ntiles + 63) / 64;
+    a.chunk = (a.ntiles + 64 * kIirScanWaves - 1) / (64 * kIirScanWaves);
     a.end = reinterpret_cast<float*>(workspace);
     a.start = a.end + 2 * (size_t)C * a.ntiles;
     a.alpha = alpha;
@@ -324,12 +364,19 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
         a.cb[i] = (float)cb[i];
     }
     const Mat2 m32{{ca[31], cb[31], ca[30], cb[30]}};
-    const Mat2 m512 = mat2_pow(m32, 16), mchunk = mat2_pow(m512, a.chunk);
+    const Mat2 m512 = mat2_pow(m32, 16), mchunk = mat2_pow(m512, a.chunk), mwave = mat2_pow(mchunk, 64);
     for (int i = 0; i < 4; ++i) {
-        if (!(fabs(m512.v[i]) < 1.0e30) || !(fabs(mchunk.v[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
+        if (!(fabs(m512.v[i]) < 1.0e30) || !(fabs(mwave.v[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
         a.m32[i] = (float)m32.v[i];
         a.m512[i] = (float)m512.v[i];
-        a.mchunk[i] = (float)mchunk.v[i];
+        a.mwave[i] = (float)mwave.v[i];
+    }
+    for (int j = 0; j < 6; ++j) {
+        const Mat2 mp = mat2_pow(mchunk, (int64_t)1 << j);
+        for (int i = 0; i < 4; ++i) {
+            if (!(fabs(mp.v[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
+            a.mpow[j][i] = (float)mp.v[i];
+        }
     }
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -337,7 +384,7 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
     const unsigned blocks = (unsigned)((waves + 3) / 4);
     if (valu) hipLaunchKernelGGL(iir2_blocks_valu_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL(iir2_state_mfma_kernel, dim3(blocks), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(iir2_scan_kernel, dim3(C), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(iir2_scan_kernel, dim3(C), dim3(64 * kIirScanWaves), 0, st, a);
     if (valu) hipLaunchKernelGGL(iir2_blocks_valu_kernel<true>, dim3(blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL(iir2_apply_mfma_kernel, dim3(blocks), dim3(256), 0, st, a);
     return launch_status();
