@@ -146,6 +146,53 @@ def iir2(sig, alpha, beta):
     return out
 
 
+def dct16_matrix():
+    """Orthonormal 16-point DCT-II: D[u][i] = s_u cos(pi (2i + 1) u / 32), s_0 = 1/4, s_u = sqrt(2)/4."""
+    u = np.arange(16, dtype=np.float64)[:, None]
+    i = np.arange(16, dtype=np.float64)[None, :]
+    D = np.cos(np.pi * (2.0 * i + 1.0) * u / 32.0) * np.sqrt(2.0 / 16.0)
+    D[0] = 0.25
+    return D
+
+
+def sine_window16():
+    """w(i) = sin(pi (i + 1/2) / 16): w(i)^2 + w(i + 8)^2 = 1, so half-overlapping tiles sum to one."""
+    return np.sin(np.pi * (np.arange(16, dtype=np.float64) + 0.5) / 16.0)
+
+
+def dct_denoise(img, threshold, margin=0.0):
+    """Transform-domain coring of one plane (Sec. V-E): 16 x 16 tiles at stride 8, each multiplied by
+    the separable sine window, transformed by the 2-D DCT (D T D^T), every bin except DC whose magnitude
+    is below `threshold` set to zero, transformed back (D^T Y D), windowed again and blended,
+    out = sum_tiles(w rec) / sum_tiles(w^2).  Tile origins are (8 ty, 8 tx), 0 <= ty < H/8 - 1.
+    Also returns a mask of the pixels touched by a tile with a bin within `margin` of the threshold
+    (a hard threshold makes those bins, and only those, sensitive to rounding)."""
+    img, _ = _u16(img)
+    X = img.view(np.float16).astype(np.float64)
+    H, W = X.shape
+    assert H % 8 == 0 and W % 8 == 0 and H >= 16 and W >= 16
+    D, w = dct16_matrix(), sine_window16()
+    w2 = np.outer(w, w)
+    num = np.zeros((H, W))
+    den = np.zeros((H, W))
+    risky = np.zeros((H, W), dtype=bool)
+    for ty in range(H // 8 - 1):
+        for tx in range(W // 8 - 1):
+            y0, x0 = 8 * ty, 8 * tx
+            Y = D @ (X[y0:y0 + 16, x0:x0 + 16] * w2) @ D.T
+            keep = np.abs(Y) >= threshold
+            keep[0, 0] = True
+            if margin > 0.0:
+                near = np.abs(np.abs(Y) - threshold) < margin
+                near[0, 0] = False
+                if near.any():
+                    risky[y0:y0 + 16, x0:x0 + 16] = True
+            rec = D.T @ (Y * keep) @ D
+            num[y0:y0 + 16, x0:x0 + 16] += rec * w2
+            den[y0:y0 + 16, x0:x0 + 16] += w2 * w2
+    return num / den, risky
+
+
 def band_resize(img, start_y, coef_y, start_x, coef_x):
     """One plane resized with two banded matrices (Sec. V-C): row o of a matrix holds `band` fp16
     coefficients for the input indices start[o] .. start[o] + band - 1 (clamped into the image)."""

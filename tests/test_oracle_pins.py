@@ -742,3 +742,63 @@ def test_iir2_channels_are_independent_and_the_recursion_holds_pointwise(orc):
     X = d(x)
     assert np.allclose(y[:, 2:], X[:, 2:] + alpha * y[:, 1:-1] + beta * y[:, :-2], atol=1e-14)
     assert np.array_equal(orc.iir2(x[1:2], alpha, beta)[0], y[1])
+
+
+# --------------------------------------------------------------------------
+# dct_denoise: transform-domain coring on 16 x 16 windowed tiles (Sec. V-E)
+# --------------------------------------------------------------------------
+
+def test_dct16_matrix_is_orthonormal_and_is_the_library_dct(orc):
+    from scipy.fft import dct
+    D = orc.dct16_matrix()
+    assert np.allclose(D @ D.T, np.eye(16), atol=1e-14)
+    x = d(rand_img(151, 16, 16))
+    assert np.allclose(D @ x, dct(x, type=2, norm="ortho", axis=0), atol=1e-13)
+    assert D[0, 0] == 0.25 and D[1, 0] == pytest.approx(np.sqrt(2) / 4 * np.cos(np.pi / 32), abs=1e-16)
+
+
+def test_sine_window_overlap_sums_to_one(orc):
+    w = orc.sine_window16()
+    assert np.allclose(w[:8] ** 2 + w[8:] ** 2, 1.0, atol=1e-15)
+    assert np.allclose(w, w[::-1], atol=1e-15)
+
+
+def test_dct_denoise_without_threshold_is_the_identity(orc):
+    img = rand_img(152, 32, 40)
+    out, _ = orc.dct_denoise(img, 0.0)
+    assert np.allclose(out, d(img), atol=1e-13)
+
+
+def test_dct_denoise_keeps_a_constant_image_at_any_threshold(orc):
+    """A constant tile times the window is not constant, so this only holds because the threshold
+    test is on the magnitude: with threshold 0 nothing is cut; with a huge one only DC survives and a
+    tile reconstructs to the projection of its windowed content on the constant."""
+    img = h(np.full((24, 24), 0.5))
+    w = orc.sine_window16()
+    out, _ = orc.dct_denoise(img, 1e9)
+    # interior pixel (8..15, 8..15) is covered by four tiles; each tile's reconstruction is the constant
+    # mean(0.5 w2) = 0.5 mean(w)^2; blended with weights w2: 0.5 mean(w)^2 sum(w2) / sum(w2^2)
+    w2 = np.outer(w, w)
+    y, x = 11, 13
+    num = den = 0.0
+    for ty in (0, 1):
+        for tx in (0, 1):
+            ww = w2[y - 8 * ty, x - 8 * tx]
+            num += 0.5 * w2.mean() * ww
+            den += ww * ww
+    assert out[y, x] == pytest.approx(num / den, abs=1e-14)
+
+
+def test_dct_denoise_removes_a_small_oscillation_and_keeps_a_large_one(orc):
+    """One tile's worth of a pure DCT basis function: below the threshold it is cut, above it survives."""
+    D, w = orc.dct16_matrix(), orc.sine_window16()
+    base = np.outer(D[3], D[5])                       # a unit-energy basis image, |values| <= 1/8
+    img16 = np.round((0.5 + 0.25 * base) * 1024) / 1024          # on the fp16 grid
+    Y = D @ (img16 * np.outer(w, w)) @ D.T
+    big = np.sort(np.abs(Y).ravel())[-2]                        # largest non-DC bin
+    img = h(img16)
+    cut, _ = orc.dct_denoise(img, big * 1.01)
+    kept, _ = orc.dct_denoise(img, 0.0)
+    rec_dc = D.T @ (Y * (np.arange(256).reshape(16, 16) == 0)) @ D
+    assert np.allclose(kept, img16, atol=1e-13)
+    assert np.allclose(cut, rec_dc * np.outer(w, w) / np.outer(w, w) ** 2, atol=1e-12)
