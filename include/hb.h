@@ -223,6 +223,29 @@ hb_status hb_iir2_valu(const hb_half *in, float *out, int C, int64_t T, int64_t 
                        float alpha, float beta, void *workspace, size_t workspace_bytes, hb_stream stream);
 
 /*
+ * DCT-domain denoising by coring (Sec. V-E): 16 x 16 tiles at stride 8; a tile is
+ * multiplied by the separable window w(i) = sin(pi (i + 1/2) / 16), transformed by
+ * the orthonormal 2-D DCT-II (D T D^T), every bin except DC with magnitude below
+ * `threshold` is set to zero, the tile is transformed back (D^T Y D), windowed again,
+ * and the overlapping tiles are blended:
+ *     out = sum_tiles(w * reconstruction) / sum_tiles(w^2)
+ * Tile origins are (8 ty, 8 tx), 0 <= ty < H/8 - 1, 0 <= tx < W/8 - 1.  (The paper
+ * fixes the tile size, the four fused products and the separate blend; window,
+ * stride and the treatment of DC are this library's choices.)  in: C planes of H x W
+ * fp16, out: C planes of H x W fp32 (row pitches and plane strides in elements);
+ * H and W multiples of 8 and >= 16; threshold >= 0.  `workspace`: device scratch of
+ * at least hb_dct_denoise_workspace_size(C, H, W) bytes, 256-byte aligned; contents
+ * undefined on exit; concurrent calls need their own.
+ */
+size_t hb_dct_denoise_workspace_size(int C, int H, int W);
+hb_status hb_dct_denoise(const hb_half *in, float *out, int C, int H, int W,
+                         int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                         float threshold, void *workspace, size_t workspace_bytes, hb_stream stream);
+hb_status hb_dct_denoise_valu(const hb_half *in, float *out, int C, int H, int W,
+                              int64_t in_pitch, int64_t in_plane, int64_t out_pitch, int64_t out_plane,
+                              float threshold, void *workspace, size_t workspace_bytes, hb_stream stream);
+
+/*
  * Summed-area table (inclusive prefix sum over rows and columns; a product
  * L * X * U with triangular all-ones matrices per tile plus inter-tile carries --
  * the tile-then-fix-up structure of Sec. V-D applied to a first-order recursion):

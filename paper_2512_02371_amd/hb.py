@@ -32,6 +32,7 @@ SYMBOLS = [
     "hb_down2", "hb_down2_valu", "hb_up2", "hb_up2_valu",
     "hb_resize_workspace_size", "hb_resize", "hb_resize_valu", "hb_lanczos3_band", "hb_lanczos3_matrix",
     "hb_iir2_workspace_size", "hb_iir2", "hb_iir2_valu",
+    "hb_dct_denoise_workspace_size", "hb_dct_denoise", "hb_dct_denoise_valu",
     "hb_sepblur", "hb_sepblur_valu",
     "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu",
     "hb_conv3x3", "hb_conv3x3_valu",
@@ -94,6 +95,12 @@ def load() -> ctypes.CDLL:
         getattr(L, name).restype = I
     L.hb_iir2_workspace_size.argtypes = [I, I64]
     L.hb_iir2_workspace_size.restype = ctypes.c_size_t
+    dct = [vp, vp, I, I, I, I64, I64, I64, I64, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    for name in ("hb_dct_denoise", "hb_dct_denoise_valu"):
+        getattr(L, name).argtypes = dct
+        getattr(L, name).restype = I
+    L.hb_dct_denoise_workspace_size.argtypes = [I, I, I]
+    L.hb_dct_denoise_workspace_size.restype = ctypes.c_size_t
     L.hb_sat2d_workspace_size.argtypes = [I, I]
     L.hb_sat2d_workspace_size.restype = ctypes.c_size_t
     _lib = L
@@ -190,6 +197,32 @@ def hb_up2(inp, out, taps2d, anchor_y, anchor_x):
 
 def hb_up2_valu(inp, out, taps2d, anchor_y, anchor_x):
     return _conv2d("hb_up2_valu", inp, out, taps2d, anchor_y, anchor_x, _double_shape)
+
+
+def hb_dct_denoise_workspace_size(C, H, W):
+    return int(load().hb_dct_denoise_workspace_size(int(C), int(H), int(W)))
+
+
+def _dct(name, inp, out, threshold, workspace):
+    import torch
+    assert inp.is_cuda and inp.dim() == 3 and inp.dtype == torch.float16 and inp.stride(2) == 1
+    assert out.is_cuda and out.dim() == 3 and out.dtype == torch.float32 and out.stride(2) == 1
+    assert tuple(inp.shape) == tuple(out.shape)
+    assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+    C, H, W = (int(v) for v in inp.shape)
+    _check(name, getattr(load(), name)(
+        ctypes.c_void_p(inp.data_ptr()), ctypes.c_void_p(out.data_ptr()), C, H, W,
+        int(inp.stride(1)), int(inp.stride(0)), int(out.stride(1)), int(out.stride(0)), float(threshold),
+        ctypes.c_void_p(workspace.data_ptr()), int(workspace.numel()), _stream()))
+    return out
+
+
+def hb_dct_denoise(inp, out, threshold, workspace):
+    return _dct("hb_dct_denoise", inp, out, threshold, workspace)
+
+
+def hb_dct_denoise_valu(inp, out, threshold, workspace):
+    return _dct("hb_dct_denoise_valu", inp, out, threshold, workspace)
 
 
 def hb_iir2_workspace_size(C, T):

@@ -191,6 +191,30 @@ def test_iir2_argument_validation(lib, fn):
     assert lib.hb_iir2_workspace_size(2, 5000) == 2 * 10 * 16     # 10 tiles of 512 samples, two states of two floats
 
 
+@pytest.mark.parametrize("fn", ["hb_dct_denoise", "hb_dct_denoise_valu"])
+def test_dct_denoise_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    WS = ctypes.c_void_p(0x10000)
+    ok = dict(i=FAKE, o=FAKE, C=3, H=64, W=96, ip=96, ipl=64 * 96, op=96, opl=64 * 96, thr=0.05, ws=WS, wsb=1 << 24)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["C"], p["H"], p["W"], p["ip"], p["ipl"], p["op"], p["opl"], p["thr"], p["ws"], p["wsb"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(C=0) == hb.HB_ERR_INVALID_ARG
+    assert call(H=8) == hb.HB_ERR_INVALID_ARG                   # at least one 16 x 16 tile
+    assert call(W=100) == hb.HB_ERR_INVALID_ARG                 # multiples of the tile stride
+    assert call(ip=95) == hb.HB_ERR_INVALID_ARG
+    assert call(opl=64 * 96 - 1) == hb.HB_ERR_INVALID_ARG
+    assert call(thr=-1.0) == hb.HB_ERR_INVALID_ARG
+    assert call(thr=float("nan")) == hb.HB_ERR_INVALID_ARG
+    assert call(ws=None) == hb.HB_ERR_WORKSPACE
+    assert call(wsb=lib.hb_dct_denoise_workspace_size(3, 64, 96) - 1) == hb.HB_ERR_WORKSPACE
+    assert lib.hb_dct_denoise_workspace_size(3, 64, 96) == 3 * 7 * 11 * 1024
+    assert lib.hb_dct_denoise_workspace_size(1, 60, 96) == 0
+
+
 def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
