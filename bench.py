@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling, Lanczos resize, recursive filter)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling, Lanczos resize, recursive filter, DCT denoise)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -330,6 +330,26 @@ def main():
         m_ms, v_ms = timed5(hb.hb_iir2, 10), timed5(hb.hb_iir2_valu, 3)
         out["supplementary"]["iir2_2x2097152"] = {
             "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gsamples_per_s": 2 * (1 << 21) / m_ms / 1e6,
+            "mfma_over_valu": v_ms / m_ms}
+        # ... and the paper's DCT-domain denoising (Sec. V-E): a one-megapixel three-channel image.
+        del aud, aout
+        dimg = torch.rand((3, 1024, 1024), device=dev).half()
+        dout = torch.empty((3, 1024, 1024), dtype=torch.float32, device=dev)
+        dws = torch.empty(hb.hb_dct_denoise_workspace_size(3, 1024, 1024), dtype=torch.uint8, device=dev)
+
+        def timed6(fn, iters):
+            for i in range(2):
+                fn(dimg, dout, 0.05, dws)
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for i in range(iters):
+                fn(dimg, dout, 0.05, dws)
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) / iters
+        m_ms, v_ms = timed6(hb.hb_dct_denoise, 10), timed6(hb.hb_dct_denoise_valu, 3)
+        out["supplementary"]["dct_denoise_3x1024x1024"] = {
+            "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": 3 * 1024 * 1024 / m_ms / 1e6,
             "mfma_over_valu": v_ms / m_ms}
 
     if not args.no_cpu:
