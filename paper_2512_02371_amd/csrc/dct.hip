@@ -66,16 +66,27 @@ __global__ void __launch_bounds__(64 * kDctWaves) dct_transform_mfma_kernel(DctA
         dkl[kk] = p.d[(4 * kk + g) * 16 + c];
         win[kk] = p.w[c] * p.w[4 * kk + g];
     }
+    float wout[4];                            // window of the lane's four output pixels
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wout[j] = p.w[4 * g + j] * p.w[c];
     const int64_t ntiles = (int64_t)p.C * p.nty * p.ntx;
     const int64_t stride = (int64_t)gridDim.x * kDctWaves;
-    for (int64_t t = (int64_t)blockIdx.x * kDctWaves + wv; t < ntiles; t += stride) {
+    // lane (c = row, g) reads pixels (row, 4 kk + g); the next tile's pixels are requested a tile ahead
+    auto request = [&](int64_t t, half_t (&raw)[4]) {
         int plane, y0, x0;
         dct_tile_origin(p, t, plane, y0, x0);
-        // lane (c = row, g): pixels (row, 4 kk + g), windowed
         const half_t* src = p.in + (int64_t)plane * p.in_plane + (int64_t)(y0 + c) * p.in_pitch + x0 + g;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) raw[kk] = src[4 * kk];
+    };
+    half_t ahead[4];
+    const int64_t first = (int64_t)blockIdx.x * kDctWaves + wv;
+    if (first < ntiles) request(first, ahead);
+    for (int64_t t = first; t < ntiles; t += stride) {
         float px[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) px[kk] = (float)src[4 * kk] * win[kk];
+        for (int kk = 0; kk < 4; ++kk) px[kk] = (float)ahead[kk] * win[kk];
+        if (t + stride < ntiles) request(t + stride, ahead);
         // Q = T D^T   (A = T [row][col], B = D^T [col][v] = D[v][col])
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -116,7 +127,7 @@ __global__ void __launch_bounds__(64 * kDctWaves) dct_transform_mfma_kernel(DctA
         // lane (c = col, g) holds rec[4g + j][col]: window again and keep the tile for the blend
         float* dst = p.tiles + t * 256;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dst[(4 * g + j) * 16 + c] = acc[j] * p.w[4 * g + j] * p.w[c];
+        for (int j = 0; j < 4; ++j) dst[(4 * g + j) * 16 + c] = acc[j] * wout[j];
     }
 }
 
@@ -175,13 +186,15 @@ __global__ void __launch_bounds__(64 * kDctWaves) dct_transform_valu_kernel(DctA
 // 2  blend: out = sum over the (up to four) tiles covering a pixel of their windowed
 // reconstruction, divided by the sum of their squared windows.  A thread owns four consecutive pixels.
 __global__ void __launch_bounds__(256) dct_blend_kernel(DctArgs p) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int wq = p.W / 4;
-    const int64_t per_plane = (int64_t)p.H * wq;
-    if (idx >= per_plane * p.C) return;
-    const int plane = (int)(idx / per_plane);
-    const int64_t rem = idx - (int64_t)plane * per_plane;
-    const int y = (int)(rem / wq), x = 4 * (int)(rem - (int64_t)y * wq);
+    // a workgroup covers 16 rows x 64 columns: the 64-byte rows of a tile it reads share their
+    // cache lines with the rows above and below, which the same workgroup reads as well
+    const int bx_n = (p.W + 63) / 64, by_n = (p.H + 15) / 16;
+    int wg = blockIdx.x;
+    const int bx = wg % bx_n;
+    wg /= bx_n;
+    const int by = wg % by_n, plane = wg / by_n;
+    const int y = 16 * by + (threadIdx.x >> 4), x = 64 * bx + 4 * (threadIdx.x & 15);
+    if (y >= p.H || x >= p.W) return;
     floatx4 num = {0.f, 0.f, 0.f, 0.f}, den = {0.f, 0.f, 0.f, 0.f};
     for (int ty = y / 8 - 1; ty <= y / 8; ++ty) {
         if (ty < 0 || ty >= p.nty) continue;
@@ -243,8 +256,7 @@ static hb_status dct_run(bool valu, const hb_half* in, float* out, int C, int H,
     const unsigned blocks = (unsigned)(wgs < 4096 ? wgs : 4096);     // waves stride over the tiles
     if (valu) hipLaunchKernelGGL(dct_transform_valu_kernel, dim3(blocks), dim3(64 * kDctWaves), 0, st, a);
     else hipLaunchKernelGGL(dct_transform_mfma_kernel, dim3(blocks), dim3(64 * kDctWaves), 0, st, a);
-    const int64_t quads = (int64_t)C * H * (W / 4);
-    const int64_t bblocks = (quads + 255) / 256;
+    const int64_t bblocks = (int64_t)C * ((H + 15) / 16) * ((W + 63) / 64);
     if (bblocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(dct_blend_kernel, dim3((unsigned)bblocks), dim3(256), 0, st, a);
     return launch_status();
