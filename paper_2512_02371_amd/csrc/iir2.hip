@@ -88,25 +88,28 @@ __device__ __forceinline__ void iir_block_tail(const IirTails& t, int b, float& 
 // 1  end state of every tile started from zero
 __global__ void __launch_bounds__(256) iir2_state_mfma_kernel(IirArgs p) {
     const int lane = threadIdx.x & 63;
-    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
-    if (wave >= (int64_t)p.C * p.ntiles) return;
-    const int ch = (int)(wave / p.ntiles), tile = (int)(wave - (int64_t)ch * p.ntiles);
-    const half8 x = iir_load_tile(p.in + (int64_t)ch * p.in_pitch, (int64_t)tile * kIirTile, p.T, lane);
-    floatx4 d1 = {0.f, 0.f, 0.f, 0.f};
-    d1 = mfma16x16x32(iir_fragment(p.thi, 1, lane), x, d1);
-    d1 = mfma16x16x32(iir_fragment(p.tlo, 1, lane), x, d1);
-    State2 s{0.f, 0.f};
-    const IirTails tails = iir_tails(d1);
+    const half8 fhi = iir_fragment(p.thi, 1, lane), flo = iir_fragment(p.tlo, 1, lane);
+    const int64_t total = (int64_t)p.C * p.ntiles, nwaves = (int64_t)gridDim.x * 4;
+    // waves stride over the tiles: the fragments above are built once per wave
+    for (int64_t w = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6; w < total; w += nwaves) {
+        const int ch = (int)(w / p.ntiles), tile = (int)(w - (int64_t)ch * p.ntiles);
+        const half8 x = iir_load_tile(p.in + (int64_t)ch * p.in_pitch, (int64_t)tile * kIirTile, p.T, lane);
+        floatx4 d1 = {0.f, 0.f, 0.f, 0.f};
+        d1 = mfma16x16x32(fhi, x, d1);
+        d1 = mfma16x16x32(flo, x, d1);
+        State2 s{0.f, 0.f};
+        const IirTails tails = iir_tails(d1);
 #pragma unroll
-    for (int b = 0; b < 16; ++b) {
-        float l1, l0;
-        iir_block_tail(tails, b, l1, l0);
-        s = iir_step(p.m32, s, l1, l0);
-    }
-    if (lane == 0) {
-        float* e = p.end + 2 * ((int64_t)ch * p.ntiles + tile);
-        e[0] = s.a;
-        e[1] = s.b;
+        for (int b = 0; b < 16; ++b) {
+            float l1, l0;
+            iir_block_tail(tails, b, l1, l0);
+            s = iir_step(p.m32, s, l1, l0);
+        }
+        if (lane == 0) {
+            float* e = p.end + 2 * w;
+            e[0] = s.a;
+            e[1] = s.b;
+        }
     }
 }
 
@@ -176,49 +179,60 @@ __global__ void __launch_bounds__(256) iir2_apply_mfma_kernel(IirArgs p) {
     __shared__ __attribute__((aligned(16))) float s_patch[4 * RowPatch<2>::kFloats];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
-    if (wave >= (int64_t)p.C * p.ntiles) return;
-    const int ch = (int)(wave / p.ntiles), tile = (int)(wave - (int64_t)ch * p.ntiles);
-    const int64_t t0 = (int64_t)tile * kIirTile;
-    const half8 x = iir_load_tile(p.in + (int64_t)ch * p.in_pitch, t0, p.T, lane);
-    floatx4 d[2];
+    half8 fhi[2], flo[2];
+    float ra[2][4], rb[2][4];                 // response of the lane's outputs i = 16 hh + 4 g + j to the block's state
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-        d[hh] = floatx4{0.f, 0.f, 0.f, 0.f};
-        d[hh] = mfma16x16x32(iir_fragment(p.thi, hh, lane), x, d[hh]);
-        d[hh] = mfma16x16x32(iir_fragment(p.tlo, hh, lane), x, d[hh]);
-    }
-    // block states from the true tile state; lane (c, g) keeps the state before block c
-    const float* st = p.start + 2 * ((int64_t)ch * p.ntiles + tile);
-    State2 s{st[0], st[1]}, mine{0.f, 0.f};
-    const IirTails tails = iir_tails(d[1]);
-#pragma unroll
-    for (int b = 0; b < 16; ++b) {
-        if (c == b) mine = s;
-        float l1, l0;
-        iir_block_tail(tails, b, l1, l0);
-        s = iir_step(p.m32, s, l1, l0);
-    }
-    // lane (c = block, g) holds outputs i = 16 hh + 4 g + j of its block: add the response to the block's state
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh)
+        fhi[hh] = iir_fragment(p.thi, hh, lane);
+        flo[hh] = iir_fragment(p.tlo, hh, lane);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int i = 16 * hh + 4 * g + j;
-            d[hh][j] += p.ca[i] * mine.a + p.cb[i] * mine.b;
+            ra[hh][j] = p.ca[16 * hh + 4 * g + j];
+            rb[hh][j] = p.cb[16 * hh + 4 * g + j];
         }
-    float* dst = p.out + (int64_t)ch * p.out_pitch + t0;
-    if (t0 + kIirTile <= p.T) {
-        // the tile is 16 rows (blocks) of 32 consecutive samples
-        store_rows_via_lds<2, true>(s_patch + wv * RowPatch<2>::kFloats, dst, kIirBlock, d, lane);
-    } else {
+    }
+    const int64_t total = (int64_t)p.C * p.ntiles, nwaves = (int64_t)gridDim.x * 4;
+    // waves stride over the tiles: fragments and responses above are built once per wave
+    for (int64_t w = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6; w < total; w += nwaves) {
+        const int ch = (int)(w / p.ntiles), tile = (int)(w - (int64_t)ch * p.ntiles);
+        const int64_t t0 = (int64_t)tile * kIirTile;
+        const half8 x = iir_load_tile(p.in + (int64_t)ch * p.in_pitch, t0, p.T, lane);
+        floatx4 d[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            d[hh] = floatx4{0.f, 0.f, 0.f, 0.f};
+            d[hh] = mfma16x16x32(fhi[hh], x, d[hh]);
+            d[hh] = mfma16x16x32(flo[hh], x, d[hh]);
+        }
+        // block states from the true tile state; lane (c, g) keeps the state before block c
+        const float* st = p.start + 2 * w;
+        State2 s{st[0], st[1]}, mine{0.f, 0.f};
+        const IirTails tails = iir_tails(d[1]);
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            if (c == b) mine = s;
+            float l1, l0;
+            iir_block_tail(tails, b, l1, l0);
+            s = iir_step(p.m32, s, l1, l0);
+        }
+        // lane (c = block, g) holds outputs i = 16 hh + 4 g + j of its block: add the response to the block's state
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = 32 * c + 16 * hh + 4 * g + j;
-                if (t0 + i < p.T) dst[i] = d[hh][j];
-            }
+            for (int j = 0; j < 4; ++j) d[hh][j] += ra[hh][j] * mine.a + rb[hh][j] * mine.b;
+        float* dst = p.out + (int64_t)ch * p.out_pitch + t0;
+        if (t0 + kIirTile <= p.T) {
+            // the tile is 16 rows (blocks) of 32 consecutive samples
+            store_rows_via_lds<2, true>(s_patch + wv * RowPatch<2>::kFloats, dst, kIirBlock, d, lane);
+        } else {
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = 32 * c + 16 * hh + 4 * g + j;
+                    if (t0 + i < p.T) dst[i] = d[hh][j];
+                }
+        }
     }
 }
 
@@ -381,7 +395,9 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int64_t waves = (int64_t)C * (valu ? (a.ntiles + 3) / 4 : a.ntiles);
-    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    int64_t wgs = (waves + 3) / 4;
+    if (!valu && wgs > 8 * kNumCU) wgs = 8 * kNumCU;          // the matrix kernels' waves stride over the tiles
+    const unsigned blocks = (unsigned)wgs;
     if (valu) hipLaunchKernelGGL(iir2_blocks_valu_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL(iir2_state_mfma_kernel, dim3(blocks), dim3(256), 0, st, a);
     hipLaunchKernelGGL(iir2_scan_kernel, dim3(C), dim3(64 * kIirScanWaves), 0, st, a);
