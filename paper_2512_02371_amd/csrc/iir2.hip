@@ -34,6 +34,8 @@ struct IirArgs {
     float* start;                             // [C][ntiles][2] true state before each tile
     float m32[4], m512[4], mwave[4];          // state maps over a block, a tile, a wave's tiles in the scan (row-major 2x2)
     float mpow[6][4];                         // ... and over 2^j lanes' tiles, j = 0..5
+    float bpow[4][4];                         // state map over 2^j blocks, j = 0..3 (in-tile scan)
+    float bsel[16][4];                        // state map over b blocks, b = 0..15
     float ca[kIirBlock], cb[kIirBlock];       // response of output i to the initial state (Y_-1, Y_-2)
     uint16_t thi[kIirBlock], tlo[kIirBlock];  // impulse response h_0..h_31 as rounded fp16 + rounded remainder
     float alpha, beta;
@@ -68,21 +70,41 @@ __device__ __forceinline__ half8 iir_load_tile(const half_t* sig, int64_t t0, in
     return r;
 }
 
-// Last two local outputs (Y_31, Y_30) of the tile's 16 blocks: elements 3 and 2 of the upper-half
-// accumulator in lanes 48 .. 63.  The two elements are first copied into plain registers behind an
-// opaque statement: reading a lane straight out of an element of the accumulator vector was
-// compiled into a read of element 0.
-struct IirTails {
-    float y31, y30;
-};
-__device__ __forceinline__ IirTails iir_tails(const floatx4& d1) {
-    IirTails t{d1[3], d1[2]};
-    asm volatile("" : "+v"(t.y31), "+v"(t.y30));
-    return t;
+// value of lane (c - SH) of the same row of 16 lanes, 0 for c < SH
+template <int SH>
+__device__ __forceinline__ float iir_row_shr(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x110 + SH, 0xf, 0xf, true));
 }
-__device__ __forceinline__ void iir_block_tail(const IirTails& t, int b, float& l1, float& l0) {
-    l1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t.y31), 48 + b));
-    l0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t.y30), 48 + b));
+
+// The last two local outputs (Y_31, Y_30) of the tile's 16 blocks sit in elements 3 and 2 of the
+// upper-half accumulator, lanes 48 .. 63 (lane 48 + b for block b).  They are copied to every row
+// of 16 lanes, and an inclusive scan in four doubling steps (the left half of a merge carried
+// across the right half's 2^j blocks by the matching power of the block map) leaves in lane column
+// b the state after block b of a tile that started from zero.  The elements are first copied into
+// plain registers behind an opaque statement: a lane read straight out of an element of the
+// accumulator vector was compiled into a read of element 0.
+__device__ __forceinline__ State2 iir_scan_blocks(const IirArgs& p, const floatx4& d1, int lane) {
+    float y31 = d1[3], y30 = d1[2];
+    asm volatile("" : "+v"(y31), "+v"(y30));
+    State2 v{__shfl(y31, 48 + (lane & 15), 64), __shfl(y30, 48 + (lane & 15), 64)};
+    const int c = lane & 15;
+    {
+        const float la = iir_row_shr<1>(v.a), lb = iir_row_shr<1>(v.b);
+        if (c >= 1) v = iir_step(p.bpow[0], State2{la, lb}, v.a, v.b);
+    }
+    {
+        const float la = iir_row_shr<2>(v.a), lb = iir_row_shr<2>(v.b);
+        if (c >= 2) v = iir_step(p.bpow[1], State2{la, lb}, v.a, v.b);
+    }
+    {
+        const float la = iir_row_shr<4>(v.a), lb = iir_row_shr<4>(v.b);
+        if (c >= 4) v = iir_step(p.bpow[2], State2{la, lb}, v.a, v.b);
+    }
+    {
+        const float la = iir_row_shr<8>(v.a), lb = iir_row_shr<8>(v.b);
+        if (c >= 8) v = iir_step(p.bpow[3], State2{la, lb}, v.a, v.b);
+    }
+    return v;
 }
 
 // 1  end state of every tile started from zero
@@ -97,15 +119,8 @@ __global__ void __launch_bounds__(256) iir2_state_mfma_kernel(IirArgs p) {
         floatx4 d1 = {0.f, 0.f, 0.f, 0.f};
         d1 = mfma16x16x32(fhi, x, d1);
         d1 = mfma16x16x32(flo, x, d1);
-        State2 s{0.f, 0.f};
-        const IirTails tails = iir_tails(d1);
-#pragma unroll
-        for (int b = 0; b < 16; ++b) {
-            float l1, l0;
-            iir_block_tail(tails, b, l1, l0);
-            s = iir_step(p.m32, s, l1, l0);
-        }
-        if (lane == 0) {
+        const State2 s = iir_scan_blocks(p, d1, lane);        // lane column 15: the state after the last block
+        if (lane == 15) {
             float* e = p.end + 2 * w;
             e[0] = s.a;
             e[1] = s.b;
@@ -191,6 +206,9 @@ __global__ void __launch_bounds__(256) iir2_apply_mfma_kernel(IirArgs p) {
             rb[hh][j] = p.cb[16 * hh + 4 * g + j];
         }
     }
+    float bsel[4];                            // state map over the c blocks before the lane's block
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bsel[i] = p.bsel[c][i];
     const int64_t total = (int64_t)p.C * p.ntiles, nwaves = (int64_t)gridDim.x * 4;
     // waves stride over the tiles: fragments and responses above are built once per wave
     for (int64_t w = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6; w < total; w += nwaves) {
@@ -204,17 +222,10 @@ __global__ void __launch_bounds__(256) iir2_apply_mfma_kernel(IirArgs p) {
             d[hh] = mfma16x16x32(fhi[hh], x, d[hh]);
             d[hh] = mfma16x16x32(flo[hh], x, d[hh]);
         }
-        // block states from the true tile state; lane (c, g) keeps the state before block c
+        // state before block c = (tile state carried across c blocks) + (blocks 0 .. c-1 from zero)
         const float* st = p.start + 2 * w;
-        State2 s{st[0], st[1]}, mine{0.f, 0.f};
-        const IirTails tails = iir_tails(d[1]);
-#pragma unroll
-        for (int b = 0; b < 16; ++b) {
-            if (c == b) mine = s;
-            float l1, l0;
-            iir_block_tail(tails, b, l1, l0);
-            s = iir_step(p.m32, s, l1, l0);
-        }
+        const State2 incl = iir_scan_blocks(p, d[1], lane);
+        const State2 mine = iir_step(bsel, State2{st[0], st[1]}, iir_row_shr<1>(incl.a), iir_row_shr<1>(incl.b));
         // lane (c = block, g) holds outputs i = 16 hh + 4 g + j of its block: add the response to the block's state
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
@@ -384,6 +395,17 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
         a.m32[i] = (float)m32.v[i];
         a.m512[i] = (float)m512.v[i];
         a.mwave[i] = (float)mwave.v[i];
+    }
+    for (int j = 0; j < 4; ++j) {
+        const Mat2 bp = mat2_pow(m32, (int64_t)1 << j);
+        for (int i = 0; i < 4; ++i) a.bpow[j][i] = (float)bp.v[i];
+    }
+    for (int b = 0; b < 16; ++b) {
+        const Mat2 bs = mat2_pow(m32, b);
+        for (int i = 0; i < 4; ++i) {
+            if (!(fabs(bs.v[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
+            a.bsel[b][i] = (float)bs.v[i];
+        }
     }
     for (int j = 0; j < 6; ++j) {
         const Mat2 mp = mat2_pow(mchunk, (int64_t)1 << j);
