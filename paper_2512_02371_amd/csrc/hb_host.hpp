@@ -99,6 +99,29 @@ inline float half_bits_to_float(uint16_t h) {
     return out;
 }
 
+// float -> fp16 bit pattern, round to nearest even (finite inputs of moderate size only).
+inline uint16_t float_to_half_bits(float v) {
+    uint32_t b;
+    memcpy(&b, &v, sizeof(b));
+    const uint32_t sign = (b >> 16) & 0x8000u;
+    const int32_t e = (int32_t)((b >> 23) & 0xff) - 127 + 15;
+    uint32_t m = b & 0x7fffffu;
+    if (e >= 31) return (uint16_t)(sign | 0x7c00u);                       // overflow -> inf
+    if (e <= 0) {                                                         // subnormal or zero
+        if (e < -10) return (uint16_t)sign;
+        m |= 0x800000u;
+        const int shift = 14 - e;
+        uint32_t h = m >> shift;
+        const uint32_t rest = m & ((1u << shift) - 1), halfway = 1u << (shift - 1);
+        if (rest > halfway || (rest == halfway && (h & 1))) ++h;
+        return (uint16_t)(sign | h);
+    }
+    uint32_t h = ((uint32_t)e << 10) | (m >> 13);
+    const uint32_t rest = m & 0x1fffu;
+    if (rest > 0x1000u || (rest == 0x1000u && (h & 1))) ++h;             // may carry into the exponent: still right
+    return (uint16_t)(sign | h);
+}
+
 template <int MAXT = HB_MAX_TAPS>
 inline TapsT<MAXT> pack_taps(const hb_half* taps, int ntaps) {
     TapsT<MAXT> t;

@@ -323,29 +323,6 @@ static Mat2 mat2_pow(Mat2 m, int64_t n) {
     return r;
 }
 
-static uint16_t iir_float_to_half_bits(float v) {
-    // round to nearest even; |v| is below the fp16 range limit here (checked by the caller)
-    uint32_t b;
-    memcpy(&b, &v, sizeof(b));
-    const uint32_t sign = (b >> 16) & 0x8000u;
-    const int32_t e = (int32_t)((b >> 23) & 0xff) - 127 + 15;
-    uint32_t m = b & 0x7fffffu;
-    if (e >= 31) return (uint16_t)(sign | 0x7bffu);
-    if (e <= 0) {
-        if (e < -10) return (uint16_t)sign;
-        m |= 0x800000u;
-        const int shift = 14 - e;
-        uint32_t h = m >> shift;
-        const uint32_t rest = m & ((1u << shift) - 1), halfway = 1u << (shift - 1);
-        if (rest > halfway || (rest == halfway && (h & 1))) ++h;
-        return (uint16_t)(sign | h);
-    }
-    uint32_t h = ((uint32_t)e << 10) | (m >> 13);
-    const uint32_t rest = m & 0x1fffu;
-    if (rest > 0x1000u || (rest == 0x1000u && (h & 1))) ++h;
-    return (uint16_t)(sign | h);
-}
-
 static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
                           float alpha, float beta, void* workspace, size_t workspace_bytes, hb_stream stream) {
     if (!in || !out) return HB_ERR_INVALID_ARG;
@@ -383,8 +360,8 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
     }
     for (int i = 0; i < kIirBlock; ++i) {
         if (!(fabs(h[i]) < 3.0e4) || !(fabs(ca[i]) < 1.0e30) || !(fabs(cb[i]) < 1.0e30)) return HB_ERR_UNSUPPORTED;
-        a.thi[i] = iir_float_to_half_bits((float)h[i]);
-        a.tlo[i] = iir_float_to_half_bits((float)(h[i] - (double)half_bits_to_float(a.thi[i])));
+        a.thi[i] = float_to_half_bits((float)h[i]);
+        a.tlo[i] = float_to_half_bits((float)(h[i] - (double)half_bits_to_float(a.thi[i])));
         a.ca[i] = (float)ca[i];
         a.cb[i] = (float)cb[i];
     }
