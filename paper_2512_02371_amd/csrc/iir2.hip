@@ -134,23 +134,48 @@ __global__ void __launch_bounds__(256) iir2_state_mfma_kernel(IirArgs p) {
 constexpr int kIirScanWaves = 16;
 
 __device__ __forceinline__ State2 iir_scan_tiles(const IirArgs& p, const float* e, float* st, int lo, int hi, State2 s) {
-    // eight tiles at a time: their end states are requested together, then chained
+    // Eight tiles at a time: their end states are requested together, then chained.  Whole groups
+    // move as 16-byte pieces (two tiles each): with a lane stride of `chunk` tiles every piece of a
+    // load instruction lies in another cache line, so fewer, wider instructions matter.
     for (int t0 = lo; t0 < hi; t0 += 8) {
-        float ea[8], eb[8];
+        float ea[8], eb[8], sa[8], sb[8];
+        const bool whole = t0 + 8 <= hi;
+        if (whole) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            ea[k] = t0 + k < hi ? e[2 * (t0 + k)] : 0.f;
-            eb[k] = t0 + k < hi ? e[2 * (t0 + k) + 1] : 0.f;
+            for (int k = 0; k < 4; ++k) {
+                const floatx4 v = *reinterpret_cast<const floatx4_u*>(e + 2 * (t0 + 2 * k));
+                ea[2 * k] = v[0];
+                eb[2 * k] = v[1];
+                ea[2 * k + 1] = v[2];
+                eb[2 * k + 1] = v[3];
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                ea[k] = t0 + k < hi ? e[2 * (t0 + k)] : 0.f;
+                eb[k] = t0 + k < hi ? e[2 * (t0 + k) + 1] : 0.f;
+            }
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (t0 + k < hi) {
-                if (st) {
-                    st[2 * (t0 + k)] = s.a;
-                    st[2 * (t0 + k) + 1] = s.b;
-                }
-                s = iir_step(p.m512, s, ea[k], eb[k]);
+        for (int k = 0; k < 8; ++k) {
+            sa[k] = s.a;
+            sb[k] = s.b;
+            if (t0 + k < hi) s = iir_step(p.m512, s, ea[k], eb[k]);
+        }
+        if (st) {
+            if (whole) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    *reinterpret_cast<floatx4_u*>(st + 2 * (t0 + 2 * k)) = floatx4{sa[2 * k], sb[2 * k], sa[2 * k + 1], sb[2 * k + 1]};
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (t0 + k < hi) {
+                        st[2 * (t0 + k)] = sa[k];
+                        st[2 * (t0 + k) + 1] = sb[k];
+                    }
             }
+        }
     }
     return s;
 }

@@ -69,6 +69,16 @@ def test_iir2_impulse_response(fn):
     assert np.max(np.abs(got[0, t0:] - h)) < 2e-5
 
 
+def test_iir2_long_signal(orc):
+    """More than eight tiles per lane of the state scan (the path that moves tile states as 16-byte
+    pieces), an odd number of them, and a ragged last tile."""
+    C, T = 1, (1 << 23) + 777
+    sig = synth.uniform_pm1_f16(9650, (C, T))
+    for fn in ("hb_iir2", "hb_iir2_valu"):
+        got, _ = run(fn, sig, 1.2, -0.52)
+        assert_close(got, orc.iir2(sig, float(np.float32(1.2)), float(np.float32(-0.52))), f"{fn} 1 x {T}")
+
+
 def test_iir2_full_size(orc):
     """The paper's workload: 2^21 stereo samples."""
     C, T = 2, 1 << 21
