@@ -64,9 +64,12 @@ __device__ __forceinline__ void rz_store_rows_half(float* patch, half_t* dst, ui
 template <bool OUT_HALF>
 __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
     constexpr int NW = kRzTiles;
-    __shared__ __attribute__((aligned(16))) half8 s_frag[kRzMaxChunks * 64];
-    __shared__ __attribute__((aligned(16))) float s_patch[kRzWaves * RowPatch<NW>::kFloats];
-    __shared__ int s_geom[2];
+    // The coefficient block and, once the products are done, the waves' store patches share one piece
+    // of LDS: with both resident a compute unit held too few workgroups to cover the grid in one round.
+    constexpr int kFragBytes = kRzMaxChunks * 64 * 16, kPatchBytes = kRzWaves * RowPatch<NW>::kFloats * 4;
+    __shared__ __attribute__((aligned(16))) char s_mem[kFragBytes > kPatchBytes ? kFragBytes : kPatchBytes];
+    half8* s_frag = reinterpret_cast<half8*>(s_mem);
+    float* s_patch = reinterpret_cast<float*>(s_mem);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -78,40 +81,22 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
     const int run = wg % p.nruns, plane = wg / p.nruns;
     const int o0 = 16 * grp;
 
-    // geometry of the group: first sample (even) and number of 32-sample chunks, capped
-    if (tid == 0) {
-        int lo = 0x7fffffff, hi = -0x7fffffff;
-        for (int i = 0; i < 16 && o0 + i < p.nout; ++i) {
-            const int st = clampi(p.start[o0 + i], -(1 << 24), 1 << 24);
-            lo = min(lo, st);
-            hi = max(hi, st + p.band);
-        }
-        lo &= ~1;
-        s_geom[0] = lo;
-        s_geom[1] = min((hi - lo + 31) / 32, kRzMaxChunks);
-    }
-    __syncthreads();
-    const int first = s_geom[0], nk = s_geom[1];
-    // coefficient block, B-operand layout: lane (c = o, g) holds B[8g + i][o] = coef[o][first + 32 kk + 8g + i - start[o]]
-    for (int idx = tid; idx < nk * 64; idx += 64 * kRzWaves) {
-        const int l = idx & 63, kk = idx >> 6;
-        const int o = o0 + (l & 15);
-        half8 f;
+    // geometry of the group: first sample (even) and number of 32-sample chunks, capped.  Lane column c
+    // reads the start of output o0 + c; the minimum and maximum over the 16 columns come from four
+    // butterfly steps inside each row of 16 lanes, so every lane ends up with the same numbers.
+    const int o = o0 + c;
+    const bool live = o < p.nout;
+    const int st = live ? clampi(p.start[o], -(1 << 24), 1 << 24) : 0;
+    int lo = live ? st : 0x7fffffff, hi = live ? st + p.band : -0x7fffffff;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = (half_t)0;
-        if (o < p.nout) {
-            const int t0 = first + 32 * kk + 8 * (l >> 4) - clampi(p.start[o], -(1 << 24), 1 << 24);
-            const half_t* row = p.coef + (size_t)o * p.band;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (t0 + i >= 0 && t0 + i < p.band) f[i] = row[t0 + i];
-        }
-        s_frag[idx] = f;
+    for (int off = 1; off < 16; off <<= 1) {
+        lo = min(lo, __shfl_xor(lo, off, 64));
+        hi = max(hi, __shfl_xor(hi, off, 64));
     }
-    __syncthreads();
+    const int first = lo & ~1, nk = min((hi - first + 31) / 32, kRzMaxChunks);
 
     const int r0 = 64 * (kRzWaves * run + wv);            // this wave's strip of rows
-    if (r0 >= p.rows) return;
+    const bool active = r0 < p.rows;
     const half_t* xpl = p.x + (size_t)plane * p.x_plane;
     const uint32_t rowbytes = (uint32_t)p.x_pitch * 2u;
     uint32_t rowoff[NW];
@@ -133,25 +118,45 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
                 }
         }
     };
+    // the first window chunk is requested before the coefficient block is built
+    half8 bufa[NW], bufb[NW];
+    if (active) load_chunk(0, bufa);
+
+    // coefficient block, B-operand layout: lane (c = o, g) holds B[8g + i][o] = coef[o][first + 32 kk + 8g + i - start[o]];
+    // wave wv builds chunks wv, wv + 4, ...
+    for (int kk = wv; kk < nk; kk += kRzWaves) {
+        half8 f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (half_t)0;
+        if (live) {
+            const int t0 = first + 32 * kk + 8 * g - st;
+            const half_t* row = p.coef + (size_t)o * p.band;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (t0 + i >= 0 && t0 + i < p.band) f[i] = row[t0 + i];
+        }
+        s_frag[kk * 64 + lane] = f;
+    }
+    __syncthreads();
 
     floatx4 acc[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
     // two window buffers used alternately: the next chunk is in flight while this one is multiplied
-    half8 bufa[NW], bufb[NW];
     auto use_chunk = [&](int kk, const half8 (&d)[NW]) {
         const half8 f = s_frag[kk * 64 + lane];
 #pragma unroll
         for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(d[w], f, acc[w]);
     };
-    load_chunk(0, bufa);
-    for (int kk = 0; kk < nk; kk += 2) {
+    for (int kk = 0; active && kk < nk; kk += 2) {
         if (kk + 1 < nk) load_chunk(kk + 1, bufb);
         use_chunk(kk, bufa);
         if (kk + 1 >= nk) break;
         if (kk + 2 < nk) load_chunk(kk + 2, bufa);
         use_chunk(kk + 1, bufb);
     }
+    __syncthreads();                                      // every wave is done with the coefficient block
+    if (!active) return;
 
     // D[m = r][n = o]: lane (c = o, g) holds rows r0 + 16 w + 4 g .. + 3 = four consecutive elements of Z's row o
     float* patch = s_patch + wv * RowPatch<NW>::kFloats;
