@@ -167,55 +167,66 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
 }
 
 // ---------------------------------------------------------------------------
-// Vector-ALU kernel: a 16 x 64 output tile per workgroup; the tile and its halo are staged in LDS
-// with both indices clamped (the definition's border rule verbatim), every thread slides the kernel
-// over 4 consecutive outputs with fp32 FMAs.
-constexpr int kC2vW = 64;
+// Vector-ALU kernel: a 16 x 128 output tile per workgroup.  The tile and its halo are staged in LDS
+// as fp32 with both indices clamped (the definition's border rule verbatim).  A thread owns 8
+// consecutive outputs of one row: for every kernel row it reads the 8 + KWP - 1 pixels under them
+// once (16-byte LDS reads) and slides the taps over them in registers, 8 FMAs per tap read.
+// KWP = kernel width rounded up to 8, 16 or 32; the taps beyond kw are zeros.
+constexpr int kC2vW = 128;
 constexpr int kC2vRows = 16 + HB_MAX_TAPS_CONV2D - 1;                 // 47
-constexpr int kC2vPitch = kC2vW + HB_MAX_TAPS_CONV2D - 1 + 1;          // 96 halves
+constexpr int kC2vPitch = kC2vW + HB_MAX_TAPS_CONV2D;                  // 160 floats
 
+template <int KWP>
 __global__ void __launch_bounds__(256) conv2d_valu_kernel(Conv2dArgs p) {
-    __shared__ half_t s_px[kC2vRows * kC2vPitch];
-    __shared__ float s_k[HB_MAX_TAPS_CONV2D * HB_MAX_TAPS_CONV2D];
-    for (int i = threadIdx.x; i < p.kh * p.kw; i += 256) s_k[i] = (float)__builtin_bit_cast(half_t, p.taps[i]);
-
+    __shared__ __attribute__((aligned(16))) float s_px[kC2vRows * kC2vPitch];
+    __shared__ float s_k[HB_MAX_TAPS_CONV2D * KWP];
+    for (int i = threadIdx.x; i < p.kh * KWP; i += 256) {
+        const int ry = i / KWP, t = i - ry * KWP;
+        s_k[i] = t < p.kw ? (float)__builtin_bit_cast(half_t, p.taps[ry * p.kw + t]) : 0.f;
+    }
     const int nt = (p.W + kC2vW - 1) / kC2vW;
     const int rg = blockIdx.x / nt, tc = blockIdx.x - rg * nt;
-    const int x0 = kC2vW * tc;
-    const int xend = min(x0 + kC2vW, p.W);
-    const int y0 = 16 * rg;
-    const int nrows = 16 + p.kh - 1, ncols = kC2vW + p.kw - 1;   // ncols <= 95
-    {
-        const int cc = threadIdx.x & 127;
-        const int x = clampi(x0 + cc - p.ax, 0, p.W - 1);
-        if (cc < ncols)
-            for (int r = threadIdx.x >> 7; r < nrows; r += 2) {
-                const int y = clampi(y0 + r - p.ay, 0, p.H - 1);
-                s_px[r * kC2vPitch + cc] = p.in[(int64_t)y * p.in_pitch + x];
-            }
+    const int x0 = kC2vW * tc, y0 = 16 * rg;
+    const int nrows = 16 + p.kh - 1;
+    for (int idx = threadIdx.x; idx < nrows * kC2vPitch; idx += 256) {
+        const int r = idx / kC2vPitch, cc = idx - r * kC2vPitch;
+        float v = 0.f;                                    // columns only zero taps can reach stay zero
+        if (cc < kC2vW + p.kw - 1) {
+            const int y = clampi(y0 + r - p.ay, 0, p.H - 1), x = clampi(x0 + cc - p.ax, 0, p.W - 1);
+            v = (float)p.in[(int64_t)y * p.in_pitch + x];
+        }
+        s_px[idx] = v;
     }
     __syncthreads();
 
-    const int r = threadIdx.x >> 4, xl = 4 * (threadIdx.x & 15);
+    const int r = threadIdx.x >> 4, xl = 8 * (threadIdx.x & 15);
     const int y = y0 + r;
-    if (y >= p.H || x0 + xl >= xend) return;
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (y >= p.H || x0 + xl >= p.W) return;
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
     for (int ry = 0; ry < p.kh; ++ry) {
-        const half_t* src = &s_px[(r + ry) * kC2vPitch + xl];
-        const float* k = &s_k[ry * p.kw];
-        float v0 = (float)src[0], v1 = (float)src[1], v2 = (float)src[2];
-        for (int t = 0; t < p.kw; ++t) {
-            const float v3 = (float)src[t + 3], kv = k[t];
-            acc[0] = fmaf(kv, v0, acc[0]);
-            acc[1] = fmaf(kv, v1, acc[1]);
-            acc[2] = fmaf(kv, v2, acc[2]);
-            acc[3] = fmaf(kv, v3, acc[3]);
-            v0 = v1;
-            v1 = v2;
-            v2 = v3;
+        float w[KWP + 8];
+        const floatx4* src = reinterpret_cast<const floatx4*>(&s_px[(r + ry) * kC2vPitch + xl]);
+#pragma unroll
+        for (int i = 0; i < (KWP + 8) / 4; ++i) {
+            const floatx4 v = src[i];
+            w[4 * i] = v[0];
+            w[4 * i + 1] = v[1];
+            w[4 * i + 2] = v[2];
+            w[4 * i + 3] = v[3];
+        }
+        const float* k = &s_k[ry * KWP];
+#pragma unroll
+        for (int t = 0; t < KWP; ++t) {
+            const float kv = k[t];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = fmaf(kv, w[t + q], acc[q]);
         }
     }
-    store4_mask(p.out + (int64_t)y * p.out_pitch, x0 + xl, xend, acc);
+    float* row = p.out + (int64_t)y * p.out_pitch;
+    store4_mask(row, x0 + xl, p.W, floatx4{acc[0], acc[1], acc[2], acc[3]});
+    store4_mask(row, x0 + xl + 4, p.W, floatx4{acc[4], acc[5], acc[6], acc[7]});
 }
 
 static hb_status conv2d_prepare(Conv2dArgs& a, const hb_half* in, float* out, int H, int W,
@@ -248,7 +259,9 @@ static hb_status conv2d_prepare(Conv2dArgs& a, const hb_half* in, float* out, in
 static hb_status conv2d_launch_valu(const Conv2dArgs& a, hipStream_t st) {
     const int64_t blocks = (int64_t)a.ngroups * ceil_div(a.W, kC2vW);
     if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
-    if (blocks > 0) hipLaunchKernelGGL(conv2d_valu_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    if (a.kw <= 8) hipLaunchKernelGGL(conv2d_valu_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else if (a.kw <= 16) hipLaunchKernelGGL(conv2d_valu_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(conv2d_valu_kernel<32>, dim3((unsigned)blocks), dim3(256), 0, st, a);
     return launch_status();
 }
 

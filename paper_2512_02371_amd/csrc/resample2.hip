@@ -272,81 +272,128 @@ __global__ void __launch_bounds__(kC2Threads) up2_mfma_kernel(Rs2Args p) {
 }
 
 // ---------------------------------------------------------------------------
-// Vector-ALU kernels: a 16 x 64 output tile per workgroup; the input pixels the tile needs are staged
-// in LDS with both indices clamped (the definition's border rule verbatim); every thread computes 4
-// consecutive outputs of one row with fp32 FMAs.
+// Vector-ALU kernels.  The input pixels an output tile needs are staged in LDS as fp32 with both
+// indices clamped (the definition's border rule verbatim).  A thread owns 8 consecutive outputs of
+// one row: for every kernel row it reads the pixels under them once (16-byte LDS reads) and slides
+// the taps over them in registers, 8 FMAs per tap read.  KWP = kernel width rounded up to 8, 16 or
+// 32; the taps beyond kw are zeros, and so are the staged columns only they can reach.
 constexpr int kRsTaps = HB_MAX_TAPS_CONV2D;
 constexpr int kRsDownRows = 2 * 15 + kRsTaps;                          // 62
-constexpr int kRsDownPitch = 2 * 63 + kRsTaps + 2;                     // 160 halves
+constexpr int kRsDownPitch = 2 * 64 + kRsTaps;                         // 160 floats
 constexpr int kRsUpRows = 8 + kRsTaps / 2 - 1;                         // 23
-constexpr int kRsUpPitch = 32 + kRsTaps / 2 - 1 + 1;                   // 48 halves
+constexpr int kRsUpPitch = 64 + kRsTaps / 2;                           // 80 floats
 
-__global__ void __launch_bounds__(256) down2_valu_kernel(Rs2Args p) {
-    __shared__ half_t s_px[kRsDownRows * kRsDownPitch];
-    __shared__ float s_k[kRsTaps * kRsTaps];
-    for (int i = threadIdx.x; i < p.kh * p.kw; i += 256) s_k[i] = (float)__builtin_bit_cast(half_t, p.taps[i]);
+template <int KWP>
+__device__ __forceinline__ void rs2_stage_taps(const Rs2Args& p, float* s_k, int nthreads) {
+    for (int i = threadIdx.x; i < p.kh * KWP; i += nthreads) {
+        const int ry = i / KWP, t = i - ry * KWP;
+        s_k[i] = t < p.kw ? (float)__builtin_bit_cast(half_t, p.taps[ry * p.kw + t]) : 0.f;
+    }
+}
+
+// 16 x 64 outputs per workgroup of 128 threads
+template <int KWP>
+__global__ void __launch_bounds__(128) down2_valu_kernel(Rs2Args p) {
+    __shared__ __attribute__((aligned(16))) float s_px[kRsDownRows * kRsDownPitch];
+    __shared__ float s_k[kRsTaps * KWP];
+    rs2_stage_taps<KWP>(p, s_k, 128);
     const int nt = (p.Wo + 63) / 64;
     const int rg = blockIdx.x / nt, tc = blockIdx.x - rg * nt;
     const int x0 = 64 * tc, y0 = 16 * rg;
-    const int nrows = 30 + p.kh, ncols = 126 + p.kw;      // ncols <= 158
-    for (int cc = threadIdx.x; cc < ncols; cc += 256) {
-        const int x = clampi(2 * x0 + cc - p.ax, 0, p.W - 1);
-        for (int r = 0; r < nrows; ++r) {
-            const int y = clampi(2 * y0 + r - p.ay, 0, p.H - 1);
-            s_px[r * kRsDownPitch + cc] = p.in[(int64_t)y * p.in_pitch + x];
+    const int nrows = 30 + p.kh;
+    for (int idx = threadIdx.x; idx < nrows * kRsDownPitch; idx += 128) {
+        const int r = idx / kRsDownPitch, cc = idx - r * kRsDownPitch;
+        float v = 0.f;
+        if (cc < 126 + p.kw) {
+            const int y = clampi(2 * y0 + r - p.ay, 0, p.H - 1), x = clampi(2 * x0 + cc - p.ax, 0, p.W - 1);
+            v = (float)p.in[(int64_t)y * p.in_pitch + x];
         }
+        s_px[idx] = v;
     }
     __syncthreads();
-    const int r = threadIdx.x >> 4, xl = 4 * (threadIdx.x & 15);
+    const int r = threadIdx.x >> 3, xl = 8 * (threadIdx.x & 7);
     const int y = y0 + r;
     if (y >= p.Ho || x0 + xl >= p.Wo) return;
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
     for (int ry = 0; ry < p.kh; ++ry) {
-        const half_t* src = &s_px[(2 * r + ry) * kRsDownPitch + 2 * xl];
-        const float* k = &s_k[ry * p.kw];
-        for (int t = 0; t < p.kw; ++t) {
+        float w[KWP + 16];                                 // inputs 2 xl .. 2 xl + KWP + 15 of row 2 r + ry
+        const floatx4* src = reinterpret_cast<const floatx4*>(&s_px[(2 * r + ry) * kRsDownPitch + 2 * xl]);
+#pragma unroll
+        for (int i = 0; i < (KWP + 16) / 4; ++i) {
+            const floatx4 v = src[i];
+            w[4 * i] = v[0];
+            w[4 * i + 1] = v[1];
+            w[4 * i + 2] = v[2];
+            w[4 * i + 3] = v[3];
+        }
+        const float* k = &s_k[ry * KWP];
+#pragma unroll
+        for (int t = 0; t < KWP; ++t) {
             const float kv = k[t];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc[q] = fmaf(kv, (float)src[2 * q + t], acc[q]);
+            for (int q = 0; q < 8; ++q) acc[q] = fmaf(kv, w[2 * q + t], acc[q]);
         }
     }
-    store4_mask(p.out + (int64_t)y * p.out_pitch, x0 + xl, p.Wo, acc);
+    float* row = p.out + (int64_t)y * p.out_pitch;
+    store4_mask(row, x0 + xl, p.Wo, floatx4{acc[0], acc[1], acc[2], acc[3]});
+    store4_mask(row, x0 + xl + 4, p.Wo, floatx4{acc[4], acc[5], acc[6], acc[7]});
 }
 
+// 16 x 128 outputs per workgroup of 256 threads = 8 x 64 input positions plus halo
+template <int KWP>
 __global__ void __launch_bounds__(256) up2_valu_kernel(Rs2Args p) {
-    __shared__ half_t s_px[kRsUpRows * kRsUpPitch];
-    __shared__ float s_k[kRsTaps * kRsTaps];
-    for (int i = threadIdx.x; i < p.kh * p.kw; i += 256) s_k[i] = (float)__builtin_bit_cast(half_t, p.taps[i]);
-    const int nt = (p.Wo + 63) / 64;
+    constexpr int RXP = KWP / 2;
+    __shared__ __attribute__((aligned(16))) float s_px[kRsUpRows * kRsUpPitch];
+    __shared__ float s_k[kRsTaps * KWP];
+    rs2_stage_taps<KWP>(p, s_k, 256);
+    const int nt = (p.Wo + 127) / 128;
     const int rg = blockIdx.x / nt, tc = blockIdx.x - rg * nt;
-    const int x0 = 64 * tc, y0 = 16 * rg;     // output tile; input tile starts at (y0/2, x0/2)
-    const int nrows = 8 + p.kh / 2 - 1, ncols = 32 + p.kw / 2 - 1;     // ncols <= 47
-    for (int idx = threadIdx.x; idx < nrows * 64; idx += 256) {
-        const int r = idx >> 6, cc = idx & 63;
-        if (cc < ncols) {
+    const int x0 = 128 * tc, y0 = 16 * rg;    // output tile; input tile starts at (y0 / 2, x0 / 2)
+    const int nrows = 8 + p.kh / 2 - 1;
+    for (int idx = threadIdx.x; idx < nrows * kRsUpPitch; idx += 256) {
+        const int r = idx / kRsUpPitch, cc = idx - r * kRsUpPitch;
+        float v = 0.f;
+        if (cc < 64 + p.kw / 2 - 1) {
             const int y = clampi(y0 / 2 + r - p.ay, 0, p.H - 1), x = clampi(x0 / 2 + cc - p.ax, 0, p.W - 1);
-            s_px[r * kRsUpPitch + cc] = p.in[(int64_t)y * p.in_pitch + x];
+            v = (float)p.in[(int64_t)y * p.in_pitch + x];
         }
+        s_px[idx] = v;
     }
     __syncthreads();
-    const int r = threadIdx.x >> 4, xl = 4 * (threadIdx.x & 15);
+    const int r = threadIdx.x >> 4, xl = 8 * (threadIdx.x & 15);
     const int y = y0 + r;
     if (y >= p.Ho || x0 + xl >= p.Wo) return;
     const int dy = y & 1;
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
     for (int ry = 0; ry < p.kh / 2; ++ry) {
-        const half_t* src = &s_px[(r / 2 + ry) * kRsUpPitch + xl / 2];
-        const float* k = &s_k[(2 * ry + dy) * p.kw];
-        for (int rx = 0; rx < p.kw / 2; ++rx) {
-            const float a = (float)src[rx], b = (float)src[rx + 1];
+        float w[RXP + 4];                                  // inputs xl / 2 .. xl / 2 + RXP + 3 of row r / 2 + ry
+        const floatx4* src = reinterpret_cast<const floatx4*>(&s_px[(r / 2 + ry) * kRsUpPitch + xl / 2]);
+#pragma unroll
+        for (int i = 0; i < (RXP + 4) / 4; ++i) {
+            const floatx4 v = src[i];
+            w[4 * i] = v[0];
+            w[4 * i + 1] = v[1];
+            w[4 * i + 2] = v[2];
+            w[4 * i + 3] = v[3];
+        }
+        const float* k = &s_k[(2 * ry + dy) * KWP];
+#pragma unroll
+        for (int rx = 0; rx < RXP; ++rx) {
             const float k0 = k[2 * rx], k1 = k[2 * rx + 1];
-            acc[0] = fmaf(k0, a, acc[0]);
-            acc[1] = fmaf(k1, a, acc[1]);
-            acc[2] = fmaf(k0, b, acc[2]);
-            acc[3] = fmaf(k1, b, acc[3]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[2 * i] = fmaf(k0, w[i + rx], acc[2 * i]);
+                acc[2 * i + 1] = fmaf(k1, w[i + rx], acc[2 * i + 1]);
+            }
         }
     }
-    store4_mask(p.out + (int64_t)y * p.out_pitch, x0 + xl, p.Wo, acc);
+    float* row = p.out + (int64_t)y * p.out_pitch;
+    store4_mask(row, x0 + xl, p.Wo, floatx4{acc[0], acc[1], acc[2], acc[3]});
+    store4_mask(row, x0 + xl + 4, p.Wo, floatx4{acc[4], acc[5], acc[6], acc[7]});
 }
 
 // ---------------------------------------------------------------------------
@@ -416,10 +463,11 @@ static hb_status rs2_launch_mfma(K kernel, const Rs2Args& a, size_t table_bytes,
     return launch_status();
 }
 
-static hb_status rs2_launch_valu(void (*kernel)(Rs2Args), const Rs2Args& a, hipStream_t st) {
-    const int64_t blocks = (int64_t)ceil_div(a.Ho, 16) * ceil_div(a.Wo, 64);
+template <class K>
+static hb_status rs2_launch_valu(K kernel, const Rs2Args& a, int tile_w, int threads, hipStream_t st) {
+    const int64_t blocks = (int64_t)ceil_div(a.Ho, 16) * ceil_div(a.Wo, tile_w);
     if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(threads), 0, st, a);
     return launch_status();
 }
 
@@ -442,7 +490,10 @@ extern "C" hb_status hb_down2_valu(const hb_half* in, float* out, int H, int W, 
     Rs2Args a;
     hb_status s = rs2_prepare(a, false, in, out, H, W, in_pitch, out_pitch, taps_host, kh, kw, anchor_y, anchor_x);
     if (s != HB_OK) return s;
-    return rs2_launch_valu(down2_valu_kernel, a, reinterpret_cast<hipStream_t>(stream));
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (kw <= 8) return rs2_launch_valu(down2_valu_kernel<8>, a, 64, 128, st);
+    if (kw <= 16) return rs2_launch_valu(down2_valu_kernel<16>, a, 64, 128, st);
+    return rs2_launch_valu(down2_valu_kernel<32>, a, 64, 128, st);
 }
 
 extern "C" hb_status hb_up2(const hb_half* in, float* out, int H, int W, int64_t in_pitch, int64_t out_pitch,
@@ -462,5 +513,8 @@ extern "C" hb_status hb_up2_valu(const hb_half* in, float* out, int H, int W, in
     Rs2Args a;
     hb_status s = rs2_prepare(a, true, in, out, H, W, in_pitch, out_pitch, taps_host, kh, kw, anchor_y, anchor_x);
     if (s != HB_OK) return s;
-    return rs2_launch_valu(up2_valu_kernel, a, reinterpret_cast<hipStream_t>(stream));
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (kw <= 8) return rs2_launch_valu(up2_valu_kernel<8>, a, 128, 256, st);
+    if (kw <= 16) return rs2_launch_valu(up2_valu_kernel<16>, a, 128, 256, st);
+    return rs2_launch_valu(up2_valu_kernel<32>, a, 128, 256, st);
 }
