@@ -65,7 +65,7 @@ typedef void *hb_stream;      /* hipStream_t */
 #define HB_MAX_TAPS 64          /* per axis, hb_sepblur */
 #define HB_MAX_TAPS_FIR1D 256   /* hb_fir1d: the large-tap regime of Sec. V-A */
 #define HB_MAX_TAPS_CONV2D 32   /* per axis, hb_conv2d, hb_down2, hb_up2 */
-#define HB_RESIZE_MAX_SPAN 512   /* hb_resize: input samples one group of 16 outputs may span */
+#define HB_RESIZE_MAX_SPAN 512   /* hb_resize: largest band; input samples of a group handled per round */
 
 /* Human-readable name of a status code (static storage). */
 const char *hb_status_string(hb_status s);
@@ -174,10 +174,9 @@ hb_status hb_sepblur_valu(const hb_half *in, float *out, int H, int W,
  * `workspace`: device scratch of at least hb_resize_workspace_size(C, H, Wo) bytes,
  * 256-byte aligned; contents undefined on exit; concurrent calls need their own.
  * 1 <= band <= HB_RESIZE_MAX_SPAN.  Every read is clamped into the image whatever
- * the matrices hold; of an aligned group of 16 outputs only the first
- * HB_RESIZE_MAX_SPAN input samples from its smallest (even) start are used, so
- * matrices whose groups span more lose those coefficients (hb_lanczos3_matrix
- * never builds such a matrix when it succeeds for factors up to 24).
+ * the matrices hold, and any starts are computed correctly: an aligned group of 16
+ * outputs whose rows together span more than HB_RESIZE_MAX_SPAN input samples is
+ * processed in several rounds of that many samples (slower, same result).
  */
 size_t hb_resize_workspace_size(int C, int H, int Wo);
 hb_status hb_resize(const hb_half *in, float *out, void *workspace, size_t workspace_bytes,
@@ -212,7 +211,12 @@ hb_status hb_lanczos3_matrix(int n_in, int n_out, int32_t *start_host, hb_half *
  * matrix of the impulse response.  in: C x T fp16, out: C x T fp32 (row pitches in
  * elements, >= T).  |alpha|, |beta| <= 4; filters whose 32-sample impulse response
  * leaves the fp16 range, or whose tile-to-tile state maps overflow, are
- * HB_ERR_UNSUPPORTED (stable filters never are).  `workspace`: device scratch of at
+ * HB_ERR_UNSUPPORTED (stable filters never are).  All sums are fp32, and a rounding
+ * error made at one sample passes through the filter like an input: the absolute
+ * error is about 2^-24 * sum|h| * max|out| (h the impulse response).  That stays
+ * within 1e-3 * max(1, |out|) for inputs in [-1, 1] while sum|h| is up to a few
+ * hundred (a complex pole pair of radius 0.95, say); sharper resonances lose more.
+ * `workspace`: device scratch of at
  * least hb_iir2_workspace_size(C, T) bytes, 256-byte aligned; contents undefined on
  * exit; concurrent calls need their own.
  */

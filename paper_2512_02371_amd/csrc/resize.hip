@@ -81,19 +81,21 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
     const int run = wg % p.nruns, plane = wg / p.nruns;
     const int o0 = 16 * grp;
 
-    // geometry of the group: first sample (even) and number of 32-sample chunks, capped.  Lane column c
+    // geometry of the group: first sample (even) and number of 32-sample chunks.  Lane column c
     // reads the start of output o0 + c; the minimum and maximum over the 16 columns come from four
     // butterfly steps inside each row of 16 lanes, so every lane ends up with the same numbers.
+    // A start below -band (above len - 1) reads nothing but the first (last) sample, and so does
+    // -band (len - 1): clamping it there changes no result and bounds the span by the image.
     const int o = o0 + c;
     const bool live = o < p.nout;
-    const int st = live ? clampi(p.start[o], -(1 << 24), 1 << 24) : 0;
+    const int st = live ? clampi(p.start[o], -p.band, p.len - 1) : 0;
     int lo = live ? st : 0x7fffffff, hi = live ? st + p.band : -0x7fffffff;
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) {
         lo = min(lo, __shfl_xor(lo, off, 64));
         hi = max(hi, __shfl_xor(hi, off, 64));
     }
-    const int first = lo & ~1, nk = min((hi - first + 31) / 32, kRzMaxChunks);
+    const int first = lo & ~1, nk_all = (hi - first + 31) / 32;
 
     const int r0 = 64 * (kRzWaves * run + wv);            // this wave's strip of rows
     const bool active = r0 < p.rows;
@@ -118,42 +120,48 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
                 }
         }
     };
-    // the first window chunk is requested before the coefficient block is built
-    half8 bufa[NW], bufb[NW];
-    if (active) load_chunk(0, bufa);
-
-    // coefficient block, B-operand layout: lane (c = o, g) holds B[8g + i][o] = coef[o][first + 32 kk + 8g + i - start[o]];
-    // wave wv builds chunks wv, wv + 4, ...
-    for (int kk = wv; kk < nk; kk += kRzWaves) {
-        half8 f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = (half_t)0;
-        if (live) {
-            const int t0 = first + 32 * kk + 8 * g - st;
-            const half_t* row = p.coef + (size_t)o * p.band;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (t0 + i >= 0 && t0 + i < p.band) f[i] = row[t0 + i];
-        }
-        s_frag[kk * 64 + lane] = f;
-    }
-    __syncthreads();
-
     floatx4 acc[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
-    // two window buffers used alternately: the next chunk is in flight while this one is multiplied
-    auto use_chunk = [&](int kk, const half8 (&d)[NW]) {
-        const half8 f = s_frag[kk * 64 + lane];
+    half8 bufa[NW], bufb[NW];
+    // The coefficient block holds kRzMaxChunks chunks; a group that spans more (a very large factor,
+    // or starts that jump inside the group) takes several rounds of block + products.
+    for (int base = 0; base < nk_all; base += kRzMaxChunks) {
+        const int nk = min(nk_all - base, kRzMaxChunks);
+        if (base) __syncthreads();                        // every wave is done with the previous block
+        // the first window chunk is requested before the coefficient block is built
+        if (active) load_chunk(base, bufa);
+
+        // coefficient block, B-operand layout: lane (c = o, g) holds B[8g + i][o] = coef[o][first + 32 kk + 8g + i - start[o]];
+        // wave wv builds chunks wv, wv + 4, ...
+        for (int kk = wv; kk < nk; kk += kRzWaves) {
+            half8 f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(d[w], f, acc[w]);
-    };
-    for (int kk = 0; active && kk < nk; kk += 2) {
-        if (kk + 1 < nk) load_chunk(kk + 1, bufb);
-        use_chunk(kk, bufa);
-        if (kk + 1 >= nk) break;
-        if (kk + 2 < nk) load_chunk(kk + 2, bufa);
-        use_chunk(kk + 1, bufb);
+            for (int i = 0; i < 8; ++i) f[i] = (half_t)0;
+            if (live) {
+                const int t0 = first + 32 * (base + kk) + 8 * g - st;
+                const half_t* row = p.coef + (size_t)o * p.band;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (t0 + i >= 0 && t0 + i < p.band) f[i] = row[t0 + i];
+            }
+            s_frag[kk * 64 + lane] = f;
+        }
+        __syncthreads();
+
+        // two window buffers used alternately: the next chunk is in flight while this one is multiplied
+        auto use_chunk = [&](int kk, const half8 (&d)[NW]) {
+            const half8 f = s_frag[kk * 64 + lane];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc[w] = mfma16x16x32(d[w], f, acc[w]);
+        };
+        for (int kk = 0; active && kk < nk; kk += 2) {
+            if (kk + 1 < nk) load_chunk(base + kk + 1, bufb);
+            use_chunk(kk, bufa);
+            if (kk + 1 >= nk) break;
+            if (kk + 2 < nk) load_chunk(base + kk + 2, bufa);
+            use_chunk(kk + 1, bufb);
+        }
     }
     __syncthreads();                                      // every wave is done with the coefficient block
     if (!active) return;
@@ -198,7 +206,7 @@ __global__ void __launch_bounds__(256) band_valu_kernel(BandArgs p) {
     const int o = (int)(rem / p.rows), r = (int)(rem - (int64_t)o * p.rows);
     const half_t* row = p.x + (size_t)plane * p.x_plane + (size_t)r * p.x_pitch;
     const half_t* k = p.coef + (size_t)o * p.band;
-    const int st = clampi(p.start[o], -(1 << 24), 1 << 24);
+    const int st = clampi(p.start[o], -p.band, p.len - 1);   // same samples as the unclamped start
     float acc = 0.f;
     for (int j = 0; j < p.band; ++j) acc = fmaf((float)k[j], (float)row[clampi(st + j, 0, p.len - 1)], acc);
     if (OUT_HALF) (reinterpret_cast<half_t*>(p.z) + (size_t)plane * p.z_plane)[(size_t)o * p.z_pitch + r] = (half_t)acc;

@@ -44,6 +44,8 @@ def lanczos(hb, n_in, n_out):
     (2, 130, 190, 130, 190),      # same size: the identity matrix with its 7-sample band
     (1, 97, 131, 45, 100),        # ragged everything
     (3, 64, 64, 1, 1),            # one output sample
+    (2, 254, 175, 3, 154),        # factor 85: band 509, the three rows together span 679 samples (two rounds)
+    (1, 40, 1300, 30, 16),        # factor 81 along x: one group of 16 outputs spans the whole row (three rounds)
     (1, 1, 1, 1, 1),
 ])
 def test_resize_lanczos_matches_oracle(orc, fn, C, H, W, Ho, Wo):
@@ -73,6 +75,23 @@ def test_resize_random_bands_and_irregular_starts(orc, fn):
     got, _ = run(fn, img, sy, cy, sx, cx)
     for c in range(C):
         assert_close(got[c], orc.band_resize(img[c], sy, cy, sx, cx), f"{fn} plane {c}")
+
+
+@pytest.mark.parametrize("fn", ["hb_resize", "hb_resize_valu"])
+def test_resize_starts_far_apart_and_far_outside(orc, fn):
+    """Starts of one group scattered over a long row (several rounds of the coefficient block) and
+    starts far outside the image on both sides (every sample clamps to the first / last pixel)."""
+    C, H, W, Ho, Wo, by, bx = 1, 70, 3000, 20, 40, 5, 33
+    img = synth.uniform01_f16(9400, (C, H, W))
+    cy = (synth.random_kernel2d_f16(9401, Ho, by).view(np.float16).astype(np.float64) * Ho).astype(np.float16).view(np.uint16)
+    cx = (synth.random_kernel2d_f16(9402, Wo, bx).view(np.float16).astype(np.float64) * Wo).astype(np.float16).view(np.uint16)
+    h = synth.hash_u64(9403, 0, Ho + Wo)
+    sy = ((h[:Ho] % np.uint64(H + 20)).astype(np.int64) - 10).astype(np.int32)
+    sx = ((h[Ho:] % np.uint64(W + 100)).astype(np.int64) - 50).astype(np.int32)
+    sx[0], sx[1], sx[17], sx[18] = -(1 << 30), 1 << 30, -5000, 7000
+    sy[0], sy[1] = -(2 ** 31), 2 ** 31 - 1
+    got, _ = run(fn, img, sy, cy, sx, cx)
+    assert_close(got[0], orc.band_resize(img[0], sy, cy, sx, cx), fn)
 
 
 @pytest.mark.parametrize("fn", ["hb_resize", "hb_resize_valu"])
