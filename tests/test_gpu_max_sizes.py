@@ -170,3 +170,29 @@ def test_kernel2d_stages_at_the_size_limits(orc, kind, v):
         else:
             got, r = out[2 * (lo + a):2 * (lo + b)], ref[2 * a:2 * b]
         assert_close(got.cpu().numpy(), r, f"{fn} input rows {lo + a}..{lo + b}")
+
+
+@pytest.mark.parametrize("fn", ["hb_resize", "hb_resize_valu"])
+def test_resize_at_the_size_limits(orc, fn):
+    """A plane of 65535 x 32768 (H * in_pitch = 2^31 - 32768) to 29999 x 30001: the transposed fp16
+    intermediate is 30001 rows of 65536 (just below 2^31 elements), the output 0.9 * 2^30 floats."""
+    import torch
+    from paper_2512_02371_amd import hb
+    H, W, Ho, Wo = 65535, 32768, 29999, 30001
+    img = tiled_image(3010, H, W, W, block_rows=1024)
+    sy, cy = hb.hb_lanczos3_matrix(H, Ho)
+    sx, cx = hb.hb_lanczos3_matrix(W, Wo)
+    out = torch.empty((1, Ho, Wo), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(hb.hb_resize_workspace_size(1, H, Wo), dtype=torch.uint8, device="cuda:0")
+    di = lambda a: torch.from_numpy(a).to("cuda:0")
+    dh = lambda a: torch.from_numpy(a.view(np.int16)).to("cuda:0").view(torch.float16)
+    print(f"{fn} {H}x{W} -> {Ho}x{Wo}", flush=True)
+    getattr(hb, fn)(img[None], out, ws, di(sy), dh(cy), di(sx), dh(cx))
+    torch.cuda.synchronize()
+    band = cy.shape[1]
+    for o0 in (0, Ho // 2 - 5, Ho - 16):
+        rows = slice(o0, o0 + 16)
+        lo, hi = max(int(sy[rows].min()), 0), min(int(sy[rows].max()) + band, H)
+        # the crop ends where the image ends or beyond the rows these outputs read: clamping agrees
+        ref = orc.band_resize(bits(img[lo:hi]), sy[rows] - lo, cy[rows], sx, cx)
+        assert_close(out[0, rows].cpu().numpy(), ref, f"{fn} output rows {o0}..{o0 + 16}")
