@@ -17,22 +17,41 @@
 // with A[m][k] = taps[k - m - e] (zero outside the taps): A_K itself, built once per
 // wave from a zero-padded tap table.  In D' a lane owns four consecutive output
 // columns of one row, so the result leaves with one 16-byte store per lane.
+#include <utility>
+
 #include "hb_device.hpp"
 #include "hb_host.hpp"
 
 #ifndef HB_FIR_TILES
-#define HB_FIR_TILES 4        // 16-column tiles per wave strip (fewer for long filters, see fir_tiles)
+#define HB_FIR_TILES 4        // 16-column tiles per wave strip
 #endif
 #ifndef HB_FIR_WAVES
 #define HB_FIR_WAVES (1 << 20) // wave tasks per launch before a task takes more than one 16-row step;
                               // rows are independent here, so short-lived waves stream best
 #endif
 
-#ifndef HB_FIR_LONG_WAVES
-#define HB_FIR_LONG_WAVES 4096 // the same for filters of more than 80 taps (four or more windows per tile)
+#ifndef HB_FIR_WALK_WAVES
+#define HB_FIR_WALK_WAVES 4096 // the walk of long filters: aim for about this many wave tasks per launch ...
+#endif
+#ifndef HB_FIR_WALK_MIN_NK
+#define HB_FIR_WALK_MIN_NK 2    // windows per tile from which the walk is used
+#endif
+#ifndef HB_FIR_WALK_MIN_TURNS
+#define HB_FIR_WALK_MIN_TURNS 2 // ... but no run shorter than this many turns of the accumulator ring (2 NK tiles each)
 #endif
 
 namespace hb {
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop that is unrolled by construction,
+// so that register arrays indexed by the step stay in registers.
+template <class F, int... I>
+__device__ __forceinline__ void unrolled_steps_impl(F& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void unrolled_steps(F& f) {
+    unrolled_steps_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 struct FirArgs {
     const half_t* in;
@@ -43,12 +62,14 @@ struct FirArgs {
     int nct;             // strips per row group
     int steps;           // 16-row steps per task
     int ntasks;          // strips x row segments
+    int ntiles, run_tiles, nruns, wtasks;   // the walk of long filters: tiles per row, per run, runs per row group, tasks
     TapsT<HB_MAX_TAPS_FIR1D> taps;
     FoldTablesT<HB_MAX_TAPS_FIR1D> fold;
 };
 
-// Tiles per wave strip: a strip keeps 2 x tiles x NK window fragments in registers.
-constexpr int fir_tiles(int nk) { return nk <= 3 ? HB_FIR_TILES : nk <= 6 ? 2 : 1; }
+// Tiles per wave strip of the one-window kernel (it is written for any NK, but filters with two or
+// more windows per tile take the walk further down).
+constexpr int fir_tiles(int) { return HB_FIR_TILES; }
 
 __device__ __forceinline__ half_t tap_from_bits(uint16_t b) {
     return __builtin_bit_cast(half_t, b);
@@ -154,52 +175,163 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     }
 }
 
-// Vector-ALU twin: a 16 x 256 tile is staged in LDS with its halo, every thread
-// slides the taps over 4 x 4 outputs with fp32 FMAs.
-constexpr int kValuTileW = 256;
-constexpr int kValuMaxChunks = (kValuTileW + HB_MAX_TAPS_FIR1D + HB_MAX_TAPS_FIR1D) / 8;   // tile + left slack + right halo
-constexpr int kValuPitch = kValuMaxChunks * 8 + 8;
+// ---------------------------------------------------------------------------
+// Long filters (three or more windows per tile): the walk along the row.
+//
+// In the kernel above every product loads its own window, NK loads of 16 rows x 64 bytes per
+// 16 x 16 outputs, and with long filters those loads are all the kernel does (256 taps: 9 KB requested
+// per 1 KB of outputs; the matrix units idle).  But window u (the 32 pixels from 16 u - aw on) is the
+// kk-th window of tile u - 2 kk for every kk < NK: here a wave walks along a run of tiles of one
+// 16-row group, loads each window ONCE and multiplies it with all NK fragments, each product going
+// to the accumulator of its own tile.  2 NK - 1 tiles are open at any time (a ring of 2 NK
+// accumulators, indexed at compile time: the walk is unrolled over one turn of the ring); a tile is
+// complete 2 NK - 2 steps after its first window, and completed tiles leave in pairs through the LDS
+// patch as 128-byte runs.  A pixel is requested twice (windows of 32 at a stride of 16) instead of
+// 2 NK times.  Windows that reach over the row ends are loaded pixel by pixel with the column
+// clamped: the Toeplitz matrix is indexed by window position, so the border rule needs nothing else.
+// Runs start 2 NK - 2 windows early (products into accumulators of tiles left of the run are
+// computed and dropped), the price of cutting a row into several tasks.
+template <int NK, bool STREAM>
+__global__ void __launch_bounds__(256) fir1d_walk_kernel(FirArgs p) {
+    constexpr int R = 2 * NK;
+    __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2>::kFloats];
+    const int lane = threadIdx.x & 63;
+    const int c = lane & 15, g = lane >> 4;
+    const int e = p.anchor & 1;
+    const int aw = p.anchor + e;
+    half8 coef[NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(p.taps.tab, 32 * kk + 8 * g - c - e);
+
+    const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int task = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
+    if (task >= p.wtasks) return;
+    const int rg = task / p.nruns, run = task - rg * p.nruns;
+    const int t0 = run * p.run_tiles;                     // first tile of the run
+    const int L = min(p.run_tiles, p.ntiles - t0);        // its tiles
+    const int nsteps = L + 2 * (NK - 1);                  // windows t0 .. t0 + nsteps - 1
+    const int y0 = 16 * rg;
+    const uint32_t rowoff = (uint32_t)min(y0 + c, p.H - 1) * (uint32_t)p.in_pitch * 2u;
+    float* patch = s_patch[threadIdx.x >> 6];
+    const bool rows16 = y0 + 16 <= p.H;
+
+    auto load_window = [&](int u) {
+        const int xs = 16 * (t0 + u) - aw;                // uniform
+        half8 v;
+        if (xs >= 0 && xs + 32 <= p.W) {
+            v = ldg8(p.in, rowoff + 2u * (uint32_t)(xs + 8 * g));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int x = clampi(xs + 8 * g + i, 0, p.W - 1);
+                v[i] = *reinterpret_cast<const half_t*>(reinterpret_cast<const char*>(p.in) + (rowoff + 2u * (uint32_t)x));
+            }
+        }
+        return v;
+    };
+    floatx4 done[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+    // the pair of tiles tb, tb + 1 (tb even, relative to the run), completed in the two steps before
+    auto store_pair = [&](int tb) {
+        if (tb < 0 || tb >= L) return;
+        const int x = 16 * (t0 + tb);
+        if (rows16 && x + 32 <= p.W) {
+            store_rows_via_lds<2, STREAM>(patch, p.out + (int64_t)y0 * p.out_pitch + x, (uint32_t)p.out_pitch, done, lane);
+        } else if (y0 + c < p.H) {
+            float* row = p.out + (int64_t)(y0 + c) * p.out_pitch;
+            store4_mask(row, x + 4 * g, p.W, done[0]);
+            if (tb + 1 < L) store4_mask(row, x + 16 + 4 * g, p.W, done[1]);
+        }
+    };
+
+    floatx4 acc[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // NK windows in flight: the longer the filter, the more products a window feeds and the further
+    // ahead the loads have to run to cover their latency
+    half8 win[NK];
+#pragma unroll
+    for (int i = 0; i < NK; ++i) win[i] = load_window(i < nsteps ? i : 0);
+    int ub = 0;
+    // one step: window ub + S against every fragment; the tile whose last window this was leaves its slot
+    auto step = [&](auto sc) {
+        constexpr int S = decltype(sc)::value;
+        const int u = ub + S;
+        if (S % 2 == 0) store_pair(u - R);                // before the loads: loads and stores share one counter
+        if (u < nsteps) {
+            auto product = [&](auto kc) {
+                constexpr int KK = decltype(kc)::value, slot = ((S - 2 * KK) % R + R) % R;
+                acc[slot] = mfma16x16x32(coef[KK], win[S % NK], acc[slot]);
+            };
+            unrolled_steps<NK>(product);
+            constexpr int last = (S + 2) % R;             // slot of tile u - 2 (NK - 1)
+            done[S & 1] = acc[last];
+            acc[last] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (u + NK < nsteps) win[S % NK] = load_window(u + NK);
+        }
+    };
+#pragma unroll 1
+    for (ub = 0; ub < nsteps; ub += R) unrolled_steps<R>(step);
+    store_pair(ub - R);
+}
+
+// Vector-ALU twin: a 16 x 128 tile is staged in LDS as fp32 with its halo, the column index clamped
+// (the definition's border rule verbatim).  A thread owns 8 consecutive outputs of one row and slides
+// the taps over them eight at a time: 8 taps and 8 new pixels are read (16-byte LDS reads), 64 FMAs use
+// them.  Taps are padded with zeros to a multiple of 8.
+constexpr int kValuTileW = 128;
+constexpr int kValuPitch = kValuTileW + HB_MAX_TAPS_FIR1D + 8;   // floats per staged row
 
 __global__ void __launch_bounds__(256) fir1d_valu_kernel(FirArgs p) {
-    __shared__ half_t s_px[16 * kValuPitch];
-    __shared__ float s_k[HB_MAX_TAPS_FIR1D];
+    __shared__ __attribute__((aligned(16))) float s_px[16 * kValuPitch];
+    __shared__ __attribute__((aligned(16))) float s_k[HB_MAX_TAPS_FIR1D];
     static_assert(HB_MAX_TAPS_FIR1D <= 256, "one tap per thread");
-    if (threadIdx.x < HB_MAX_TAPS_FIR1D) s_k[threadIdx.x] = (float)tap_at(p.taps.tab, threadIdx.x);
+    const int tp = (p.T + 7) & ~7;
+    if ((int)threadIdx.x < tp) s_k[threadIdx.x] = (int)threadIdx.x < p.T ? (float)tap_at(p.taps.tab, threadIdx.x) : 0.f;
 
     const int nctv = (p.W + kValuTileW - 1) / kValuTileW;
     const int rg = blockIdx.x / nctv, ct = blockIdx.x - rg * nctv;
     const int x0 = ct * kValuTileW;
-    const int lead = 8 * ((p.anchor + 7) / 8);                 // aligned slack left of the tile
-    const int nch = (kValuTileW + lead + (p.T - 1 - p.anchor) + 7) / 8;
+    // staged column j holds pixel clampW(x0 - anchor + j); j < 128 + tp covers every window
+    const int nch = (kValuTileW + tp) / 8;
     for (int idx = threadIdx.x; idx < 16 * nch; idx += 256) {
         const int r = idx / nch, ch = idx - r * nch;
         const half_t* row = p.in + (int64_t)min(16 * rg + r, p.H - 1) * p.in_pitch;
-        half8 v = load8_clamp(row, x0 - lead + 8 * ch, p.W);
-        *reinterpret_cast<half8*>(&s_px[r * kValuPitch + 8 * ch]) = v;
+        const half8 v = load8_clamp(row, x0 - p.anchor + 8 * ch, p.W);
+        floatx4* dst = reinterpret_cast<floatx4*>(&s_px[r * kValuPitch + 8 * ch]);
+        dst[0] = floatx4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+        dst[1] = floatx4{(float)v[4], (float)v[5], (float)v[6], (float)v[7]};
     }
     __syncthreads();
 
-    const int r = threadIdx.x >> 4, cg = threadIdx.x & 15;
+    const int r = threadIdx.x >> 4, xl = 8 * (threadIdx.x & 15);
     const int y = 16 * rg + r;
-    if (y >= p.H) return;
-    float* orow = p.out + (int64_t)y * p.out_pitch;
-    const int off = lead - p.anchor;
+    if (y >= p.H || x0 + xl >= p.W) return;
+    const floatx4* src = reinterpret_cast<const floatx4*>(&s_px[r * kValuPitch + xl]);
+    float acc[8], w[16];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int xl = 4 * cg + 64 * j;
-        if (x0 + xl >= p.W) continue;
-        const half_t* src = &s_px[r * kValuPitch + xl + off];
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int u = 0; u < p.T + 3; ++u) {
-            const float v = (float)src[u];
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    {
+        const floatx4 a = src[0], b = src[1];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int t = u - q;
-                if (t >= 0 && t < p.T) acc[q] = fmaf(s_k[t], v, acc[q]);
-            }
-        }
-        store4_mask(orow, x0 + xl, p.W, acc);
+        for (int i = 0; i < 4; ++i) w[i] = a[i], w[4 + i] = b[i];
     }
+    for (int tb = 0; tb < tp; tb += 8) {
+        const floatx4 a = src[tb / 4 + 2], b = src[tb / 4 + 3];      // pixels xl + tb + 8 .. + 15
+        const floatx4 ka = *reinterpret_cast<const floatx4*>(&s_k[tb]), kb = *reinterpret_cast<const floatx4*>(&s_k[tb + 4]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[8 + i] = a[i], w[12 + i] = b[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float kv = i < 4 ? ka[i] : kb[i - 4];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = fmaf(kv, w[q + i], acc[q]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = w[8 + i];
+    }
+    float* orow = p.out + (int64_t)y * p.out_pitch;
+    store4_mask(orow, x0 + xl, p.W, floatx4{acc[0], acc[1], acc[2], acc[3]});
+    store4_mask(orow, x0 + xl + 4, p.W, floatx4{acc[4], acc[5], acc[6], acc[7]});
 }
 
 static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H, int W,
@@ -222,12 +354,21 @@ static hb_status fir1d_prepare(FirArgs& a, const hb_half* in, float* out, int H,
     const int nk = ceil_div(15 + ntaps + (anchor & 1), 32);
     a.nct = ceil_div(W, 16 * fir_tiles(nk));
     const int rowsteps = ceil_div(H, 16);
-    // long filters are bound by the latency of one step, not by bandwidth: their waves take several
-    // steps each, with the next step's windows in flight during the products
-    const int64_t waves = nk <= 3 ? (int64_t)HB_FIR_WAVES : HB_FIR_LONG_WAVES;
+    const int64_t waves = HB_FIR_WAVES;
     int steps = (int)(((int64_t)rowsteps * a.nct + waves - 1) / waves);
     a.steps = steps < 1 ? 1 : steps;
     a.ntasks = ceil_div(rowsteps, a.steps) * a.nct;
+    // the walk of long filters: runs of an even number of tiles, at least a few turns of the ring long
+    a.ntiles = ceil_div(W, 16);
+    const int want_runs = ceil_div(HB_FIR_WALK_WAVES, rowsteps);
+    int max_runs = a.ntiles / (HB_FIR_WALK_MIN_TURNS * 2 * nk);
+    if (max_runs < 1) max_runs = 1;
+    const int runs = want_runs < max_runs ? want_runs : max_runs;
+    a.run_tiles = (ceil_div(a.ntiles, runs) + 1) & ~1;
+    a.nruns = ceil_div(a.ntiles, a.run_tiles);
+    const int64_t wtasks = (int64_t)rowsteps * a.nruns;
+    if (wtasks > 0x7fffffff / 4) return HB_ERR_UNSUPPORTED;
+    a.wtasks = (int)wtasks;
     a.taps = pack_taps<HB_MAX_TAPS_FIR1D>(taps_host, ntaps);
     a.fold = pack_fold_tables<HB_MAX_TAPS_FIR1D>(taps_host, ntaps);
     return HB_OK;
@@ -251,21 +392,27 @@ extern "C" hb_status hb_fir1d(const hb_half* in, float* out, int H, int W,
     const int nk = ceil_div(15 + ntaps + (anchor & 1), 32);
     if (W < 32 * nk)   // narrower than one window of the matrix formulation: vector-ALU kernel
         return hb_fir1d_valu(in, out, H, W, in_pitch, out_pitch, taps_host, ntaps, anchor, stream);
-    const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
-    const dim3 grid(blocks), block(256);
-#define HB_FIR_LAUNCH(N)                                                                          \
+    if (nk >= HB_FIR_WALK_MIN_NK) {   // long filters: the walk along the row, every window loaded once
+        const dim3 wgrid(ceil_div(a.wtasks, 4)), wblock(256);
+#define HB_FIR_WALK(N)                                                                            \
     case N:                                                                                       \
-        if (ss) hipLaunchKernelGGL((fir1d_mfma_kernel<N, true>), grid, block, 0, st, a);          \
-        else hipLaunchKernelGGL((fir1d_mfma_kernel<N, false>), grid, block, 0, st, a);            \
+        if (ss) hipLaunchKernelGGL((fir1d_walk_kernel<N, true>), wgrid, wblock, 0, st, a);        \
+        else hipLaunchKernelGGL((fir1d_walk_kernel<N, false>), wgrid, wblock, 0, st, a);          \
         break;
-    switch (nk) {
-        HB_FIR_LAUNCH(1) HB_FIR_LAUNCH(2) HB_FIR_LAUNCH(3) HB_FIR_LAUNCH(4) HB_FIR_LAUNCH(5)
-        HB_FIR_LAUNCH(6) HB_FIR_LAUNCH(7) HB_FIR_LAUNCH(8) HB_FIR_LAUNCH(9)
-        default: return HB_ERR_UNSUPPORTED;
+        switch (nk) {
+            HB_FIR_WALK(2) HB_FIR_WALK(3) HB_FIR_WALK(4) HB_FIR_WALK(5) HB_FIR_WALK(6) HB_FIR_WALK(7) HB_FIR_WALK(8) HB_FIR_WALK(9)
+            default: return HB_ERR_UNSUPPORTED;
+        }
+#undef HB_FIR_WALK
+        return launch_status();
     }
-#undef HB_FIR_LAUNCH
+    // one window per tile: nothing to share between tiles, every wave takes one strip of tiles
+    const int blocks = min(ceil_div(a.ntasks, 4), kMaxStreamBlocks);
+    const dim3 grid(blocks), block(256);
+    if (ss) hipLaunchKernelGGL((fir1d_mfma_kernel<1, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fir1d_mfma_kernel<1, false>), grid, block, 0, st, a);
     return launch_status();
 }
 
