@@ -208,63 +208,94 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
 }
 
 // ---------------------------------------------------------------------------
-// Vector-ALU twin: 32 x 64 output tile per workgroup; pixels with halo in LDS,
-// row pass to an fp16 LDS intermediate, column pass from it.
+// Vector-ALU twin: 32 x 64 output tile per workgroup; pixels with halo in LDS (column and row indices
+// clamped, the definition's border rule verbatim), row pass to an LDS intermediate (rounded to fp16 like
+// the matrix kernel's, kept as fp32), column pass from it.  Both passes are register-blocked: a thread
+// owns 8 consecutive outputs of a row (of a column) and reads 8 taps and 8 new samples per 64 FMAs.
+// Taps are padded with zeros to a multiple of 8.
 constexpr int kVTH = 32, kVTW = 64;
-constexpr int kVRows = kVTH + HB_MAX_TAPS - 1;          // 95
-constexpr int kVPxPitch = kVTW + 64 + 64 + 8;           // 200
-constexpr int kVTmpPitch = kVTW + 4;                    // 68
+constexpr int kVRows = kVTH + HB_MAX_TAPS;              // 96: rows the column pass may touch
+constexpr int kVPxPitch = kVTW + HB_MAX_TAPS + 8;       // 136 halves
 
 __global__ void __launch_bounds__(256) sepblur_valu_kernel(SepArgs p) {
-    __shared__ half_t s_px[kVRows * kVPxPitch];
-    __shared__ half_t s_tmp[kVRows * kVTmpPitch];
-    __shared__ float s_kx[HB_MAX_TAPS], s_ky[HB_MAX_TAPS];
+    __shared__ __attribute__((aligned(16))) half_t s_px[kVRows * kVPxPitch];
+    __shared__ __attribute__((aligned(16))) float s_tmp[kVRows * kVTW];
+    __shared__ __attribute__((aligned(16))) float s_kx[HB_MAX_TAPS], s_ky[HB_MAX_TAPS];
+    static_assert(HB_MAX_TAPS % 8 == 0, "taps are processed eight at a time");
     if (threadIdx.x < HB_MAX_TAPS) {
-        s_kx[threadIdx.x] = (float)tap_at(p.tx.tab, threadIdx.x);
-        s_ky[threadIdx.x] = (float)tap_at(p.ty.tab, threadIdx.x);
+        s_kx[threadIdx.x] = (int)threadIdx.x < p.Tx ? (float)tap_at(p.tx.tab, threadIdx.x) : 0.f;
+        s_ky[threadIdx.x] = (int)threadIdx.x < p.Ty ? (float)tap_at(p.ty.tab, threadIdx.x) : 0.f;
     }
     const int nctv = (p.W + kVTW - 1) / kVTW;
     const int rt = blockIdx.x / nctv, ct = blockIdx.x - rt * nctv;
     const int x0 = ct * kVTW, y0 = rt * kVTH;
-    const int lead = 8 * ((p.ax + 7) / 8);
-    const int nch = (kVTW + lead + (p.Tx - 1 - p.ax) + 7) / 8;
-    const int nrows = kVTH + p.Ty - 1;
+    const int txp = (p.Tx + 7) & ~7, typ = (p.Ty + 7) & ~7;
+    const int nrows = kVTH + p.Ty - 1;                     // image rows under the tile
+    // staged pixel (r, j) = in[clampH(y0 - ay + r)][clampW(x0 - ax + j)], j < 64 + txp covers every window
+    const int nch = (kVTW + txp) / 8;
     for (int idx = threadIdx.x; idx < nrows * nch; idx += 256) {
         const int r = idx / nch, ch = idx - r * nch;
         const half_t* row = p.in + (int64_t)clampi(y0 - p.ay + r, 0, p.H - 1) * p.in_pitch;
-        *reinterpret_cast<half8*>(&s_px[r * kVPxPitch + 8 * ch]) =
-            load8_clamp(row, x0 - lead + 8 * ch, p.W);
+        *reinterpret_cast<half8*>(&s_px[r * kVPxPitch + 8 * ch]) = load8_clamp(row, x0 - p.ax + 8 * ch, p.W);
     }
     __syncthreads();
-    const int off = lead - p.ax;
-    for (int idx = threadIdx.x; idx < nrows * (kVTW / 4); idx += 256) {
-        const int r = idx / (kVTW / 4), cg = idx - r * (kVTW / 4);
-        const half_t* src = &s_px[r * kVPxPitch + 4 * cg + off];
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int u = 0; u < p.Tx + 3; ++u) {
-            const float v = (float)src[u];
+    // row pass: thread = 8 consecutive columns of one staged row
+    for (int idx = threadIdx.x; idx < nrows * (kVTW / 8); idx += 256) {
+        const int r = idx >> 3, xl = 8 * (idx & 7);
+        const half8* src = reinterpret_cast<const half8*>(&s_px[r * kVPxPitch + xl]);
+        float acc[8], w[16];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int t = u - q;
-                if (t >= 0 && t < p.Tx) acc[q] = fmaf(s_kx[t], v, acc[q]);
+        for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+        {
+            const half8 v = src[0];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = (float)v[i];
+        }
+        for (int tb = 0; tb < txp; tb += 8) {
+            const half8 v = src[tb / 8 + 1];
+            const floatx4 ka = *reinterpret_cast<const floatx4*>(&s_kx[tb]), kb = *reinterpret_cast<const floatx4*>(&s_kx[tb + 4]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[8 + i] = (float)v[i];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float kv = i < 4 ? ka[i] : kb[i - 4];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) acc[q] = fmaf(kv, w[q + i], acc[q]);
             }
-        }
-        *reinterpret_cast<half4*>(&s_tmp[r * kVTmpPitch + 4 * cg]) = to_half4(acc);
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < kVTH * (kVTW / 4); idx += 256) {
-        const int r = idx / (kVTW / 4), cg = idx - r * (kVTW / 4);
-        const int y = y0 + r, x = x0 + 4 * cg;
-        if (y >= p.H || x >= p.W) continue;
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int t = 0; t < p.Ty; ++t) {
-            const half4 v = *reinterpret_cast<const half4*>(&s_tmp[(r + t) * kVTmpPitch + 4 * cg]);
-            const float k = s_ky[t];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc[q] = fmaf(k, (float)v[q], acc[q]);
+            for (int i = 0; i < 8; ++i) w[i] = w[8 + i];
         }
-        store4_mask(p.out + (int64_t)y * p.out_pitch, x, p.W, acc);
+        floatx4* dst = reinterpret_cast<floatx4*>(&s_tmp[r * kVTW + xl]);
+        dst[0] = floatx4{(float)(half_t)acc[0], (float)(half_t)acc[1], (float)(half_t)acc[2], (float)(half_t)acc[3]};
+        dst[1] = floatx4{(float)(half_t)acc[4], (float)(half_t)acc[5], (float)(half_t)acc[6], (float)(half_t)acc[7]};
     }
+    // rows only the zero taps reach
+    for (int idx = nrows * kVTW + threadIdx.x; idx < (kVTH + typ) * kVTW; idx += 256) s_tmp[idx] = 0.f;
+    __syncthreads();
+    // column pass: thread = 8 consecutive rows of one column
+    const int x = threadIdx.x & 63, r0 = 8 * (threadIdx.x >> 6);
+    if (x0 + x >= p.W || y0 + r0 >= p.H) return;
+    float acc[8], w[16];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = s_tmp[(r0 + i) * kVTW + x];
+    for (int tb = 0; tb < typ; tb += 8) {
+        const floatx4 ka = *reinterpret_cast<const floatx4*>(&s_ky[tb]), kb = *reinterpret_cast<const floatx4*>(&s_ky[tb + 4]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[8 + i] = s_tmp[(r0 + tb + 8 + i) * kVTW + x];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float kv = i < 4 ? ka[i] : kb[i - 4];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = fmaf(kv, w[q + i], acc[q]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = w[8 + i];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        if (y0 + r0 + q < p.H) p.out[(int64_t)(y0 + r0 + q) * p.out_pitch + x0 + x] = acc[q];
 }
 
 static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, int W,
