@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, 256-tap FIR, 2-D convolution, 2x resampling, Lanczos resize, recursive filter, DCT denoise)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, long-tap FIR, 2-D convolution, 2x resampling, Lanczos resize, recursive filter, DCT denoise)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -223,28 +223,29 @@ def main():
         out["supplementary"] = {"fir1d_stacked_262144x256": {
             "ms": sms, "gpixels_per_s": Hs * 256 / sms / 1e6, "achieved": Hs * 256 * 6 / sms / 1e6,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": Hs * 256 * 6 / sms / 1e6 / HBM_PEAK_GBS}}
-        # ... and the large-tap regime of the paper's 1-D study (Sec. V-A): 256 taps on the blur
-        # stage's 4096 x 4096 image, matrix-unit kernel and vector-ALU twin.
+        # ... and the large-tap regime of the paper's 1-D study (Sec. V-A): 64, 128 and 256 taps on the
+        # blur stage's 4096 x 4096 image, matrix-unit kernel and vector-ALU twin.
         del sx, so
         torch.cuda.empty_cache()
-        long_taps = synth.random_taps_f16(2256, 256)
         lx, lo = ins["sepblur"], outs["sepblur"]
-
-        def timed(fn, iters):
-            for i in range(2):
-                fn(lx[i % 4], lo[i % 4], long_taps, 127)
-            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a0.record()
-            for i in range(iters):
-                fn(lx[i % 4], lo[i % 4], long_taps, 127)
-            a1.record()
-            torch.cuda.synchronize()
-            return a0.elapsed_time(a1) / iters
-        m_ms, v_ms = timed(hb.hb_fir1d, 10), timed(hb.hb_fir1d_valu, 3)
         npx = 4096 * 4096
-        out["supplementary"]["fir1d_256taps_4096x4096"] = {
-            "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
-            "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
+        for ntaps in (64, 128, 256):
+            long_taps = synth.random_taps_f16(2000 + ntaps, ntaps)
+
+            def timed(fn, iters):
+                for i in range(2):
+                    fn(lx[i % 4], lo[i % 4], long_taps, (ntaps - 1) // 2)
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for i in range(iters):
+                    fn(lx[i % 4], lo[i % 4], long_taps, (ntaps - 1) // 2)
+                a1.record()
+                torch.cuda.synchronize()
+                return a0.elapsed_time(a1) / iters
+            m_ms, v_ms = timed(hb.hb_fir1d, 10), timed(hb.hb_fir1d_valu, 3)
+            out["supplementary"]["fir1d_%dtaps_4096x4096" % ntaps] = {
+                "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
+                "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
         # ... and the paper's 2-D study (Sec. V-A): non-separable k x k kernels, k = 16 and 32, on
         # the same image.  tflops counts the definition's 2 k^2 flops per pixel, not the Toeplitz zeros.
         for k in (16, 32):
