@@ -100,18 +100,19 @@ __global__ void __launch_bounds__(kC2Threads) down2_mfma_kernel(Rs2Args p) {
             // input rows 2 (16 G + c + t_min) + par, clamped into the image
             const int yr = clampi(2 * (16 * G + c + p.tmin[par]) + par, 0, p.H - 1);
             const uint32_t rowoff = (uint32_t)yr * rowbytes;
+            // window kk of tile w starts at pixel 32 (w + kk): NW + NK - 1 different windows, each loaded once
+            half8 win[NW + NK - 1];
             if (inside) {
 #pragma unroll
-                for (int w = 0; w < NW; ++w)
-#pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) d[par][w][kk] = ldg8(src, rowoff + 16u * g + 2u * (32u * w + 32u * kk));
+                for (int u = 0; u < NW + NK - 1; ++u) win[u] = ldg8(src, rowoff + 16u * g + 2u * (32u * u));
             } else {
 #pragma unroll
-                for (int w = 0; w < NW; ++w)
-#pragma unroll
-                    for (int kk = 0; kk < NK; ++kk)
-                        d[par][w][kk] = rs2_load8_clamped(p.in, rowoff, xs0 + 8 * g + 32 * w + 32 * kk, p.W);
+                for (int u = 0; u < NW + NK - 1; ++u) win[u] = rs2_load8_clamped(p.in, rowoff, xs0 + 8 * g + 32 * u, p.W);
             }
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk) d[par][w][kk] = win[w + kk];
         }
     };
     auto store_group = [&](int Q, const floatx4 (&acc)[NW]) {
