@@ -63,6 +63,93 @@ def test_fir_argument_validation(lib, fn):
     assert call(i=ctypes.c_void_p(0x1001)) == hb.HB_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("fn", ["hb_sepblur", "hb_sepblur_valu"])
+def test_sepblur_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    ok = dict(i=FAKE, o=FAKE, H=16, W=16, ip=16, op=16, tx=TAPS, nx=8, ax=3, ty=TAPS, ny=8, ay=3)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["H"], p["W"], p["ip"], p["op"], p["tx"], p["nx"], p["ax"], p["ty"], p["ny"], p["ay"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(tx=None) == hb.HB_ERR_INVALID_ARG
+    assert call(ty=None) == hb.HB_ERR_INVALID_ARG
+    assert call(H=0) == hb.HB_ERR_INVALID_ARG
+    assert call(W=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=15) == hb.HB_ERR_INVALID_ARG
+    assert call(op=15) == hb.HB_ERR_INVALID_ARG
+    assert call(nx=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ny=hb.HB_MAX_TAPS + 1) == hb.HB_ERR_INVALID_ARG
+    assert call(ax=8) == hb.HB_ERR_INVALID_ARG
+    assert call(ay=-1) == hb.HB_ERR_INVALID_ARG
+    assert call(o=ctypes.c_void_p(0x1002)) == hb.HB_ERR_INVALID_ARG      # fp32 output on a 2-byte boundary
+
+
+@pytest.mark.parametrize("fn", ["hb_sat2d", "hb_sat2d_valu"])
+def test_sat2d_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    need = lib.hb_sat2d_workspace_size(100, 200)
+    assert need > 0 and lib.hb_sat2d_workspace_size(0, 5) == 0 and lib.hb_sat2d_workspace_size(5, -1) == 0
+    # the workspace holds row and column sums per tile: it grows with the image
+    assert lib.hb_sat2d_workspace_size(1000, 2000) > need
+    WS = ctypes.c_void_p(0x10000)
+    ok = dict(i=FAKE, o=FAKE, H=100, W=200, ip=200, op=200, ws=WS, wsb=need)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["o"], p["H"], p["W"], p["ip"], p["op"], p["ws"], p["wsb"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(H=0) == hb.HB_ERR_INVALID_ARG
+    assert call(W=-3) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=199) == hb.HB_ERR_INVALID_ARG
+    assert call(op=100) == hb.HB_ERR_INVALID_ARG
+    assert call(ws=None) == hb.HB_ERR_WORKSPACE
+    assert call(wsb=need - 1) == hb.HB_ERR_WORKSPACE
+    assert call(ws=ctypes.c_void_p(0x100010)) == hb.HB_ERR_WORKSPACE       # not 256-byte aligned
+
+
+@pytest.mark.parametrize("fn", ["hb_conv3x3", "hb_conv3x3_valu"])
+def test_conv3x3_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    ok = dict(i=FAKE, w=FAKE, o=FAKE, N=1, H=8, W=8, ci=64, co=64)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["w"], p["o"], p["N"], p["H"], p["W"], p["ci"], p["co"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(w=None) == hb.HB_ERR_INVALID_ARG
+    assert call(o=None) == hb.HB_ERR_INVALID_ARG
+    assert call(N=0) == hb.HB_ERR_INVALID_ARG
+    assert call(H=0) == hb.HB_ERR_INVALID_ARG
+    assert call(W=-1) == hb.HB_ERR_INVALID_ARG
+    assert call(ci=0) == hb.HB_ERR_INVALID_ARG
+    assert call(i=ctypes.c_void_p(0x1008)) == hb.HB_ERR_INVALID_ARG      # pixels are read 16 bytes at a time
+    assert call(ci=32) == hb.HB_ERR_UNSUPPORTED
+    assert call(co=128) == hb.HB_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("fn", ["hb_pyr_level", "hb_pyr_level_valu"])
+def test_pyr_level_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    ok = dict(i=FAKE, r=FAKE, d=FAKE, H=16, W=32, ip=32, rp=32, dp=16)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["i"], p["r"], p["d"], p["H"], p["W"], p["ip"], p["rp"], p["dp"], None)
+    assert call(i=None) == hb.HB_ERR_INVALID_ARG
+    assert call(r=None) == hb.HB_ERR_INVALID_ARG
+    assert call(H=15) == hb.HB_ERR_INVALID_ARG                             # odd sizes have no half-size level
+    assert call(W=31, ip=32) == hb.HB_ERR_INVALID_ARG
+    assert call(H=0) == hb.HB_ERR_INVALID_ARG
+    assert call(ip=31) == hb.HB_ERR_INVALID_ARG
+    assert call(rp=16) == hb.HB_ERR_INVALID_ARG
+    assert call(dp=15) == hb.HB_ERR_INVALID_ARG                            # down is W / 2 wide
+    assert call(d=ctypes.c_void_p(0x1001)) == hb.HB_ERR_INVALID_ARG
+    assert call(dp=(1 << 26) + 2) == hb.HB_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("fn", ["hb_conv2d", "hb_conv2d_valu"])
 def test_conv2d_argument_validation(lib, fn):
     f = getattr(lib, fn)
