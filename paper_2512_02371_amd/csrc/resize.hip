@@ -195,22 +195,68 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
     }
 }
 
-// Vector-ALU twin of one pass: a thread per (o, r), r fastest; plain loop over the band.
+// Vector-ALU twin of one pass.  A workgroup takes one group of 16 outputs and 64 rows of X: the samples
+// the group reads (from its smallest start on, 256 at a time, every index clamped) are staged in LDS
+// with coalesced row loads; a thread owns one output o and four rows, reads a coefficient once and
+// uses it for its four rows; the four results are consecutive elements of row o of the transposed Z.
+constexpr int kRzvChunk = 256;                // staged samples per row and round
+constexpr int kRzvPitch = kRzvChunk + 8;      // halves
+
 template <bool OUT_HALF>
 __global__ void __launch_bounds__(256) band_valu_kernel(BandArgs p) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t per_plane = (int64_t)p.nout * p.rows;
-    if (idx >= per_plane * p.planes) return;
-    const int plane = (int)(idx / per_plane);
-    const int64_t rem = idx - (int64_t)plane * per_plane;
-    const int o = (int)(rem / p.rows), r = (int)(rem - (int64_t)o * p.rows);
-    const half_t* row = p.x + (size_t)plane * p.x_plane + (size_t)r * p.x_pitch;
-    const half_t* k = p.coef + (size_t)o * p.band;
-    const int st = clampi(p.start[o], -p.band, p.len - 1);   // same samples as the unclamped start
-    float acc = 0.f;
-    for (int j = 0; j < p.band; ++j) acc = fmaf((float)k[j], (float)row[clampi(st + j, 0, p.len - 1)], acc);
-    if (OUT_HALF) (reinterpret_cast<half_t*>(p.z) + (size_t)plane * p.z_plane)[(size_t)o * p.z_pitch + r] = (half_t)acc;
-    else (reinterpret_cast<float*>(p.z) + (size_t)plane * p.z_plane)[(size_t)o * p.z_pitch + r] = acc;
+    __shared__ __attribute__((aligned(16))) half_t s_x[64 * kRzvPitch];
+    const int tid = threadIdx.x;
+    int wg = blockIdx.x;
+    const int grp = wg % p.ngroups;
+    wg /= p.ngroups;
+    const int nblk = (p.rows + 63) / 64;
+    const int blk = wg % nblk, plane = wg / nblk;
+    const int r0 = 64 * blk;
+    const int o = 16 * grp + (tid & 15), rq = tid >> 4;
+    const bool live = o < p.nout;
+    const int st = live ? clampi(p.start[o], -p.band, p.len - 1) : 0;   // same samples as the unclamped start
+    int lo = live ? st : 0x7fffffff, hi = live ? st + p.band : -0x7fffffff;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+        lo = min(lo, __shfl_xor(lo, off, 64));
+        hi = max(hi, __shfl_xor(hi, off, 64));
+    }
+    const half_t* xpl = p.x + (size_t)plane * p.x_plane;
+    const half_t* k = p.coef + (size_t)(live ? o : 0) * p.band;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int base = lo; base < hi; base += kRzvChunk) {
+        const int n = min(kRzvChunk, hi - base);          // samples of this round
+        const int nch = (n + 7) / 8;
+        if (base != lo) __syncthreads();                  // everyone is done with the previous round
+        for (int idx = tid; idx < 64 * nch; idx += 256) {
+            const int r = idx / nch, ch = idx - r * nch;
+            const half_t* row = xpl + (size_t)min(r0 + r, p.rows - 1) * p.x_pitch;
+            *reinterpret_cast<half8*>(&s_x[r * kRzvPitch + 8 * ch]) = load8_clamp(row, base + 8 * ch, p.len);
+        }
+        __syncthreads();
+        if (live) {
+            const int j0 = max(0, base - st), j1 = min(p.band, base + n - st);
+            for (int j = j0; j < j1; ++j) {
+                const float c = (float)k[j];
+                const half_t* src = &s_x[4 * rq * kRzvPitch + (st + j - base)];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] = fmaf(c, (float)src[q * kRzvPitch], acc[q]);
+            }
+        }
+    }
+    if (!live) return;
+    const int r = r0 + 4 * rq;
+    if (OUT_HALF) {
+        half_t* z = reinterpret_cast<half_t*>(p.z) + (size_t)plane * p.z_plane + (size_t)o * p.z_pitch;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (r + q < p.rows) z[r + q] = (half_t)acc[q];
+    } else {
+        float* z = reinterpret_cast<float*>(p.z) + (size_t)plane * p.z_plane + (size_t)o * p.z_pitch;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (r + q < p.rows) z[r + q] = acc[q];
+    }
 }
 
 static int64_t rz_pitch(int H) { return ((int64_t)H + 7) & ~(int64_t)7; }
@@ -271,7 +317,7 @@ static hb_status resize_run(bool valu, const hb_half* in, float* out, void* work
         q->ngroups = ceil_div(q->nout, 16);
         q->nruns = ceil_div(q->rows, 64 * kRzWaves);
         if (valu) {
-            const int64_t blocks = ((int64_t)q->planes * q->nout * q->rows + 255) / 256;
+            const int64_t blocks = (int64_t)q->planes * q->ngroups * ceil_div(q->rows, 64);
             if (blocks > 0x7fffffff) return HB_ERR_UNSUPPORTED;
             if (q == &a) hipLaunchKernelGGL(band_valu_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, *q);
             else hipLaunchKernelGGL(band_valu_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, *q);
