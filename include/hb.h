@@ -239,7 +239,9 @@ hb_status hb_iir2_valu(const hb_half *in, float *out, int C, int64_t T, int64_t 
  * fp16, out: C planes of H x W fp32 (row pitches and plane strides in elements);
  * H and W multiples of 8 and >= 16; threshold >= 0.  `workspace`: device scratch of
  * at least hb_dct_denoise_workspace_size(C, H, W) bytes, 256-byte aligned; contents
- * undefined on exit; concurrent calls need their own.
+ * undefined on exit; concurrent calls need their own.  (hb_dct_denoise blends inside
+ * its one kernel and leaves the workspace untouched; the twin keeps its tiles there.
+ * Both check it the same way.)
  */
 size_t hb_dct_denoise_workspace_size(int C, int H, int W);
 hb_status hb_dct_denoise(const hb_half *in, float *out, int C, int H, int W,
