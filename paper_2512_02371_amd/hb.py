@@ -111,6 +111,9 @@ def status_string(code: int) -> str:
     return load().hb_status_string(int(code)).decode()
 
 
+hb_status_string = status_string          # the entry point's own name
+
+
 def _check(fn: str, code: int) -> None:
     if code != HB_OK:
         raise HbError(fn, code)

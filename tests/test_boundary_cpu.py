@@ -27,6 +27,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(hb.SYMBOLS)
     for s in declared:
         assert hasattr(lib, s), s
+        assert callable(getattr(hb, s, None)), f"the binding has no function named {s}"
 
 
 def test_status_strings(lib):
