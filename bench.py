@@ -373,23 +373,20 @@ def cpu_baseline(host, fir_taps, gau_taps, total_px):
 
     s = timed(lambda: oracle.fir1d(host["fir1d"], fir_taps, 3))
     rates["fir1d"] = 256 * 256 / s
-    rows = 1024
-    s = timed(lambda: oracle.sepblur(host["sepblur"][:rows], gau_taps, 7, gau_taps, 7))
-    rates["sepblur"] = rows * 4096 / s
-    s = timed(lambda: oracle.sat2d(host["sat2d"][:rows]))
-    rates["sat2d"] = rows * 4096 / s
-    band = 64
-    s = timed(lambda: oracle.conv3x3_rows(host["conv3x3"], host["conv3x3_w"], 480, 480 + band))
+    s = timed(lambda: oracle.sepblur(host["sepblur"], gau_taps, 7, gau_taps, 7))
+    rates["sepblur"] = 4096 * 4096 / s
+    s = timed(lambda: oracle.sat2d(host["sat2d"]))
+    rates["sat2d"] = 4096 * 4096 / s
+    band = 512                                   # half the image: ~20 G fp64 multiply-adds
+    s = timed(lambda: oracle.conv3x3_rows(host["conv3x3"], host["conv3x3_w"], 256, 256 + band))
     rates["conv3x3"] = band * 1024 / s
-    rows = 1024
-    s = timed(lambda: oracle.pyr_level(host["pyr_level"][:rows]))
-    rates["pyr_level"] = rows * 8192 / s
+    s = timed(lambda: oracle.pyr_level(host["pyr_level"]))
+    rates["pyr_level"] = 8192 * 8192 / s
     step_s = sum(stage_work(st)[0] / rates[st] for st in STAGES)
     return {
         "value": total_px / step_s / 1e9, "unit": "Gpixels/s", "cores": ncores, "kind": "oracle",
-        "sample": "fir1d full 256x256; sepblur, sat2d first 1024 rows of 4096x4096; conv3x3 a 64-row "
-                  "band of 1024x1024x64; pyr_level first 1024 rows of 8192x8192; step rate projected "
-                  "from the per-stage rates",
+        "sample": "every stage once on its whole benchmark input, except conv3x3: rows 256..767 of "
+                  "1024x1024x64 (half the image); step rate from the per-stage rates",
         "stages_gpixels_per_s": {k: v / 1e9 for k, v in rates.items()},
     }
 
