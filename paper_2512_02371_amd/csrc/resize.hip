@@ -23,7 +23,7 @@
 namespace hb {
 
 constexpr int kRzTiles = 4;                   // 16-row tiles of X per wave (64 rows r)
-constexpr int kRzWaves = 4;                   // waves per workgroup: 4 strips of 64 rows, one group of 16 outputs
+constexpr int kRzWaves = 2;                   // waves per workgroup: 2 strips of 64 rows, one group of 16 outputs (measured: 1, 4, 8 are slower)
 constexpr int kRzMaxChunks = HB_RESIZE_MAX_SPAN / 32;
 
 struct BandArgs {
@@ -33,7 +33,7 @@ struct BandArgs {
     const half_t* coef;                       // device: nout x band coefficients
     int rows, len, nout, band, planes;
     int64_t x_pitch, x_plane, z_pitch, z_plane;
-    int ngroups, nruns;                       // groups of 16 outputs; runs of 4 strips per plane
+    int ngroups, nruns;                       // groups of 16 outputs; runs of kRzWaves strips per plane
 };
 
 // Sixteen rows of 64 floats from the accumulators (lane (c, g): row c, columns 16 w + 4 g ..) to
