@@ -191,10 +191,15 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
 // clamped: the Toeplitz matrix is indexed by window position, so the border rule needs nothing else.
 // Runs start 2 NK - 2 windows early (products into accumulators of tiles left of the run are
 // computed and dropped), the price of cutting a row into several tasks.
+// Waves per workgroup of the walk: the longest filters (few, long-lived waves of 100+ registers) run
+// best as single-wave workgroups, the shorter ones four to a workgroup (measured).
+constexpr int fir_walk_waves(int nk) { return nk >= 7 ? 1 : 4; }
+
 template <int NK, bool STREAM>
-__global__ void __launch_bounds__(256) fir1d_walk_kernel(FirArgs p) {
+__global__ void __launch_bounds__(64 * fir_walk_waves(NK)) fir1d_walk_kernel(FirArgs p) {
     constexpr int R = 2 * NK;
-    __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2>::kFloats];
+    constexpr int WV = fir_walk_waves(NK);
+    __shared__ __attribute__((aligned(16))) float s_patch[WV][RowPatch<2>::kFloats];
     const int lane = threadIdx.x & 63;
     const int c = lane & 15, g = lane >> 4;
     const int e = p.anchor & 1;
@@ -204,7 +209,7 @@ __global__ void __launch_bounds__(256) fir1d_walk_kernel(FirArgs p) {
     for (int kk = 0; kk < NK; ++kk) coef[kk] = tap_run(p.taps.tab, 32 * kk + 8 * g - c - e);
 
     const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int task = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
+    const int task = __builtin_amdgcn_readfirstlane(wgpos * WV + (threadIdx.x >> 6));
     if (task >= p.wtasks) return;
     const int rg = task / p.nruns, run = task - rg * p.nruns;
     const int t0 = run * p.run_tiles;                     // first tile of the run
@@ -395,12 +400,13 @@ extern "C" hb_status hb_fir1d(const hb_half* in, float* out, int H, int W,
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool ss = (int64_t)H * W * 4 <= kStreamStoreMaxBytes;
     if (nk >= HB_FIR_WALK_MIN_NK) {   // long filters: the walk along the row, every window loaded once
-        const dim3 wgrid(ceil_div(a.wtasks, 4)), wblock(256);
 #define HB_FIR_WALK(N)                                                                            \
-    case N:                                                                                       \
+    case N: {                                                                                     \
+        const dim3 wgrid(ceil_div(a.wtasks, fir_walk_waves(N))), wblock(64 * fir_walk_waves(N));  \
         if (ss) hipLaunchKernelGGL((fir1d_walk_kernel<N, true>), wgrid, wblock, 0, st, a);        \
         else hipLaunchKernelGGL((fir1d_walk_kernel<N, false>), wgrid, wblock, 0, st, a);          \
-        break;
+        break;                                                                                    \
+    }
         switch (nk) {
             HB_FIR_WALK(2) HB_FIR_WALK(3) HB_FIR_WALK(4) HB_FIR_WALK(5) HB_FIR_WALK(6) HB_FIR_WALK(7) HB_FIR_WALK(8) HB_FIR_WALK(9)
             default: return HB_ERR_UNSUPPORTED;
