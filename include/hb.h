@@ -270,6 +270,23 @@ hb_status hb_sat2d_valu(const hb_half *in, float *out, int H, int W,
                         void *workspace, size_t workspace_bytes, hb_stream stream);
 
 /*
+ * hb_sat2d for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (minus the workspace), same kernels and bit-identical results; the carry
+ * tables live in a fixed array of HB_SAT2D_NOALLOC_SCRATCH_BYTES inside the library's
+ * code object, which every GPU the library runs on holds until the process ends.  The
+ * call allocates and frees nothing.  Images whose hb_sat2d_workspace_size(H, W) exceeds
+ * HB_SAT2D_NOALLOC_SCRATCH_BYTES (4096 x 4096 fits, as does any H x W with
+ * ceil(H/64) * ceil(W/64) <= 5000) return HB_ERR_UNSUPPORTED.  All calls on one GPU share
+ * that GPU's array: two such calls that overlap in time on one GPU (different streams)
+ * race; calls on one stream, or ordered by events, are fine.  The first call on a device
+ * looks the array's address up (make it outside a graph capture).
+ */
+#define HB_SAT2D_NOALLOC_SCRATCH_BYTES (5u << 20)
+hb_status hb_sat2d_noalloc(const hb_half *in, float *out, int H, int W,
+                           int64_t in_pitch, int64_t out_pitch, hb_stream stream);
+
+/*
  * Multi-channel 3x3 convolution, stride 1, zero padding 1 (Sec. V-A 2-D form summed
  * over input channels; the conv layer of Sec. IV without bias and activation), as an
  * implicit GEMM with M = pixels, N = Cout, K = 9 * Cin:

@@ -411,6 +411,44 @@ extern "C" size_t hb_sat2d_workspace_size(int H, int W) {
     return hb::sat_workspace_floats(H, W) * sizeof(float);
 }
 
+// Scratch of hb_sat2d_noalloc: the carry tables live in this array instead of a caller's workspace.
+// In host code the array's name is only a handle, not a device address: the address is looked up
+// once per device (every GPU holds its own copy of the array) and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[HB_SAT2D_NOALLOC_SCRATCH_BYTES];
+
+namespace hb {
+
+static hb_status sat_launch_mfma(const SatArgs& a, hipStream_t st) {
+    const int ntiles = a.nb * a.ns;
+    hipLaunchKernelGGL(sat_sums_mfma_kernel, dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(sat_scan_kernel, dim3(ceil_div(a.Hs + a.Ws + a.nb, 4)), dim3(256), 0, st, a);
+    if ((int64_t)a.H * a.W * 4 <= kStreamStoreMaxBytes)
+        hipLaunchKernelGGL((sat_apply_mfma_kernel<true>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((sat_apply_mfma_kernel<false>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
+    return launch_status();
+}
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+static hb_status sat_scratch_address(void** ptr) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return HB_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return HB_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HB_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return HB_OK;
+}
+
+}  // namespace hb
+
 extern "C" hb_status hb_sat2d(const hb_half* in, float* out, int H, int W,
                               int64_t in_pitch, int64_t out_pitch,
                               void* workspace, size_t workspace_bytes, hb_stream stream) {
@@ -418,15 +456,22 @@ extern "C" hb_status hb_sat2d(const hb_half* in, float* out, int H, int W,
     SatArgs a;
     hb_status s = sat_prepare(a, in, out, H, W, in_pitch, out_pitch, workspace, workspace_bytes);
     if (s != HB_OK) return s;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const int ntiles = a.nb * a.ns;
-    hipLaunchKernelGGL(sat_sums_mfma_kernel, dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(sat_scan_kernel, dim3(ceil_div(a.Hs + a.Ws + a.nb, 4)), dim3(256), 0, st, a);
-    if ((int64_t)H * W * 4 <= kStreamStoreMaxBytes)
-        hipLaunchKernelGGL((sat_apply_mfma_kernel<true>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL((sat_apply_mfma_kernel<false>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
-    return launch_status();
+    return sat_launch_mfma(a, reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" hb_status hb_sat2d_noalloc(const hb_half* in, float* out, int H, int W,
+                                      int64_t in_pitch, int64_t out_pitch, hb_stream stream) {
+    using namespace hb;
+    hb_status s = check_image(in, out, H, W, in_pitch, out_pitch);
+    if (s != HB_OK) return s;
+    if (hb_sat2d_workspace_size(H, W) > (size_t)HB_SAT2D_NOALLOC_SCRATCH_BYTES) return HB_ERR_UNSUPPORTED;
+    void* ws = nullptr;
+    s = sat_scratch_address(&ws);
+    if (s != HB_OK) return s;
+    SatArgs a;
+    s = sat_prepare(a, in, out, H, W, in_pitch, out_pitch, ws, (size_t)HB_SAT2D_NOALLOC_SCRATCH_BYTES);
+    if (s != HB_OK) return s;
+    return sat_launch_mfma(a, reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" hb_status hb_sat2d_valu(const hb_half* in, float* out, int H, int W,
