@@ -276,8 +276,8 @@ hb_status hb_sat2d_valu(const hb_half *in, float *out, int H, int W,
  * tables live in a fixed array of HB_SAT2D_NOALLOC_SCRATCH_BYTES inside the library's
  * code object, which every GPU the library runs on holds until the process ends.  The
  * call allocates and frees nothing.  Images whose hb_sat2d_workspace_size(H, W) exceeds
- * HB_SAT2D_NOALLOC_SCRATCH_BYTES (4096 x 4096 fits, as does any H x W with
- * ceil(H/64) * ceil(W/64) <= 5000) return HB_ERR_UNSUPPORTED.  All calls on one GPU share
+ * HB_SAT2D_NOALLOC_SCRATCH_BYTES (4096 x 4096 needs 4.6 MiB and fits) return
+ * HB_ERR_UNSUPPORTED.  All calls on one GPU share
  * that GPU's array: two such calls that overlap in time on one GPU (different streams)
  * race; calls on one stream, or ordered by events, are fine.  The first call on a device
  * looks the array's address up (make it outside a graph capture).
@@ -285,6 +285,16 @@ hb_status hb_sat2d_valu(const hb_half *in, float *out, int H, int W,
 #define HB_SAT2D_NOALLOC_SCRATCH_BYTES (5u << 20)
 hb_status hb_sat2d_noalloc(const hb_half *in, float *out, int H, int W,
                            int64_t in_pitch, int64_t out_pitch, hb_stream stream);
+
+/*
+ * Tuning and test hook of hb_sat2d's one-launch kernel (see hb_sat2d): how many polls a
+ * workgroup spends in the grid-wide wait before it hands its region to a finisher.
+ * polls > 0 sets the limit, 0 restores the default (16384), a negative value makes every
+ * workgroup that does not find the wait already over stop at once (tests use it to run
+ * the finisher path).  Whatever the value, every kernel exits and the result is the same.
+ * Process-wide; read when a call is enqueued.  Returns the previous limit.
+ */
+int hb_sat2d_set_wait_limit(int polls);
 
 /*
  * Multi-channel 3x3 convolution, stride 1, zero padding 1 (Sec. V-A 2-D form summed

@@ -282,7 +282,7 @@ extern "C" hb_status hb_conv2d(const hb_half* in, float* out, int H, int W,
     a.nstrips = ceil_div(W, 16 * kC2Tiles);
     // One task per wave: a strip times a run of output row groups.  Every task walks
     // (kernel rows / 16) extra input groups, so runs are as long as filling the chip allows.
-    const int waves = kNumCU * (kC2Threads / 64);
+    const int waves = num_cu() * (kC2Threads / 64);
     int len = (int)(((int64_t)a.nstrips * a.ngroups + waves - 1) / waves);
     if (len < 2) len = a.ngroups < 2 ? a.ngroups : 2;
     a.seg_len = len;

@@ -369,7 +369,7 @@ static hb_status conv_prepare(ConvArgs& a, const hb_half* in, const hb_half* w, 
     a.tiles_y = ceil_div(H, kCvTY);
     a.ntiles = (int)tiles;
     // column segments of the MFMA kernel: about one per compute unit, at least 4 tiles long
-    const int want = ceil_div(kNumCU, N * a.tiles_x);
+    const int want = ceil_div(num_cu(), N * a.tiles_x);
     int len = ceil_div(a.tiles_y, want);
     if (len < 4) len = a.tiles_y < 4 ? a.tiles_y : 4;
     a.seg_len = len;

@@ -31,10 +31,10 @@ struct FoldTablesT {
 using Taps = TapsT<HB_MAX_TAPS>;
 using FoldTables = FoldTablesT<HB_MAX_TAPS>;
 
-// MI355X: 256 compute units, 4 SIMDs each.  Streaming kernels launch one short-lived
-// wave per task (the dispatcher keeps the memory pipes fed best that way); beyond this
-// many 256-thread workgroups every wave walks a strided list of tasks instead.
-constexpr int kNumCU = 256;
+// Streaming kernels launch one short-lived wave per task (the dispatcher keeps the memory
+// pipes fed best that way); beyond this many 256-thread workgroups every wave walks a
+// strided list of tasks instead.  The number of compute units (MI355X: 256, 4 SIMDs each) is
+// read from the device, see num_cu().
 constexpr int kMaxStreamBlocks = 1 << 20;
 
 // Tasks form an nct x nseg grid.  Those in the rectangle [c0, c1) x [s0, s1) touch no image
@@ -160,6 +160,27 @@ inline hb_status allow_dynamic_lds(const void* kernel, size_t bytes) {
     if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return HB_ERR_HIP;
     have = bytes;
     return HB_OK;
+}
+
+// Compute units of the current device (0 if the query fails), read once per device.
+inline int device_num_cu() {
+    static std::mutex mu;
+    static std::map<int, int> known;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = known.find(dev);
+    if (it != known.end()) return it->second;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    known[dev] = n;
+    return n;
+}
+
+// Compute units used for launch geometry: the device's count, 256 (MI355X) if it cannot be read.
+inline int num_cu() {
+    const int n = device_num_cu();
+    return n > 0 ? n : 256;
 }
 
 inline int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }

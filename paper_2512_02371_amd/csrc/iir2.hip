@@ -420,7 +420,7 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int64_t waves = (int64_t)C * (valu ? (a.ntiles + 3) / 4 : a.ntiles);
     int64_t wgs = (waves + 3) / 4;
-    if (!valu && wgs > 8 * kNumCU) wgs = 8 * kNumCU;          // the matrix kernels' waves stride over the tiles
+    if (!valu && wgs > 8 * num_cu()) wgs = 8 * num_cu();          // the matrix kernels' waves stride over the tiles
     const unsigned blocks = (unsigned)wgs;
     if (valu) hipLaunchKernelGGL(iir2_blocks_valu_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL(iir2_state_mfma_kernel, dim3(blocks), dim3(256), 0, st, a);

@@ -445,7 +445,7 @@ static hb_status rs2_prepare(Rs2Args& a, bool up, const hb_half* in, float* out,
     a.nstrips = ceil_div(Wo, 16 * kC2Tiles);
     a.ngroups = up ? ceil_div(H, 16) : ceil_div(Ho, 16);
     // one task per wave: a strip times a run of groups, as long as filling the chip allows
-    const int waves = kNumCU * (kC2Threads / 64);
+    const int waves = num_cu() * (kC2Threads / 64);
     int len = (int)(((int64_t)a.nstrips * a.ngroups + waves - 1) / waves);
     if (len < 2) len = a.ngroups < 2 ? a.ngroups : 2;
     a.seg_len = len;

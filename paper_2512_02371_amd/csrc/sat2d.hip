@@ -19,12 +19,15 @@
 //   The sums pass uses the same operands: X * 1 for row sums; X * [I|0], X * [0|I] copy the pixels
 //   into accumulator layout (exactly), whose stacked pairs times the all-ones matrix give column
 //   sums.  No cross-lane traffic in that pass at all.
+#include <atomic>
+
 #include "hb_device.hpp"
 #include "hb_host.hpp"
 
 namespace hb {
 
 constexpr int kSatTile = 64;
+constexpr int kMaxDevices = 64;
 
 struct SatArgs {
     const half_t* in;
@@ -305,6 +308,425 @@ __global__ void __launch_bounds__(256) sat_apply_mfma_kernel(SatArgs p) {
 }
 
 // ---------------------------------------------------------------------------
+// One launch for images whose tiles are all resident at once: the image is read ONCE.
+//
+// A workgroup of TR x TC waves owns a region of TR x TC tiles.  Before the grid-wide wait every
+// wave loads its tile and turns it into the tile's LOCAL table Lt (row prefix on the matrix units,
+// column prefix over the lanes), which stays in registers.  For a pixel (i, j) of a tile with
+// origin (i0, j0)
+//     S[i][j] = Lt[i-i0][j-j0] + R[i] + C[j] + A
+//     R[i] = sum over the tiles to the left, in the same tile row, of the LAST COLUMN of their local table at row i
+//     C[j] = sum over the tiles above, in the same tile column, of the LAST ROW of their local table at column j
+//     A    = sum of everything above-left of the tile
+// so what a tile has to publish is the last row and last column of its local table.  The
+// workgroup adds those up over its region (prefixes restart at every tile border) and publishes
+// RS[region column][row], CS[region row][column] and TOT[region]; one grid-wide wait; then it adds
+// up the table lines of the regions to its left and above (coalesced 1 KB lines, few of them
+// because regions are large), finishes R, C and A of its tiles through LDS, and what is left per
+// pixel after the wait is two additions and the store.  The heavy arithmetic sits before the wait,
+// where it overlaps with the loads of the other waves.
+//
+// Grid-wide wait.  Arrival is a two-level count (up to 16 leaf counters, one root, each on its own
+// 128-byte line: arrivals at one address are served one after the other by the memory side); the
+// last arrival raises eight copies of a `go` word and workgroup w polls copy w % 8.  Table data and
+// the words of the wait are written and read with agent-scope accesses (they bypass the per-XCD L2,
+// so no cache write-back or invalidation is needed; a write-back per workgroup costs ~20 ns each,
+// one after the other).  The wait is BOUNDED: after `wait_limit` polls a workgroup stops waiting.
+// It has already arrived, so the count still completes when the last workgroup gets to run; a
+// workgroup that stopped waiting marks its region in `todo`, raises `late` and leaves, unless `go`
+// came up meanwhile.  Every workgroup that passes the wait reads `late` (raised before `go` by
+// construction, see below) and, if it is set, claims marked regions one by one, reloads their
+// pixels and finishes them.  So every wave exits whatever the residency, and every region is
+// finished by someone:
+//   late workgroup: store todo[r], late; wait for the stores; load go.  go == 0 -> leave.
+//   finisher:       observes go == 1; then loads late and todo.
+//   go is raised once, after the late workgroup's load returned 0, hence after its stores were
+//   performed at the memory side: the finisher's loads see them.
+// The host uses this kernel only when the grid fits on the device at once (occupancy query), so the
+// bounded wait ends by `go` unless other work holds compute units for longer than the limit.
+#ifndef HB_SAT_POLL_SLEEP
+#define HB_SAT_POLL_SLEEP 3                               // s_sleep units (64 clocks each) between two polls of `go`
+#endif
+struct SatSync {
+    static constexpr int kLine = 32;                      // words per 128 bytes
+    static constexpr int kLeaves = 16, kGo = 8, kMaxRegions = 1024;
+    unsigned leaf[kLeaves * kLine];
+    unsigned root[kLine];
+    unsigned go[kGo * kLine];
+    unsigned late[kLine];
+    unsigned todo[kMaxRegions];                           // 0 idle, 1 waiting for a finisher, 2 claimed
+#ifdef HB_SAT_TIMING
+    unsigned long long stamp[kMaxRegions][8];             // measurement builds only: phase time stamps per workgroup
+#endif
+};
+#ifdef HB_SAT_TIMING
+#define SAT_STAMP(S, wg, i) do { if (threadIdx.x == 0) (S)->stamp[wg][i] = wall_clock64(); } while (0)
+#else
+#define SAT_STAMP(S, wg, i) do { } while (0)
+#endif
+
+struct SatFusedArgs {
+    const half_t* in;
+    float* out;
+    int H, W;
+    int64_t in_pitch, out_pitch;
+    int nsw, nbw;          // regions down, across
+    int Hr, Wr;            // H, W rounded up to whole regions
+    float* RS;             // [nbw][Hr]  row y: sum over the columns of region column bw of the rows from its tile row's top to y
+    float* CS;             // [nsw][Wr]  column x: sum over the rows of region row sw of the columns from its tile column's left to x
+    float* TOT;            // [nsw][nbw] region totals
+    SatSync* sync;
+    int wait_limit;
+};
+
+__device__ __forceinline__ unsigned ld_agent(const unsigned* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(unsigned* p, unsigned v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ldf_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stf_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all earlier stores of this lane performed, and no memory access moved across this point
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__global__ void __launch_bounds__(256) sat_sync_clear_kernel(SatSync* s) {
+    unsigned* w = reinterpret_cast<unsigned*>(s);
+    constexpr int kWords = (SatSync::kLeaves + 1 + SatSync::kGo + 1) * SatSync::kLine + SatSync::kMaxRegions;
+    for (int i = threadIdx.x; i < kWords; i += 256) w[i] = 0u;
+}
+
+template <int TR, int TC>
+struct SatFusedLds {
+    static constexpr int kWaves = TR * TC;
+    static constexpr int kRH = kSatTile * TR, kRW = kSatTile * TC;
+    // (members that are accessed 16 bytes at a time come first and are sized in multiples of 16 bytes:
+    // a misaligned 16-byte LDS access is split and runs at a fraction of the rate)
+    float patch[kWaves][RowPatch<4>::kFloats];            // store patches
+    union {
+        struct { float r[kWaves][kRH]; float c[kWaves][kRW]; } part;    // per-wave partial sums of table lines
+        struct { float row[kWaves][kSatTile]; float col[kWaves][kSatTile]; } term;   // R and C + A of every wave's tile
+    } u;
+    float lastrow[TR][TC][kSatTile];                      // per tile: last row of its local table
+    float lastcol[TR][TC][kSatTile];                      // per tile: last column of its local table (prefix over its rows of the row sums)
+    float Rc[kRH];                                        // per region row: the RS lines of the regions to the left, added up
+    float Cc[kRW];                                        // per region column: the CS lines of the regions above, added up
+    float Apart[kWaves];
+    float A;                                              // sum of everything above-left of the region
+    int ctl;
+};
+static_assert(RowPatch<4>::kFloats % 4 == 0, "patches stay 16-byte aligned");
+
+// Before the wait, per wave: load the tile and build its local table in registers; its last row,
+// last column (and so its total) go to LDS.  Lt[rt][t]: lane (c, g) holds row 16 rt + c, columns 16 t + 4 g + v.
+template <int TR, int TC>
+__device__ __forceinline__ void sat_fused_local(const SatFusedArgs& p, SatFusedLds<TR, TC>& L,
+                                                int y0, int x0, int ts, int tb, int lane, floatx4 (&Lt)[4][4]) {
+    const int c = lane & 15, g = lane >> 4;
+    half8 X[4][2];
+    if (y0 + kSatTile <= p.H && x0 + kSatTile <= p.W) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            const half_t* src = p.in + (int64_t)(y0 + 16 * rt) * p.in_pitch + x0;       // 64-bit base per 16 rows
+            const uint32_t off = ((uint32_t)c * (uint32_t)p.in_pitch + 8u * g) * 2u;
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) X[rt][blk] = ldg8(src, off + 64u * blk);
+        }
+    } else {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+                X[rt][blk] = load8_zero(p.in, p.in_pitch, y0 + 16 * rt + c, x0 + 32 * blk + 8 * g, p.H, p.W);
+    }
+    half8 tri[2];                                         // Ut[m][k] = (k <= m + 16 half)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tri[h][i] = (half_t)((8 * g + i <= c + 16 * h) ? 1.f : 0.f);
+    const half8 one = ones8();
+    floatx4 ccar[4];                                      // running column sums: lane (c, g), columns 16 t + 4 g + v
+#pragma unroll
+    for (int t = 0; t < 4; ++t) ccar[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+        Lt[rt][0] = mfma16x16x32(tri[0], X[rt][0], zero);             // [m = column][n = row]: lane c = row, columns 4g + v
+        Lt[rt][1] = mfma16x16x32(tri[1], X[rt][0], zero);
+        const floatx4 left = mfma16x16x32(one, X[rt][0], zero);       // the row's total over the first 32 columns
+        Lt[rt][2] = mfma16x16x32(tri[0], X[rt][1], left);
+        Lt[rt][3] = mfma16x16x32(tri[1], X[rt][1], left);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float x = Lt[rt][t][v];                   // inclusive prefix over the 16 rows of the DPP row
+                x += dpp_row_shr(x, 1);
+                x += dpp_row_shr(x, 2);
+                x += dpp_row_shr(x, 4);
+                x += dpp_row_shr(x, 8);
+                x += ccar[t][v];
+                Lt[rt][t][v] = x;
+                ccar[t][v] = __shfl(x, (lane & 48) | 15, 64);         // value of the last row = next column carry
+            }
+        if (g == 3) L.lastcol[ts][tb][16 * rt + c] = Lt[rt][3][3];    // column 63 of row 16 rt + c
+    }
+    if (c == 0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) *reinterpret_cast<floatx4*>(&L.lastrow[ts][tb][16 * t + 4 * g]) = ccar[t];
+    }
+}
+
+// After the wait, for the whole workgroup (every wave's local table in Lt): carries, two additions per pixel, store.
+template <int TR, int TC, bool STREAM>
+__device__ __forceinline__ void sat_fused_finish(const SatFusedArgs& p, SatFusedLds<TR, TC>& L,
+                                                 int sw, int bw, int wv, int lane, floatx4 (&Lt)[4][4]) {
+    using LT = SatFusedLds<TR, TC>;
+    constexpr int kWaves = LT::kWaves, kRH = LT::kRH, kRW = LT::kRW, kThreads = 64 * kWaves;
+    const int c = lane & 15, g = lane >> 4;
+    const int ts = wv / TC, tb = wv - ts * TC;
+    const int I0 = kRH * sw, J0 = kRW * bw;
+    const int tid = wv * 64 + lane;
+
+    // table lines of the regions to the left (RS) and above (CS): wave w takes lines w, w + kWaves, ...
+    {
+        float ar[kRH / 64], ac[kRW / 64];
+#pragma unroll
+        for (int k = 0; k < kRH / 64; ++k) ar[k] = 0.f;
+#pragma unroll
+        for (int k = 0; k < kRW / 64; ++k) ac[k] = 0.f;
+        for (int b2 = wv; b2 < bw; b2 += kWaves) {
+            const float* line = p.RS + (int64_t)b2 * p.Hr + I0;
+#pragma unroll
+            for (int k = 0; k < kRH / 64; ++k) ar[k] += ldf_agent(line + 64 * k + lane);
+        }
+        for (int s2 = wv; s2 < sw; s2 += kWaves) {
+            const float* line = p.CS + (int64_t)s2 * p.Wr + J0;
+#pragma unroll
+            for (int k = 0; k < kRW / 64; ++k) ac[k] += ldf_agent(line + 64 * k + lane);
+        }
+        float a = 0.f;
+        for (int i = tid; i < sw * bw; i += kThreads) {
+            const int s2 = i / bw, b2 = i - s2 * bw;
+            a += ldf_agent(p.TOT + (int64_t)s2 * p.nbw + b2);
+        }
+#pragma unroll
+        for (int k = 0; k < kRH / 64; ++k) L.u.part.r[wv][64 * k + lane] = ar[k];
+#pragma unroll
+        for (int k = 0; k < kRW / 64; ++k) L.u.part.c[wv][64 * k + lane] = ac[k];
+        a = wave_sum(a);
+        if (lane == 0) L.Apart[wv] = a;
+    }
+    __syncthreads();
+    if (tid < kRH) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v += L.u.part.r[w][tid];
+        L.Rc[tid] = v;
+    } else if (tid < kRH + kRW) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v += L.u.part.c[w][tid - kRH];
+        L.Cc[tid - kRH] = v;
+    }
+    if (tid == kThreads - 1) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v += L.Apart[w];
+        L.A = v;
+    }
+    __syncthreads();
+
+    // this wave's tile: R for row `lane`, C + A for column `lane`
+    float R = L.Rc[kSatTile * ts + lane];
+    for (int b2 = 0; b2 < tb; ++b2) R += L.lastcol[ts][b2][lane];
+    float C = L.Cc[kSatTile * tb + lane];
+    for (int t2 = 0; t2 < ts; ++t2) C += L.lastrow[t2][tb][lane];
+    float A = L.A;
+    for (int k = 0; k < tb; ++k) A += L.Cc[kSatTile * k + kSatTile - 1];      // above the region, tile columns to the left
+    for (int k = 0; k < ts; ++k) A += L.Rc[kSatTile * k + kSatTile - 1];      // left of the region, tile rows above
+    for (int t2 = 0; t2 < ts; ++t2)
+        for (int b2 = 0; b2 < tb; ++b2) A += L.lastrow[t2][b2][kSatTile - 1]; // inside the region, tiles above-left
+    L.u.term.row[wv][lane] = R;                           // (the parts were last read before the barrier above)
+    L.u.term.col[wv][lane] = C + A;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    SAT_STAMP(p.sync, sw * p.nbw + bw, 4);
+
+    const int y0 = I0 + kSatTile * ts, x0 = J0 + kSatTile * tb;
+    const bool full = (y0 + kSatTile <= p.H) && (x0 + kSatTile <= p.W);
+    if (y0 >= p.H || x0 >= p.W) return;                   // tile outside the image: nothing to store (no barrier follows)
+    floatx4 ct[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) ct[t] = *reinterpret_cast<const floatx4*>(&L.u.term.col[wv][16 * t + 4 * g]);
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+        const float r = L.u.term.row[wv][16 * rt + c];
+        floatx4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[t][v] = Lt[rt][t][v] + (r + ct[t][v]);
+        if (full) {
+            store_rows_via_lds<4, STREAM>(L.patch[wv], p.out + (int64_t)(y0 + 16 * rt) * p.out_pitch + x0,
+                                          (uint32_t)p.out_pitch, acc, lane);
+        } else {
+            const int y = y0 + 16 * rt + c;
+            if (y < p.H) {
+                float* orow = p.out + (int64_t)y * p.out_pitch;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int xo = x0 + 16 * t + 4 * g;
+                    if (xo < p.W) store4_mask(orow, xo, p.W, acc[t]);
+                }
+            }
+        }
+    }
+}
+
+extern __shared__ __attribute__((aligned(16))) unsigned char s_sat_fused_lds[];
+
+template <int TR, int TC, bool STREAM>
+__global__ void __launch_bounds__(64 * TR * TC) sat_fused_kernel(SatFusedArgs p) {
+    using LT = SatFusedLds<TR, TC>;
+    constexpr int kWaves = LT::kWaves, kRH = LT::kRH, kRW = LT::kRW;
+    LT& L = *reinterpret_cast<LT*>(s_sat_fused_lds);
+    const int nwg = p.nsw * p.nbw;
+    const int wg = blockIdx.x;
+    SatSync* S = p.sync;
+
+    // The first turn of this loop is the workgroup's own region (local tables, publish, arrive, wait,
+    // finish).  Further turns run only in a finisher, on regions whose workgroups stopped waiting
+    // (reload, local tables, finish).  `region` and `own` are the same in every lane.
+    int region = wg;
+    bool own = true;
+    SAT_STAMP(S, wg, 0);
+    for (;;) {
+        // Lane-derived values (LDS addresses, per-lane offsets, the 0/1 operand fragments) are made to
+        // look new in every turn: hoisted out of the loop they would stay live through it all, about
+        // ninety registers, and push the kernel over the 128 its 16 waves per compute unit allow.
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63;
+        const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int ts = wv / TC, tb = wv - ts * TC;
+        const int sw = region / p.nbw, bw = region - sw * p.nbw;
+        floatx4 Lt[4][4];
+        sat_fused_local<TR, TC>(p, L, kRH * sw + kSatTile * ts, kRW * bw + kSatTile * tb, ts, tb, lane, Lt);
+        __syncthreads();
+        unsigned late = 0u;
+        if (own) {
+            SAT_STAMP(S, wg, 1);
+            // publish the region's sums: the tiles' last columns added across a tile row, last rows down a tile column
+            if (tid < kRH) {
+                const int t2 = tid >> 6, y = tid & 63;
+                float v = 0.f;
+#pragma unroll
+                for (int b2 = 0; b2 < TC; ++b2) v += L.lastcol[t2][b2][y];
+                stf_agent(p.RS + (int64_t)bw * p.Hr + kRH * sw + tid, v);
+            } else if (tid < kRH + kRW) {
+                const int x = tid - kRH, b2 = x >> 6;
+                float v = 0.f;
+#pragma unroll
+                for (int t2 = 0; t2 < TR; ++t2) v += L.lastrow[t2][b2][x & 63];
+                stf_agent(p.CS + (int64_t)sw * p.Wr + kRW * bw + x, v);
+            }
+            if (tid == 64 * kWaves - 1) {
+                float v = 0.f;
+#pragma unroll
+                for (int t2 = 0; t2 < TR; ++t2)
+#pragma unroll
+                    for (int b2 = 0; b2 < TC; ++b2) v += L.lastrow[t2][b2][kSatTile - 1];
+                stf_agent(p.TOT + wg, v);
+            }
+            stores_done();
+            __syncthreads();
+            SAT_STAMP(S, wg, 2);
+            // arrive, then wait (bounded) for the others
+            if (tid == 0) {
+                const int nleaf = nwg < SatSync::kLeaves ? nwg : SatSync::kLeaves;
+                const int lf = wg % nleaf;
+                const int leaf_target = (nwg - lf + nleaf - 1) / nleaf;
+                const unsigned old = __hip_atomic_fetch_add(&S->leaf[SatSync::kLine * lf], 1u, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                if ((int)old + 1 == leaf_target) {
+                    const unsigned r = __hip_atomic_fetch_add(&S->root[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((int)r + 1 == nleaf) {
+#pragma unroll
+                        for (int i = 0; i < SatSync::kGo; ++i) st_agent(&S->go[SatSync::kLine * i], 1u);
+                    }
+                }
+                const unsigned* mygo = &S->go[SatSync::kLine * (wg & (SatSync::kGo - 1))];
+                int state = 1;                            // 1 passed, 0 leave
+                int polls = 0;
+                while (ld_agent(mygo) == 0u) {
+                    if (++polls > p.wait_limit) { state = 0; break; }
+                    __builtin_amdgcn_s_sleep(HB_SAT_POLL_SLEEP);
+                }
+                if (state == 0) {                         // stop waiting: hand the region to a finisher
+                    st_agent(&S->todo[wg], 1u);
+                    st_agent(&S->late[0], 1u);
+                    stores_done();
+                    if (ld_agent(mygo) != 0u) {           // the count completed meanwhile: finish it here after all
+                        unsigned expect = 1u;             // (a finisher may have claimed it too: both write the same values)
+                        __hip_atomic_compare_exchange_strong(&S->todo[wg], &expect, 2u, __ATOMIC_RELAXED,
+                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        state = 1;
+                    }
+                }
+                L.ctl = state;
+            }
+            __syncthreads();
+            if (L.ctl == 0) return;
+            if (tid == 0) late = ld_agent(&S->late[0]);   // in flight during the finish step
+            SAT_STAMP(S, wg, 3);
+        }
+
+        sat_fused_finish<TR, TC, STREAM>(p, L, sw, bw, wv, lane, Lt);
+
+        __syncthreads();
+        if (own) {
+            SAT_STAMP(S, wg, 5);
+            if (tid == 0) L.ctl = (int)late;
+            __syncthreads();
+            if (__builtin_amdgcn_readfirstlane(L.ctl) == 0) return;   // nobody stopped waiting: done
+            own = false;
+            __syncthreads();
+        }
+        // finisher duty: wave 0 looks for a marked region and claims it
+        if (tid < 64) {
+            int found = -1;
+            for (int r0 = 0; r0 < nwg && found < 0; r0 += 64) {
+                const int r = r0 + lane;
+                const bool marked = r < nwg && ld_agent(&S->todo[r]) == 1u;
+                unsigned long long m = __ballot(marked);
+                while (m && found < 0) {
+                    const int cand = r0 + __builtin_ctzll(m);
+                    m &= m - 1;
+                    int won = 0;
+                    if (lane == 0) {
+                        unsigned expect = 1u;
+                        won = __hip_atomic_compare_exchange_strong(&S->todo[cand], &expect, 2u, __ATOMIC_RELAXED,
+                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? 1 : 0;
+                    }
+                    if (__shfl(won, 0, 64)) found = cand;
+                }
+            }
+            if (lane == 0) L.ctl = found;
+        }
+        __syncthreads();
+        region = __builtin_amdgcn_readfirstlane(L.ctl);
+        if (region < 0) return;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Vector-ALU twin of passes 1 and 3: the tile goes through LDS, threads add.
 __global__ void __launch_bounds__(256) sat_sums_valu_kernel(SatArgs p) {
     __shared__ float s_px[kSatTile][kSatTile + 1];
@@ -379,6 +801,26 @@ static size_t sat_workspace_floats(int H, int W) {
     return 2 * (nb * ns * kSatTile) + 2 * (ns * nb * kSatTile) + 2 * ns * nb;   // rs, rcarry, cs, ccarry, tot, es
 }
 
+// Region shapes of the one-launch kernel: 2 x 2 tiles (128 x 128 pixels, 256 threads) for small
+// images, 4 x 4 tiles (256 x 256 pixels, 1024 threads: fewer arrivals at the grid-wide wait, fewer
+// table lines per region) once that still gives 128 regions or more.  0: more regions than the
+// wait's bookkeeping holds; the three-launch path serves those.
+static int sat_fused_shape(int H, int W) {
+    const int64_t ra = (int64_t)ceil_div(H, 128) * ceil_div(W, 128), rb = (int64_t)ceil_div(H, 256) * ceil_div(W, 256);
+    if (rb >= 128) return rb <= SatSync::kMaxRegions ? 4 : 0;
+    return ra <= SatSync::kMaxRegions ? 2 : 4;            // rb < 128 here
+}
+// floats of the one-launch tables (RS, CS, TOT), rounded up to 64, for region edge `t` tiles
+static size_t sat_fused_table_floats(int H, int W, int t) {
+    const size_t e = (size_t)kSatTile * t, nsw = (size_t)ceil_div(H, (int)e), nbw = (size_t)ceil_div(W, (int)e);
+    const size_t n = nbw * nsw * e + nsw * nbw * e + nsw * nbw;
+    return (n + 63) & ~(size_t)63;
+}
+static size_t sat_fused_bytes(int H, int W) {
+    const int t = sat_fused_shape(H, W);
+    return t ? sat_fused_table_floats(H, W, t) * sizeof(float) + sizeof(SatSync) : 0;
+}
+
 static hb_status sat_prepare(SatArgs& a, const hb_half* in, float* out, int H, int W,
                              int64_t in_pitch, int64_t out_pitch, void* ws, size_t ws_bytes) {
     hb_status st = check_image(in, out, H, W, in_pitch, out_pitch);
@@ -404,11 +846,32 @@ static hb_status sat_prepare(SatArgs& a, const hb_half* in, float* out, int H, i
     return HB_OK;
 }
 
+// The one-launch tables follow the three-launch tables in the workspace (both sized by hb_sat2d_workspace_size).
+static void sat_prepare_fused(SatFusedArgs& f, const SatArgs& a, void* ws, int t, int wait_limit) {
+    const int e = kSatTile * t;
+    f.in = a.in;
+    f.out = a.out;
+    f.H = a.H;
+    f.W = a.W;
+    f.in_pitch = a.in_pitch;
+    f.out_pitch = a.out_pitch;
+    f.nsw = ceil_div(a.H, e);
+    f.nbw = ceil_div(a.W, e);
+    f.Hr = f.nsw * e;
+    f.Wr = f.nbw * e;
+    float* base = reinterpret_cast<float*>(ws) + ((sat_workspace_floats(a.H, a.W) + 63) & ~(size_t)63);
+    f.RS = base;
+    f.CS = f.RS + (size_t)f.nbw * f.Hr;
+    f.TOT = f.CS + (size_t)f.nsw * f.Wr;
+    f.sync = reinterpret_cast<SatSync*>(base + sat_fused_table_floats(a.H, a.W, t));
+    f.wait_limit = wait_limit;
+}
+
 }  // namespace hb
 
 extern "C" size_t hb_sat2d_workspace_size(int H, int W) {
     if (H < 1 || W < 1) return 0;
-    return hb::sat_workspace_floats(H, W) * sizeof(float);
+    return ((hb::sat_workspace_floats(H, W) + 63) & ~(size_t)63) * sizeof(float) + hb::sat_fused_bytes(H, W);
 }
 
 // Scratch of hb_sat2d_noalloc: the carry tables live in this array instead of a caller's workspace.
@@ -418,18 +881,73 @@ static __device__ __align__(256) unsigned char scratch[HB_SAT2D_NOALLOC_SCRATCH_
 
 namespace hb {
 
-static hb_status sat_launch_mfma(const SatArgs& a, hipStream_t st) {
+// Polls a workgroup of the one-launch kernel spends in its grid-wide wait before it hands its region
+// to a finisher (a poll is a quarter of a microsecond of sleep plus one memory round trip).
+constexpr int kSatDefaultWaitLimit = 1 << 14;
+static std::atomic<int> g_sat_wait_limit{kSatDefaultWaitLimit};
+
+// Workgroups of each one-launch kernel shape the current device holds at once (0: query failed).
+struct SatCapacity { int shape2 = -1, shape4 = -1; };
+static SatCapacity g_sat_capacity[kMaxDevices];
+static std::mutex g_sat_mu;
+
+template <int T, bool STREAM>
+static hb_status sat_fused_launch(const SatFusedArgs& f, hipStream_t st) {
+    auto kernel = sat_fused_kernel<T, T, STREAM>;
+    const size_t lds = sizeof(SatFusedLds<T, T>);
+    hb_status s = allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds);
+    if (s != HB_OK) return s;
+    hipLaunchKernelGGL(sat_sync_clear_kernel, dim3(1), dim3(256), 0, st, f.sync);
+    hipLaunchKernelGGL(kernel, dim3(f.nsw * f.nbw), dim3(64 * T * T), lds, st, f);
+    return launch_status();
+}
+
+template <int T>
+static int sat_fused_capacity_query() {
+    auto kernel = sat_fused_kernel<T, T, true>;
+    const size_t lds = sizeof(SatFusedLds<T, T>);
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds) != HB_OK) return 0;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * T * T, lds) != hipSuccess) return 0;
+    const int ncu = device_num_cu();
+    return ncu > 0 && per_cu > 0 ? per_cu * ncu : 0;
+}
+
+// 0 when the grid of shape `t` cannot be resident at once on the current device.
+static int sat_fused_capacity(int t) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    std::lock_guard<std::mutex> lock(g_sat_mu);
+    SatCapacity& c = g_sat_capacity[dev];
+    if (t == 2) {
+        if (c.shape2 < 0) c.shape2 = sat_fused_capacity_query<2>();
+        return c.shape2;
+    }
+    if (c.shape4 < 0) c.shape4 = sat_fused_capacity_query<4>();
+    return c.shape4;
+}
+
+static hb_status sat_launch_mfma(const SatArgs& a, void* ws, hipStream_t st) {
+    const bool stream_stores = (int64_t)a.H * a.W * 4 <= kStreamStoreMaxBytes;
+    const int t = sat_fused_shape(a.H, a.W);
+    if (t) {
+        SatFusedArgs f;
+        sat_prepare_fused(f, a, ws, t, g_sat_wait_limit.load());
+        if (f.nsw * f.nbw <= sat_fused_capacity(t)) {
+            if (t == 2) return stream_stores ? sat_fused_launch<2, true>(f, st) : sat_fused_launch<2, false>(f, st);
+            return stream_stores ? sat_fused_launch<4, true>(f, st) : sat_fused_launch<4, false>(f, st);
+        }
+    }
     const int ntiles = a.nb * a.ns;
     hipLaunchKernelGGL(sat_sums_mfma_kernel, dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(sat_scan_kernel, dim3(ceil_div(a.Hs + a.Ws + a.nb, 4)), dim3(256), 0, st, a);
-    if ((int64_t)a.H * a.W * 4 <= kStreamStoreMaxBytes)
+    if (stream_stores)
         hipLaunchKernelGGL((sat_apply_mfma_kernel<true>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL((sat_apply_mfma_kernel<false>), dim3(ceil_div(ntiles, 4)), dim3(256), 0, st, a);
     return launch_status();
 }
 
-constexpr int kMaxDevices = 64;
 static void* g_scratch_ptr[kMaxDevices];
 static std::mutex g_scratch_mu;
 
@@ -449,6 +967,12 @@ static hb_status sat_scratch_address(void** ptr) {
 
 }  // namespace hb
 
+extern "C" int hb_sat2d_set_wait_limit(int polls) {
+    const int prev = hb::g_sat_wait_limit.load();
+    hb::g_sat_wait_limit.store(polls > 0 ? polls : (polls == 0 ? hb::kSatDefaultWaitLimit : 0));
+    return prev;
+}
+
 extern "C" hb_status hb_sat2d(const hb_half* in, float* out, int H, int W,
                               int64_t in_pitch, int64_t out_pitch,
                               void* workspace, size_t workspace_bytes, hb_stream stream) {
@@ -456,7 +980,7 @@ extern "C" hb_status hb_sat2d(const hb_half* in, float* out, int H, int W,
     SatArgs a;
     hb_status s = sat_prepare(a, in, out, H, W, in_pitch, out_pitch, workspace, workspace_bytes);
     if (s != HB_OK) return s;
-    return sat_launch_mfma(a, reinterpret_cast<hipStream_t>(stream));
+    return sat_launch_mfma(a, workspace, reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" hb_status hb_sat2d_noalloc(const hb_half* in, float* out, int H, int W,
@@ -471,7 +995,7 @@ extern "C" hb_status hb_sat2d_noalloc(const hb_half* in, float* out, int H, int 
     SatArgs a;
     s = sat_prepare(a, in, out, H, W, in_pitch, out_pitch, ws, (size_t)HB_SAT2D_NOALLOC_SCRATCH_BYTES);
     if (s != HB_OK) return s;
-    return sat_launch_mfma(a, reinterpret_cast<hipStream_t>(stream));
+    return sat_launch_mfma(a, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" hb_status hb_sat2d_valu(const hb_half* in, float* out, int H, int W,

@@ -34,7 +34,7 @@ SYMBOLS = [
     "hb_iir2_workspace_size", "hb_iir2", "hb_iir2_valu",
     "hb_dct_denoise_workspace_size", "hb_dct_denoise", "hb_dct_denoise_valu",
     "hb_sepblur", "hb_sepblur_valu",
-    "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu", "hb_sat2d_noalloc",
+    "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu", "hb_sat2d_noalloc", "hb_sat2d_set_wait_limit",
     "hb_conv3x3", "hb_conv3x3_valu",
     "hb_pyr_level", "hb_pyr_level_valu",
     "hb_copy_f16_f32", "hb_mfma_probe",
@@ -103,6 +103,8 @@ def load() -> ctypes.CDLL:
     L.hb_dct_denoise_workspace_size.restype = ctypes.c_size_t
     L.hb_sat2d_noalloc.argtypes = [vp, vp, I, I, I64, I64, vp]
     L.hb_sat2d_noalloc.restype = I
+    L.hb_sat2d_set_wait_limit.argtypes = [I]
+    L.hb_sat2d_set_wait_limit.restype = I
     L.hb_sat2d_workspace_size.argtypes = [I, I]
     L.hb_sat2d_workspace_size.restype = ctypes.c_size_t
     _lib = L
@@ -345,6 +347,10 @@ def hb_sat2d_valu(inp, out, workspace):
 
 
 HB_SAT2D_NOALLOC_SCRATCH_BYTES = 5 << 20
+
+
+def hb_sat2d_set_wait_limit(polls: int) -> int:
+    return int(load().hb_sat2d_set_wait_limit(int(polls)))
 
 
 def hb_sat2d_noalloc(inp, out):

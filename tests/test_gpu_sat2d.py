@@ -81,3 +81,26 @@ def test_sat_full_benchmark_size(orc):
     got, _ = run("hb_sat2d", bits)
     ref = np.cumsum(np.cumsum(synth.f16_bits_to_f64(bits), axis=0), axis=1)
     assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("H,W", [(300, 520), (1000, 1500), (4096, 4096)])
+def test_sat_finisher_path(orc, H, W):
+    """The one-launch kernel with its grid-wide wait cut to nothing from the host: workgroups that do
+    not find the wait already over hand their regions to a finisher, which reloads and finishes them.
+    Every kernel still exits by itself and the table is the same (0/1 image: bit-exact)."""
+    from paper_2512_02371_amd import hb
+    bits = synth.binary01_f16(7900 + H, (H, W))
+    ref = np.cumsum(np.cumsum(synth.f16_bits_to_f64(bits), axis=0), axis=1)
+    hb.hb_sat2d_set_wait_limit(-1)
+    try:
+        got, _ = run("hb_sat2d", bits)
+        assert np.array_equal(got.astype(np.float64), ref)
+        got, _ = run("hb_sat2d", bits)                    # and again on the used state
+        assert np.array_equal(got.astype(np.float64), ref)
+        hb.hb_sat2d_set_wait_limit(3)                     # a few polls: a mix of both paths
+        got, _ = run("hb_sat2d", bits)
+        assert np.array_equal(got.astype(np.float64), ref)
+    finally:
+        hb.hb_sat2d_set_wait_limit(0)
+    got, _ = run("hb_sat2d", bits)
+    assert np.array_equal(got.astype(np.float64), ref)
