@@ -4,22 +4,30 @@
 One *step* runs every stage once at its benchmark configuration (hb_fir1d 256x256/8 taps,
 hb_sepblur 4096x4096/16-tap Gaussian, hb_sat2d 4096x4096, hb_conv3x3 1x1024x1024x64->64,
 hb_pyr_level 8192x8192) on seeded synthetic inputs that are already resident in HBM.
-Buffers rotate between steps so that no input or output is reused before more than the
-256 MB memory-side cache has gone past.
+Buffers rotate between launches so that no input is reused before more than the 256 MB
+memory-side cache has gone past (the outputs are written with streaming stores).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--variant mfma|valu] [--no-cpu] [--no-extra]
 
-prints ONE JSON line: aggregate Gpixels/s of the step (wall clock over the K timed steps), per-stage
-Gpixels/s with each stage's roofline fraction (HIP events around every stage, in an instrumented
-pass before the timed steps), the roofline object of the stage that takes the longest (HIP events
-around that stage inside the timed steps), and the fp64 oracle timed on the host cores
-(cpu_baseline).
+prints ONE JSON line:
+  value / ms_per_step   wall clock over exactly K timed steps (after W warm-up steps);
+  step_stats            median / min / max over five more batches of K steps (HIP events);
+  stages                per stage: median / min / max per launch over five batches of 50 back-to-back
+                        launches between one pair of HIP events (rotating buffers), its roofline
+                        fraction from the median, and the HBM traffic measured for it (profiles/);
+  roofline              the stage that takes the longest: HIP events around its launch inside the
+                        timed steps (and the batched figure next to it);
+  supplementary         the tuned fp16 -> fp32 copy as the practical ceiling, the stacked FIR, a graph
+                        replay of the step, and the paper's other case studies, each with its own
+                        roofline object;
+  cpu_baseline          the fp64 oracle timed on the host cores.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -30,18 +38,27 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense f16 MFMA
+MFMA_F32_PEAK_TFLOPS = 157.3   # fp32 on the matrix units
 
 STAGES = ["fir1d", "sepblur", "sat2d", "conv3x3", "pyr_level"]
-
-# HBM bytes per launch (read + written) of the MFMA kernels at the benchmark configurations, from
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this program scaled by its calibration copy (the
-# summaries and commands are under profiles/).
+BATCHES, PER_BATCH = 5, 50
 MIB = 1 << 20
-MEASURED_TRAFFIC_BYTES = {
-    "pyr_level": int((143.47 + 256.27) * MIB),
-    "conv3x3": int((138.18 + 128.00) * MIB),
-    "sepblur": int((33.75 + 64.00) * MIB),
-}
+
+
+def measured_traffic(fname):
+    """HBM bytes per launch {name: (read, written)} from a counter summary under profiles/ (lines
+    `traffic <name> read_MiB <r> write_MiB <w>`, written by the FETCH_SIZE / WRITE_SIZE runs whose
+    commands the file states).  Empty when the file is absent: the figure is then reported as null."""
+    out = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", fname)) as f:
+            for line in f:
+                m = re.match(r"traffic\s+(\S+)\s+read_MiB\s+([0-9.]+)\s+write_MiB\s+([0-9.]+)", line)
+                if m:
+                    out[m.group(1)] = (float(m.group(2)) * MIB, float(m.group(3)) * MIB)
+    except OSError:
+        pass
+    return out
 
 
 def stage_work(cfg):
@@ -63,6 +80,29 @@ def stage_work(cfg):
     return px, nbytes, flops
 
 
+def stats(v):
+    v = sorted(v)
+    return {"median": float(np.median(v)), "min": float(v[0]), "max": float(v[-1])}
+
+
+def roofline_object(ms, nbytes, flops, mfma_peak=MFMA_F16_PEAK_TFLOPS, traffic=None, force=None):
+    """The roofline that binds at the peaks: memory time against matrix time of the ALGORITHMIC work
+    (`force` names it for the five stages, whose governing roofline the benchmark definition fixes:
+    the conv stage sits at the ridge, 30.9 us of products against 33.6 us of traffic, and counts as
+    a matrix-unit stage)."""
+    t_mem, t_mat = nbytes / (HBM_PEAK_GBS * 1e9), flops / (mfma_peak * 1e12)
+    if force == "mfma" or (force is None and t_mat > t_mem):
+        ach = flops / ms / 1e9
+        o = {"bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s", "frac": ach / mfma_peak}
+    else:
+        ach = nbytes / ms / 1e6
+        o = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
+    o["algorithmic_bytes"] = int(nbytes)
+    o["algorithmic_flops"] = int(flops)
+    o["traffic"] = None if traffic is None else int(traffic[0] + traffic[1])
+    return o
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,7 +110,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs (stacked FIR, long-tap FIR, 2-D convolution, 2x resampling, Lanczos resize, recursive filter, DCT denoise)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -84,12 +124,32 @@ def main():
     torch.cuda.set_device(dev)
     C = synth.CONFIGS
     sfx = "" if args.variant == "mfma" else "_valu"
+    traffic5 = measured_traffic("bench_five_stages_hbm_traffic.txt") if sfx == "" else {}
+    traffic_x = measured_traffic("bench_supplementary_hbm_traffic.txt") if sfx == "" else {}
 
     def up(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.float16)).to(dev)
 
-    # ---- seeded inputs, several buffer sets per stage (rotated per step) -----------------
-    t0 = time.time()
+    def event():
+        return torch.cuda.Event(enable_timing=True)
+
+    def batched(fn, nsets, per_batch=PER_BATCH, batches=BATCHES, warm=10):
+        """ms per launch: `batches` times `per_batch` back-to-back launches between two HIP events."""
+        for i in range(warm):
+            fn(i % nsets)
+        torch.cuda.synchronize()
+        ms = []
+        for b in range(batches):
+            e0, e1 = event(), event()
+            e0.record()
+            for i in range(per_batch):
+                fn((b * per_batch + i) % nsets)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1) / per_batch)
+        return stats(ms)
+
+    # ---- seeded inputs, several buffer sets per stage (rotated per launch) -----------------
     fir_taps = synth.random_taps_f16(C["fir1d"]["seed_taps"], 8)
     gau_taps = synth.gaussian_taps_f16(16, 3.0)
     host = {
@@ -100,17 +160,16 @@ def main():
         "conv3x3_w": synth.normal_f16(C["conv3x3"]["seed_w"], (3, 3, 64, 64), 1.0 / 24.0),
         "pyr_level": synth.uniform01_f16(C["pyr_level"]["seed_img"], (8192, 8192)),
     }
-    nsets = {"fir1d": 4, "sepblur": 4, "sat2d": 4, "conv3x3": 2, "pyr_level": 2}
+    # inputs of one stage alone exceed the 256 MB memory-side cache between two uses of a buffer
+    nsets = {"fir1d": 4, "sepblur": 10, "sat2d": 10, "conv3x3": 3, "pyr_level": 3}
     ins, outs = {}, {}
     for st in STAGES:
         base = up(host[st])
         ins[st] = [base] + [base.clone() for _ in range(nsets[st] - 1)]
         odt = torch.float16 if st == "conv3x3" else torch.float32
-        oshape = base.shape
-        outs[st] = [torch.empty(oshape, dtype=odt, device=dev) for _ in range(nsets[st])]
+        outs[st] = [torch.empty(base.shape, dtype=odt, device=dev) for _ in range(nsets[st])]
     w_dev = up(host["conv3x3_w"])
     sat_ws = torch.empty(hb.hb_sat2d_workspace_size(4096, 4096), dtype=torch.uint8, device=dev)
-    gen_s = time.time() - t0
 
     calls = {
         "fir1d": lambda i: getattr(hb, "hb_fir1d" + sfx)(ins["fir1d"][i], outs["fir1d"][i], fir_taps, 3),
@@ -121,19 +180,13 @@ def main():
         "pyr_level": lambda i: getattr(hb, "hb_pyr_level" + sfx)(ins["pyr_level"][i], outs["pyr_level"][i], None),
     }
 
-    def step(k, events=None, only=None):
+    def step(k, ev=None, only=None):
         for st in STAGES:
-            i = k % nsets[st]
-            rec = events is not None and (only is None or only == st)
-            if rec:
-                events[st][0].record()
-            calls[st](i)
-            if rec:
-                events[st][1].record()
-
-    def new_events(n):
-        return [{st: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for st in STAGES}
-                for _ in range(n)]
+            if ev is not None and only == st:
+                ev[0].record()
+            calls[st](k % nsets[st])
+            if ev is not None and only == st:
+                ev[1].record()
 
     # One plain copy of known size (32 MiB read, 64 MiB written), untimed: a counter run of this
     # program reads its own scale for FETCH_SIZE / WRITE_SIZE from this dispatch.
@@ -142,48 +195,45 @@ def main():
         step(k)
     torch.cuda.synchronize()
 
-    # Instrumented pass (untimed): HIP events around every stage.  Event records cost about 3 us of
-    # GPU idle time each, so the timed steps below carry them around the longest stage only.
-    nprobe = max(1, min(args.steps, 10))
-    evp = new_events(nprobe)
-    for k in range(nprobe):
-        step(args.warmup + k, evp[k])
-    torch.cuda.synchronize()
-    stage_ms = {st: float(np.mean([e[st][0].elapsed_time(e[st][1]) for e in evp])) for st in STAGES}
-    dom = max(STAGES, key=lambda s: stage_ms[s])
+    # ---- per stage: batches of back-to-back launches (before the timed steps, untimed region) ----
+    per_batch = PER_BATCH if sfx == "" else 10
+    stage_ms = {st: batched(calls[st], nsets[st], per_batch=per_batch) for st in STAGES}
+    dom = max(STAGES, key=lambda s: stage_ms[s]["median"])
 
-    ev = new_events(args.steps)
+    # ---- the timed region: exactly K steps, wall clock; HIP events around the longest stage only ----
+    evs = [(event(), event()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(args.warmup + nprobe + k, ev[k], only=dom)
+        step(args.warmup + k, evs[k], only=dom)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    dom_ms = float(np.mean([e[dom][0].elapsed_time(e[dom][1]) for e in ev]))   # inside the timed steps
+    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))      # inside the timed steps
     total_px = sum(stage_work(st)[0] for st in STAGES)
+
+    # ---- five more batches of K steps for the spread ----
+    step_ms = []
+    for b in range(BATCHES):
+        e0, e1 = event(), event()
+        e0.record()
+        for k in range(args.steps):
+            step(b * args.steps + k)
+        e1.record()
+        torch.cuda.synchronize()
+        step_ms.append(e0.elapsed_time(e1) / args.steps)
 
     stages = {}
     for st in STAGES:
         px, nbytes, flops = stage_work(st)
-        ms = stage_ms[st]
-        gbs = nbytes / ms / 1e6
-        tfl = flops / ms / 1e9
-        bound = "mfma" if st == "conv3x3" else "hbm"
-        stages[st] = {
-            "gpixels_per_s": px / ms / 1e6, "ms": ms, "bound": bound,
-            "achieved": tfl if bound == "mfma" else gbs,
-            "peak": MFMA_F16_PEAK_TFLOPS if bound == "mfma" else HBM_PEAK_GBS,
-            "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
-            "frac": (tfl / MFMA_F16_PEAK_TFLOPS) if bound == "mfma" else (gbs / HBM_PEAK_GBS),
-        }
-    # roofline of the longest stage, from its HIP-event time inside the timed steps
+        ms = stage_ms[st]["median"]
+        r = roofline_object(ms, nbytes, flops, traffic=traffic5.get(st), force="mfma" if st == "conv3x3" else "hbm")
+        stages[st] = dict({"gpixels_per_s": px / ms / 1e6, "ms": ms, "ms_min": stage_ms[st]["min"],
+                           "ms_max": stage_ms[st]["max"], "launches_per_batch": per_batch, "batches": BATCHES}, **r)
     _, dbytes, dflops = stage_work(dom)
-    dbound = stages[dom]["bound"]
-    dach = (dflops / dom_ms / 1e9) if dbound == "mfma" else (dbytes / dom_ms / 1e6)
-    roofline = {"bound": dbound, "achieved": dach, "peak": stages[dom]["peak"], "unit": stages[dom]["unit"],
-                "frac": dach / stages[dom]["peak"], "kernel": "hb_" + dom + sfx, "ms": dom_ms,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if sfx == "" else None}
+    roofline = roofline_object(dom_ms, dbytes, dflops, traffic=traffic5.get(dom), force="mfma" if dom == "conv3x3" else "hbm")
+    roofline.update({"kernel": "hb_" + dom + sfx, "ms": dom_ms, "ms_batched_median": stage_ms[dom]["median"],
+                     "timing": "HIP events around the launch inside the timed steps (mean over the steps)"})
 
     out = {
         "metric": "Gpixels/s per stage (fp16 in, fp32 acc) + % of HBM / MFMA roofline",
@@ -198,185 +248,146 @@ def main():
                                "fir1d 256x256 T8, sepblur 4096x4096 T16 sigma3, sat2d 4096x4096, "
                                "conv3x3 1x1024x1024x64->64, pyr_level 8192x8192",
                    "variant": args.variant, "pixels_per_step": total_px},
+        "step_stats": dict(stats(step_ms), unit="ms", batches=BATCHES, steps_per_batch=args.steps),
         "stages": stages,
         "roofline": roofline,
     }
 
     if not args.no_extra:
-        # Supplementary (outside the timed step).  First the same step replayed from a HIP graph (four
-        # steps per graph, so that the buffer sets rotate as in the timed loop): what the launch gaps
-        # between the seven kernels of a step cost.  The library allocates nothing, synchronises
-        # nothing and issues no memset, so its launches can be captured.
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for k in range(4):
-                step(k)
-        graph.replay()
-        torch.cuda.synchronize()
-        nrep = max(1, args.steps // 4)
-        t0 = time.perf_counter()
-        for _ in range(nrep):
-            graph.replay()
-        torch.cuda.synchronize()
-        gms = (time.perf_counter() - t0) * 1e3 / (4 * nrep)
-        graph_line = {
-            "ms_per_step": gms, "gpixels_per_s": total_px / gms / 1e6, "steps_per_graph": 4,
-            "eager_over_graph": ms_per_step / gms}
-        del graph
-        # The FIR stage on 1024 of its 256 x 256 images stacked into one 262144 x 256 image, where its
-        # launch latency no longer hides its bandwidth.
-        del ins["pyr_level"], outs["pyr_level"], ins["conv3x3"], outs["conv3x3"]
-        torch.cuda.empty_cache()
-        Hs = 256 * 1024
-        sx = [up(host["fir1d"]).repeat(1024, 1) for _ in range(2)]
-        so = [torch.empty((Hs, 256), dtype=torch.float32, device=dev) for _ in range(2)]
-        fir = getattr(hb, "hb_fir1d" + sfx)
-        for i in range(4):
-            fir(sx[i % 2], so[i % 2], fir_taps, 3)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(10):
-            fir(sx[i % 2], so[i % 2], fir_taps, 3)
-        e1.record()
-        torch.cuda.synchronize()
-        sms = e0.elapsed_time(e1) / 10
-        out["supplementary"] = {"fir1d_stacked_262144x256": {
-            "ms": sms, "gpixels_per_s": Hs * 256 / sms / 1e6, "achieved": Hs * 256 * 6 / sms / 1e6,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": Hs * 256 * 6 / sms / 1e6 / HBM_PEAK_GBS}}
-        out["supplementary"]["five_stage_step_graph_replay"] = graph_line
-        # ... and the large-tap regime of the paper's 1-D study (Sec. V-A): 64, 128 and 256 taps on the
-        # blur stage's 4096 x 4096 image, matrix-unit kernel and vector-ALU twin.
-        del sx, so
-        torch.cuda.empty_cache()
-        lx, lo = ins["sepblur"], outs["sepblur"]
-        npx = 4096 * 4096
-        for ntaps in (64, 128, 256):
-            long_taps = synth.random_taps_f16(2000 + ntaps, ntaps)
-
-            def timed(fn, iters):
-                for i in range(2):
-                    fn(lx[i % 4], lo[i % 4], long_taps, (ntaps - 1) // 2)
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a0.record()
-                for i in range(iters):
-                    fn(lx[i % 4], lo[i % 4], long_taps, (ntaps - 1) // 2)
-                a1.record()
-                torch.cuda.synchronize()
-                return a0.elapsed_time(a1) / iters
-            m_ms, v_ms = timed(hb.hb_fir1d, 10), timed(hb.hb_fir1d_valu, 3)
-            out["supplementary"]["fir1d_%dtaps_4096x4096" % ntaps] = {
-                "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
-                "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
-        # ... and the paper's 2-D study (Sec. V-A): non-separable k x k kernels, k = 16 and 32, on
-        # the same image.  tflops counts the definition's 2 k^2 flops per pixel, not the Toeplitz zeros.
-        for k in (16, 32):
-            k2d = synth.random_kernel2d_f16(2300 + k, k, k)
-
-            def timed2(fn, iters):
-                for i in range(2):
-                    fn(lx[i % 4], lo[i % 4], k2d, k // 2, k // 2)
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a0.record()
-                for i in range(iters):
-                    fn(lx[i % 4], lo[i % 4], k2d, k // 2, k // 2)
-                a1.record()
-                torch.cuda.synchronize()
-                return a0.elapsed_time(a1) / iters
-            m_ms, v_ms = timed2(hb.hb_conv2d, 10), timed2(hb.hb_conv2d_valu, 3)
-            out["supplementary"]["conv2d_%dx%d_4096x4096" % (k, k)] = {
-                "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
-                "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms,
-                "mfma_tflops": 2.0 * k * k * npx / m_ms / 1e9}
-        # ... and the paper's resampling study (Sec. V-B): 2x down (4096^2 -> 2048^2) and 2x up
-        # (2048^2 -> 4096^2) with k x k kernels.  Pixels are counted on the larger image.
-        half_out = [torch.empty((2048, 2048), dtype=torch.float32, device=dev) for _ in range(4)]
-        half_in = [t[:2048, :2048] for t in lx]              # row pitch 4096
-        for k in (16, 32):
-            k2d = synth.random_kernel2d_f16(2400 + k, k, k)
-            for name, src, dst, anc in (("down2", lx, half_out, k // 2), ("up2", half_in, lo, k // 4)):
-                def timed3(fn, iters):
-                    for i in range(2):
-                        fn(src[i % 4], dst[i % 4], k2d, anc, anc)
-                    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a0.record()
-                    for i in range(iters):
-                        fn(src[i % 4], dst[i % 4], k2d, anc, anc)
-                    a1.record()
-                    torch.cuda.synchronize()
-                    return a0.elapsed_time(a1) / iters
-                m_ms, v_ms = timed3(getattr(hb, "hb_" + name), 10), timed3(getattr(hb, "hb_" + name + "_valu"), 3)
-                out["supplementary"]["%s_%dx%d_4096x4096" % (name, k, k)] = {
-                    "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": npx / m_ms / 1e6,
-                    "valu_gpixels_per_s": npx / v_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
-        # ... and the paper's non-integer resize (Sec. V-C, Table II): a 2048 x 2048 RGB image (three
-        # planes) down to 143 / 245 / 450 / 921 squared with Lanczos-3 matrices built by the library.
-        del half_out, half_in
-        rgb = (torch.rand((3, 2048, 2048), device=dev)).half()
-        for n in (143, 245, 450, 921):
-            st_h, cf_h = hb.hb_lanczos3_matrix(2048, n)
-            st_d = torch.from_numpy(st_h).to(dev)
-            cf_d = torch.from_numpy(cf_h.view(np.int16)).to(dev).view(torch.float16)
-            ro = torch.empty((3, n, n), dtype=torch.float32, device=dev)
-            rws = torch.empty(hb.hb_resize_workspace_size(3, 2048, n), dtype=torch.uint8, device=dev)
-
-            def timed4(fn, iters):
-                for i in range(2):
-                    fn(rgb, ro, rws, st_d, cf_d, st_d, cf_d)
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a0.record()
-                for i in range(iters):
-                    fn(rgb, ro, rws, st_d, cf_d, st_d, cf_d)
-                a1.record()
-                torch.cuda.synchronize()
-                return a0.elapsed_time(a1) / iters
-            m_ms, v_ms = timed4(hb.hb_resize, 10), timed4(hb.hb_resize_valu, 3)
-            out["supplementary"]["resize_lanczos3_3x2048x2048_to_%d" % n] = {
-                "mfma_ms": m_ms, "valu_ms": v_ms, "band": int(cf_h.shape[1]),
-                "mfma_input_gpixels_per_s": 3 * 2048 * 2048 / m_ms / 1e6, "mfma_over_valu": v_ms / m_ms}
-        # ... and the paper's recursive filter (Sec. V-D): 2^21 stereo samples, a resonant second-order filter.
-        del rgb
-        aud = (torch.rand((2, 1 << 21), device=dev) * 2 - 1).half()
-        aout = torch.empty((2, 1 << 21), dtype=torch.float32, device=dev)
-        aws = torch.empty(hb.hb_iir2_workspace_size(2, 1 << 21), dtype=torch.uint8, device=dev)
-
-        def timed5(fn, iters):
-            for i in range(2):
-                fn(aud, aout, 1.6, -0.8, aws)
-            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a0.record()
-            for i in range(iters):
-                fn(aud, aout, 1.6, -0.8, aws)
-            a1.record()
-            torch.cuda.synchronize()
-            return a0.elapsed_time(a1) / iters
-        m_ms, v_ms = timed5(hb.hb_iir2, 10), timed5(hb.hb_iir2_valu, 3)
-        out["supplementary"]["iir2_2x2097152"] = {
-            "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gsamples_per_s": 2 * (1 << 21) / m_ms / 1e6,
-            "mfma_over_valu": v_ms / m_ms}
-        # ... and the paper's DCT-domain denoising (Sec. V-E): a one-megapixel three-channel image.
-        del aud, aout
-        dimg = torch.rand((3, 1024, 1024), device=dev).half()
-        dout = torch.empty((3, 1024, 1024), dtype=torch.float32, device=dev)
-        dws = torch.empty(hb.hb_dct_denoise_workspace_size(3, 1024, 1024), dtype=torch.uint8, device=dev)
-
-        def timed6(fn, iters):
-            for i in range(2):
-                fn(dimg, dout, 0.05, dws)
-            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a0.record()
-            for i in range(iters):
-                fn(dimg, dout, 0.05, dws)
-            a1.record()
-            torch.cuda.synchronize()
-            return a0.elapsed_time(a1) / iters
-        m_ms, v_ms = timed6(hb.hb_dct_denoise, 10), timed6(hb.hb_dct_denoise_valu, 3)
-        out["supplementary"]["dct_denoise_3x1024x1024"] = {
-            "mfma_ms": m_ms, "valu_ms": v_ms, "mfma_gpixels_per_s": 3 * 1024 * 1024 / m_ms / 1e6,
-            "mfma_over_valu": v_ms / m_ms}
-
+        out["supplementary"] = supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host,
+                                             fir_taps, total_px, ms_per_step, sfx, traffic_x)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)
     print(json.dumps(out))
+
+
+def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host, fir_taps, total_px,
+                  ms_per_step, sfx, traffic_x):
+    """Outside the timed step: the copy ceiling, the stacked FIR, the step from a graph, and the paper's other
+    case studies (matrix-unit kernel and vector-ALU twin), each with a roofline object of its ALGORITHMIC work
+    (input + output bytes once, the definition's multiply-adds; Sec. V-A's accounting)."""
+    sup = {}
+    lx, lo = ins["sepblur"], outs["sepblur"]
+    ns = len(lx)
+    npx = 4096 * 4096
+
+    def pair(name, mfn, vfn, nsets, nbytes, flops, px, mfma_peak=MFMA_F16_PEAK_TFLOPS, extra=None):
+        m = batched(mfn, nsets, per_batch=20)
+        v = batched(vfn, nsets, per_batch=5, batches=3, warm=2)
+        row = {"mfma_ms": m["median"], "mfma_ms_min": m["min"], "mfma_ms_max": m["max"], "valu_ms": v["median"],
+               "mfma_gpixels_per_s": px / m["median"] / 1e6, "valu_gpixels_per_s": px / v["median"] / 1e6,
+               "mfma_over_valu": v["median"] / m["median"],
+               "roofline": roofline_object(m["median"], nbytes, flops, mfma_peak, traffic_x.get(name))}
+        if extra:
+            row.update(extra)
+        sup[name] = row
+
+    # the practical ceiling of a 2 B in + 4 B out stream: the tuned copy at both image sizes
+    for size, bufs_in, bufs_out in ((4096, lx, lo), (8192, ins["pyr_level"], outs["pyr_level"])):
+        n = size * size
+        m = batched(lambda i: hb.hb_copy_f16_f32(bufs_in[i], bufs_out[i]), len(bufs_in))
+        sup["copy_ceiling_%dx%d" % (size, size)] = {
+            "ms": m["median"], "ms_min": m["min"], "ms_max": m["max"], "achieved": 6.0 * n / m["median"] / 1e6,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": 6.0 * n / m["median"] / 1e6 / HBM_PEAK_GBS}
+
+    # the same step replayed from a HIP graph (the library allocates nothing, synchronises nothing and issues
+    # no memset, so its launches can be captured)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for k in range(4):
+            step(k)
+    graph.replay()
+    torch.cuda.synchronize()
+    nrep = max(1, args.steps // 4)
+    t0 = time.perf_counter()
+    for _ in range(nrep):
+        graph.replay()
+    torch.cuda.synchronize()
+    gms = (time.perf_counter() - t0) * 1e3 / (4 * nrep)
+    sup["five_stage_step_graph_replay"] = {"ms_per_step": gms, "gpixels_per_s": total_px / gms / 1e6,
+                                           "steps_per_graph": 4, "eager_over_graph": ms_per_step / gms}
+    del graph
+    del ins["pyr_level"], outs["pyr_level"], ins["conv3x3"], outs["conv3x3"]
+    torch.cuda.empty_cache()
+
+    # the FIR stage on 1024 of its 256 x 256 images stacked into one 262144 x 256 image, where its launch
+    # latency no longer hides its bandwidth
+    Hs = 256 * 1024
+    sx = [up(host["fir1d"]).repeat(1024, 1) for _ in range(3)]
+    so = [torch.empty((Hs, 256), dtype=torch.float32, device=dev) for _ in range(3)]
+    fir = getattr(hb, "hb_fir1d" + sfx)
+    m = batched(lambda i: fir(sx[i], so[i], fir_taps, 3), 3, per_batch=10)
+    sup["fir1d_stacked_262144x256"] = dict(
+        {"ms": m["median"], "ms_min": m["min"], "ms_max": m["max"], "gpixels_per_s": Hs * 256 / m["median"] / 1e6},
+        **roofline_object(m["median"], Hs * 256 * 6, Hs * 256 * 16, traffic=traffic_x.get("fir1d_stacked_262144x256")))
+    del sx, so
+    torch.cuda.empty_cache()
+
+    # the large-tap regime of the paper's 1-D study (Sec. V-A)
+    for ntaps in (64, 128, 256):
+        t = synth.random_taps_f16(2000 + ntaps, ntaps)
+        pair("fir1d_%dtaps_4096x4096" % ntaps,
+             lambda i: hb.hb_fir1d(lx[i], lo[i], t, (ntaps - 1) // 2),
+             lambda i: hb.hb_fir1d_valu(lx[i], lo[i], t, (ntaps - 1) // 2),
+             ns, 6 * npx, 2 * ntaps * npx, npx)
+    # the 2-D study (Sec. V-A): non-separable k x k kernels
+    for k in (16, 32):
+        k2d = synth.random_kernel2d_f16(2300 + k, k, k)
+        pair("conv2d_%dx%d_4096x4096" % (k, k),
+             lambda i: hb.hb_conv2d(lx[i], lo[i], k2d, k // 2, k // 2),
+             lambda i: hb.hb_conv2d_valu(lx[i], lo[i], k2d, k // 2, k // 2),
+             ns, 6 * npx, 2 * k * k * npx, npx)
+    # the resampling study (Sec. V-B): 2x down (4096^2 -> 2048^2) and 2x up (2048^2 -> 4096^2); pixels are counted
+    # on the larger image
+    half_out = [torch.empty((2048, 2048), dtype=torch.float32, device=dev) for _ in range(ns)]
+    half_in = [t[:2048, :2048] for t in lx]               # row pitch 4096
+    for k in (16, 32):
+        k2d = synth.random_kernel2d_f16(2400 + k, k, k)
+        pair("down2_%dx%d_4096x4096" % (k, k),
+             lambda i: hb.hb_down2(lx[i], half_out[i], k2d, k // 2, k // 2),
+             lambda i: hb.hb_down2_valu(lx[i], half_out[i], k2d, k // 2, k // 2),
+             ns, 2 * npx + 4 * npx // 4, 2 * k * k * (npx // 4), npx)
+        pair("up2_%dx%d_4096x4096" % (k, k),
+             lambda i: hb.hb_up2(half_in[i], lo[i], k2d, k // 4, k // 4),
+             lambda i: hb.hb_up2_valu(half_in[i], lo[i], k2d, k // 4, k // 4),
+             ns, 2 * npx // 4 + 4 * npx, 2 * (k // 2) * (k // 2) * npx, npx)
+    del half_out, half_in
+    # the non-integer resize (Sec. V-C, Table II): a 2048 x 2048 RGB image down to 143 / 245 / 450 / 921 squared
+    rgb = [torch.rand((3, 2048, 2048), device=dev).half() for _ in range(12)]
+    for n in (143, 245, 450, 921):
+        st_h, cf_h = hb.hb_lanczos3_matrix(2048, n)
+        st_d = torch.from_numpy(st_h).to(dev)
+        cf_d = torch.from_numpy(cf_h.view(np.int16)).to(dev).view(torch.float16)
+        ro = torch.empty((3, n, n), dtype=torch.float32, device=dev)
+        rws = torch.empty(hb.hb_resize_workspace_size(3, 2048, n), dtype=torch.uint8, device=dev)
+        band = int(cf_h.shape[1])
+        pair("resize_lanczos3_3x2048x2048_to_%d" % n,
+             lambda i: hb.hb_resize(rgb[i], ro, rws, st_d, cf_d, st_d, cf_d),
+             lambda i: hb.hb_resize_valu(rgb[i], ro, rws, st_d, cf_d, st_d, cf_d),
+             12, 3 * (2 * 2048 * 2048 + 4 * n * n), 3 * 2 * band * (2048 * n + n * n), 3 * 2048 * 2048,
+             extra={"band": band})
+    del rgb
+    # the recursive filter (Sec. V-D): 2^21 stereo samples, a resonant second-order filter
+    T = 1 << 21
+    aud = [(torch.rand((2, T), device=dev) * 2 - 1).half() for _ in range(4)]
+    aout = [torch.empty((2, T), dtype=torch.float32, device=dev) for _ in range(4)]
+    aws = torch.empty(hb.hb_iir2_workspace_size(2, T), dtype=torch.uint8, device=dev)
+    pair("iir2_2x2097152",
+         lambda i: hb.hb_iir2(aud[i], aout[i], 1.6, -0.8, aws),
+         lambda i: hb.hb_iir2_valu(aud[i], aout[i], 1.6, -0.8, aws),
+         4, 6 * 2 * T, 4 * 2 * T, 2 * T)
+    sup["iir2_2x2097152"]["mfma_gsamples_per_s"] = 2 * T / sup["iir2_2x2097152"]["mfma_ms"] / 1e6
+    del aud, aout
+    # DCT-domain denoising (Sec. V-E): a one-megapixel three-channel image; fp32 products on the matrix units
+    dimg = [torch.rand((3, 1024, 1024), device=dev).half() for _ in range(4)]
+    dout = [torch.empty((3, 1024, 1024), dtype=torch.float32, device=dev) for _ in range(4)]
+    dws = torch.empty(hb.hb_dct_denoise_workspace_size(3, 1024, 1024), dtype=torch.uint8, device=dev)
+    ntile = 3 * 127 * 127
+    pair("dct_denoise_3x1024x1024",
+         lambda i: hb.hb_dct_denoise(dimg[i], dout[i], 0.05, dws),
+         lambda i: hb.hb_dct_denoise_valu(dimg[i], dout[i], 0.05, dws),
+         4, 6 * 3 * 1024 * 1024, ntile * 4 * 2 * 16 ** 3, 3 * 1024 * 1024, mfma_peak=MFMA_F32_PEAK_TFLOPS)
+    return sup
 
 
 def cpu_baseline(host, fir_taps, gau_taps, total_px):

@@ -174,7 +174,11 @@ __device__ __forceinline__ void store_rows_via_lds(float* patch, float* dst, uin
 // This maps a workgroup id to a position such that every XCD works through one contiguous
 // eighth of the positions, in order: neighbouring tasks, which share halo pixels, then meet
 // in the same L2 at about the same time instead of each fetching the halo from memory.
+#ifndef HB_XCD_CONTIGUOUS
+#define HB_XCD_CONTIGUOUS 1
+#endif
 __device__ __forceinline__ int xcd_contiguous(int wg, int nwg) {
+    if (!HB_XCD_CONTIGUOUS) return wg;
     const int per = nwg >> 3;                             // positions per XCD (remainder handled below)
     if (wg >= per * 8) return wg;                         // tail workgroups keep their place
     return (wg & 7) * per + (wg >> 3);

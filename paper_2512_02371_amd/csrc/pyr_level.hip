@@ -476,8 +476,10 @@ __global__ void __launch_bounds__(256, 2) pyr_mfma_kernel(PyrArgs p) {
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2 * NS>::kFloats];
     __shared__ __attribute__((aligned(16))) char s_stash[4][PyrStash<NS>::kBytes];
 
-    const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
+    // (tasks in plain launch order: the waves in flight then sweep down the image as one band; with
+    // the order that keeps neighbouring tasks on one XCD, eight separate bands, 8192 x 8192 took 97
+    // instead of 92 us)
+    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     const int ntasks = p.count();
     for (int task = wave; task < ntasks; task += nwaves) {

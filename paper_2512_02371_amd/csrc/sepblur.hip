@@ -34,6 +34,18 @@
 #define HB_SEP_WAVES 4096     // at most this many wave tasks per launch: one resident round, no straggler round
 #endif
 
+#ifdef HB_SEP_TIMING
+__device__ unsigned long long g_sep_stamp[16384][4];      // measurement builds only
+extern "C" int hb_debug_sep_stamps(void* host, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_sep_stamp), bytes);
+}
+#define SEP_STAMP(task, i) do { if ((threadIdx.x & 63) == 0 && (task) < 16384) g_sep_stamp[task][i] = wall_clock64(); } while (0)
+static __device__ int g_dbg_task_unused;
+#define g_dbg_task dbg_task_local
+#else
+#define SEP_STAMP(task, i) do { } while (0)
+#endif
+
 namespace hb {
 
 struct SepArgs {
@@ -173,7 +185,108 @@ __device__ __forceinline__ void sep_task(const SepArgs& p, const FoldTables& fol
     }
 }
 
-template <int NKX, int NT, bool STREAM>
+// Coefficient fragments, read from the tap tables in the kernel arguments: coefx[kk] = B operand of the
+// row pass, Bx[32 kk + 8g + i][c]; coefy[j] = B operand of the column pass in the chained slot order.
+template <int NKX, int NK>
+__device__ __forceinline__ void sep_fragments(const SepArgs& p, int c, int g, half8 (&coefx)[NKX], half8 (&coefy)[NK]) {
+    const int e = p.ax & 1;
+#pragma unroll
+    for (int kk = 0; kk < NKX; ++kk) coefx[kk] = tap_run(p.tx.tab, 32 * kk + 8 * g - c - e);
+#pragma unroll
+    for (int j = 0; j < NK; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) coefy[j][i] = tap_at(p.ty.tab, 32 * j + krow32(g, i) - c);
+}
+
+// Short task for the common case (one window per tile, up to three row tiles under an output tile):
+// a strip of NW tiles x NS output steps whose NS + NT - 1 row tiles are ALL requested before the
+// first product.  A wave then lives for one memory round trip plus its arithmetic, and what keeps
+// the memory system busy is the number of such waves in flight (the dispatcher refills as they
+// leave) rather than a chain of dependent steps inside one long-lived wave, each waiting for the
+// one tile it has in flight.  Interior strips only (plain fragment, full tiles); rows are clamped
+// per lane and rows beyond the image are not stored.
+template <int NT, int NS, bool STREAM>
+__device__ __forceinline__ void sep_task_short(const SepArgs& p, float* patch,
+                                               int x0, int Y0, int xw, int c, int g, int dbg_task_local = 0) {
+    constexpr int NW = HB_SEP_TILES, NL = NS + NT - 1, NK = (NT + 1) / 2;
+#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 4)
+    const half_t* src = p.in + x0;
+#else
+    const half_t* src = p.in + (x0 - xw);                 // uniform; lanes add row * pitch + 8g
+#endif
+    float* dst = p.out + x0;
+    half8 px[NL][NW];
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 2)
+        if (q >= NS) continue;
+#endif
+        const int yr = clampi(Y0 - p.ay + 16 * q + c, 0, p.H - 1);
+        const uint32_t off = ((uint32_t)yr * (uint32_t)p.in_pitch + 8u * g) * 2u;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) px[q][w] = ldg8(src, off + 32u * w);
+#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 1)
+#pragma unroll
+        for (int w = 1; w < NW; ++w) px[q][w] = px[q][0];
+#endif
+    }
+#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 2)
+#pragma unroll
+    for (int q = NS; q < NL; ++q)
+#pragma unroll
+        for (int w = 0; w < NW; ++w) px[q][w] = px[NS - 1][w];
+#endif
+    // The tap tables are read only now: a wave that waited for them first would put a memory round
+    // trip in front of its pixel requests.
+    __builtin_amdgcn_sched_barrier(0);
+    half8 coefx1[1], coefy[NK];
+    sep_fragments<1, NK>(p, c, g, coefx1, coefy);
+    const half8 coefx = coefx1[0];
+    half4 h[NL][NW];                                      // row-filtered tiles, rounded to fp16
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+            h[q][w] = to_half4(mfma16x16x32(px[q][w], coefx, zero));
+        }
+#ifdef HB_SEP_TIMING
+        if (q == 0 || q == NL - 1) { asm volatile("" :: "v"(h[q][0]) : "memory"); SEP_STAMP(g_dbg_task, q == 0 ? 1 : 2); }
+#endif
+        if (q < NT - 1) continue;
+        const int s = q - (NT - 1);                       // output step completed by this tile
+        floatx4 acc[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            acc[w] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NK; ++j) {
+                const half4 lo = h[s + 2 * j][w];
+                const half4 hi = (2 * j + 1 < NT) ? h[s + 2 * j + 1][w] : half4{0, 0, 0, 0};
+                acc[w] = mfma16x16x32(join(lo, hi), coefy[j], acc[w]);
+            }
+        }
+        if (Y0 + 16 * s + 16 <= p.H) {
+            store_rows_via_lds<NW, STREAM>(patch, dst + (int64_t)(Y0 + 16 * s) * p.out_pitch,
+                                           (uint32_t)p.out_pitch, acc, (g << 4) | c);
+        } else {
+            const int yo = Y0 + 16 * s + c;
+            if (yo < p.H) {
+                const uint32_t off = ((uint32_t)yo * (uint32_t)p.out_pitch + 4u * g) * 4u;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) stg4<STREAM>(dst, off + 64u * w, acc[w]);
+            }
+        }
+    }
+}
+
+// Short tasks come in two lengths: 8 output steps while that still leaves the image in one resident
+// round of waves (4096 x 4096: 4096 waves; measured 24 us against 27 us with 4 steps), else 4 steps
+// (8192 x 8192: 98 us against 107 us).  NS = 0 selects the walking task.
+constexpr bool sep_short_ok(int nkx, int nt) { return nkx == 1 && nt <= 3; }
+constexpr int kSepOneRoundWaves = 4608;
+
+template <int NKX, int NT, bool STREAM, int NS = 0>
 __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
     constexpr int NK = (NT + 1) / 2;          // K = 32 chunks of the column pass
     constexpr int NW = HB_SEP_TILES;
@@ -184,15 +297,6 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
 
     const int e = p.ax & 1;
     const int xw = p.ax + e;                  // window start, left of the tile
-    half8 coefx[NKX];                         // B operand of the row pass: Bx[32kk + 8g + i][c]
-#pragma unroll
-    for (int kk = 0; kk < NKX; ++kk) coefx[kk] = tap_run(p.tx.tab, 32 * kk + 8 * g - c - e);
-    half8 coefy[NK];                          // B operand of the column pass, chained slot order
-#pragma unroll
-    for (int j = 0; j < NK; ++j)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) coefy[j][i] = tap_at(p.ty.tab, 32 * j + krow32(g, i) - c);
-
     const int wgpos = xcd_contiguous(blockIdx.x, gridDim.x);
     const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
@@ -202,8 +306,24 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
         const int x0 = 16 * NW * ct;
         const int Y0 = seg * p.steps * 16;
         const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
+#ifdef HB_SEP_TIMING
+        const int dbg_task_local = task;
+        SEP_STAMP(task, 0);
+#else
+        const int dbg_task_local = 0;
+#endif
+        if constexpr (NS > 0) {
+            if (p.grid.interior(seg, ct)) {   // builds its fragments itself, AFTER its pixel loads are on their way
+                sep_task_short<NT, NS, STREAM>(p, s_patch[threadIdx.x >> 6], x0, Y0, xw, c, g, dbg_task_local);
+                SEP_STAMP(task, 3);
+                continue;
+            }
+        }
+        half8 coefx[NKX], coefy[NK];
+        sep_fragments<NKX, NK>(p, c, g, coefx, coefy);
         if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, p.foldx, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
         else sep_task<NKX, NT, NW, false, STREAM>(p, p.foldx, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
+        SEP_STAMP(task, 3);
     }
 }
 
@@ -319,9 +439,13 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
     a.ay = ay;
     const int nct = ceil_div(W, 16 * HB_SEP_TILES);
     const int rowsteps = ceil_div(H, 16);
-    // enough tasks to fill the chip, few enough that the (NT-1)-tile warm-up stays small
+    // enough tasks to fill the chip, few enough that the (NT-1)-tile warm-up stays small; the short
+    // tasks of the common case have a fixed length
+    const int nkx0 = ceil_div(15 + ntx + (ax & 1), 32);
     int steps = (int)(((int64_t)rowsteps * nct + HB_SEP_WAVES - 1) / HB_SEP_WAVES);
     steps = steps < 1 ? 1 : steps;
+    if (sep_short_ok(nkx0, (nty + 30) / 16))
+        steps = (int64_t)ceil_div(rowsteps, 8) * nct <= kSepOneRoundWaves ? 8 : 4;
     a.steps = steps;
     a.grid.nct = nct;
     a.grid.nseg = ceil_div(rowsteps, steps);
@@ -342,8 +466,13 @@ static hb_status sep_prepare(SepArgs& a, const hb_half* in, float* out, int H, i
 
 template <int NKX, int NT, bool STREAM>
 static void sep_launch2(hipStream_t st, const SepArgs& a) {
-    hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, NT, STREAM>), dim3(min(ceil_div(a.grid.count(), 4), kMaxStreamBlocks)),
-                       dim3(256), 0, st, a);
+    const dim3 grid(min(ceil_div(a.grid.count(), 4), kMaxStreamBlocks));
+    if constexpr (sep_short_ok(NKX, NT)) {
+        if (a.steps == 8) hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, NT, STREAM, 8>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, NT, STREAM, 4>), grid, dim3(256), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((sepblur_mfma_kernel<NKX, NT, STREAM, 0>), grid, dim3(256), 0, st, a);
+    }
 }
 template <int NKX, bool STREAM>
 static void sep_launch_nt(int nt, hipStream_t st, const SepArgs& a) {

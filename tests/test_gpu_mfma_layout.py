@@ -24,3 +24,16 @@ def test_mfma_probe_matches_host_product(which):
     hb.hb_mfma_probe(which, dA, dB, dD)
     torch.cuda.synchronize()
     assert np.array_equal(dD.cpu().numpy().astype(np.float64), A @ B)
+
+
+@pytest.mark.parametrize("n", [8, 2048, 2049, 4096 * 3 + 5, 1 << 20])
+def test_copy_reference_converts_every_element(n):
+    """hb_copy_f16_f32 (the bandwidth reference) is an exact fp16 -> fp32 conversion, tails included."""
+    import torch
+    from paper_2512_02371_amd import hb
+    x = (torch.rand(n, device="cuda:0") * 4 - 2).half()
+    out = torch.full((n + 8,), -7.0, dtype=torch.float32, device="cuda:0")
+    hb.hb_copy_f16_f32(x, out[:n])
+    torch.cuda.synchronize()
+    assert torch.equal(out[:n], x.float())
+    assert torch.all(out[n:] == -7.0), "wrote past the end"
