@@ -73,8 +73,10 @@ __device__ __forceinline__ int cv_fresh(int v) {
 // stay in flight for two tiles.  The waits that order them are explicit in the tile loop.
 typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void cv_dma16(u32x4s rsrc, uint32_t lds_addr, uint32_t voff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+    uint32_t m0_before;                                   // M0 cannot be named as clobbered: it is put back
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\t"
+                 "s_mov_b32 m0, %0"
+                 : "=&s"(m0_before) : "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
 }
 __device__ __forceinline__ uint32_t cv_lds_addr(const void* p) {
     return (uint32_t)(size_t)(__attribute__((address_space(3))) const void*)p;
@@ -193,7 +195,7 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     // coefficient fragments: wf[s] lane (c32, h) = w[tap][16 kc + 8h + i][32 j + c32], s = 4 tap + kc.
     // The weights arrive with the output channel innermost; a fragment wants eight consecutive INPUT
     // channels per lane.  They pass through LDS once, transposed on the way in: coalesced 16-byte
-    // reads of eight output channels, 2-byte writes to [tap][co][ci] with a 144-byte pitch per
+    // reads of eight output channels, 4-byte writes to [tap][co][ci] with a 144-byte pitch per
     // (tap, co), so that each fragment is one conflict-free 16-byte read.  Taps 0..6 use ring rows
     // 10..25 (free until the second tile's rows are requested), taps 7, 8 the output stage.
     half8 wf[36];
@@ -204,13 +206,21 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
         static_assert(kTapsInRing * kWTap <= (kCvRing - 10) * kCvRowBytes, "taps 0..6 must fit ring rows 10..25");
         static_assert((9 - kTapsInRing) * kWTap <= kCvStageBytes, "taps 7, 8 must fit the output stage");
         char* const wring = s_ring + 10 * kCvRowBytes;
-        for (int i = tid; i < 9 * kCvC * kCvC / 8; i += kCvThreads) {
-            const half8 v = reinterpret_cast<const half8*>(p.w)[i];          // w[tap][ci][8 cog .. 8 cog + 7]
-            const int cog = i & 7, ci = (i >> 3) & 63, tap = i >> 9;
+        // a thread takes the same eight output channels of TWO neighbouring input channels and writes
+        // eight 4-byte pairs; with the input-channel pair as the fastest lane index the 64 writes of an
+        // instruction fall into 64 different banks (2-byte writes, one input channel at a time, took
+        // twice the instructions and met two lanes in every bank word)
+        for (int i = tid; i < 9 * (kCvC / 2) * (kCvC / 8); i += kCvThreads) {
+            const int cip = i & 31, cog = (i >> 5) & 7, tap = i >> 8;
+            const half8 v0 = reinterpret_cast<const half8*>(p.w)[(tap * kCvC + 2 * cip) * 8 + cog];      // w[tap][2 cip][8 cog ..]
+            const half8 v1 = reinterpret_cast<const half8*>(p.w)[(tap * kCvC + 2 * cip + 1) * 8 + cog];
             char* dst = (tap < kTapsInRing ? wring + tap * kWTap : s_stage + (tap - kTapsInRing) * kWTap) +
-                        8 * cog * kWPitch + 2 * ci;
+                        8 * cog * kWPitch + 4 * cip;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) *reinterpret_cast<half_t*>(dst + e * kWPitch) = v[e];
+            for (int e = 0; e < 8; ++e) {
+                typedef half_t half2v __attribute__((ext_vector_type(2)));
+                *reinterpret_cast<half2v*>(dst + e * kWPitch) = half2v{v0[e], v1[e]};
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -233,8 +243,13 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     char* swrite = s_stage + (ro * kCvTX + c32) * kCvStagePitch + (32 * j + 4 * h) * 2;
 
     // start-up, part 2: the 8 new rows of the second tile, now that ring rows 10..17 are free
-    if (len > 1) cv_request_row(p, d, n, ys + 10 + wv, x0, s_ring, 10 + wv, lane);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // (only the first tile's rows have to be there now: everything but this wave's newest request)
+    if (len > 1) {
+        cv_request_row(p, d, n, ys + 10 + wv, x0, s_ring, 10 + wv, lane);
+        asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __syncthreads();
 
     int rb = 0;                                           // ring row of the tile's first row: 8 k mod 26
