@@ -34,9 +34,14 @@
  *    (HB_ERR_INVALID_ARG / HB_ERR_UNSUPPORTED / HB_ERR_WORKSPACE); a launch failure
  *    reported by the runtime gives HB_ERR_HIP.  Faults inside a kernel surface at
  *    the caller's next synchronisation, as for any asynchronous launch.
- *  - Thread safety: the library keeps no mutable global state; calls on different
- *    streams may run concurrently provided their buffers (and SAT workspaces) are
- *    distinct.
+ *  - Thread safety: calls from several host threads and on different streams may run
+ *    concurrently provided their buffers and workspaces are distinct.  The state the
+ *    library keeps is small and guarded by locks or atomics: per device, the
+ *    number of compute units, the LDS limit already granted to each kernel, how many
+ *    workgroups of the one-launch summed-area kernel are resident at once, and the
+ *    address of hb_sat2d_noalloc's array (each looked up at the first call that needs
+ *    it on that device); process-wide, the wait limit of hb_sat2d_set_wait_limit.
+ *    None of it depends on the data of a call.
  *  - Every stage has a `_valu` twin with the same signature and results that uses
  *    only vector-ALU FMAs (no MFMA): the ablation that shows what the matrix units
  *    buy.
@@ -92,9 +97,9 @@ hb_status hb_fir1d_valu(const hb_half *in, float *out, int H, int W,
  * in: H x W fp16, out: H x W fp32.  taps_host: kh x kw fp16 bit patterns, row-major,
  * HOST memory, read before the call returns.  1 <= kh, kw <= HB_MAX_TAPS_CONV2D,
  * 0 <= anchor_y < kh, 0 <= anchor_x < kw; otherwise HB_ERR_INVALID_ARG.  Size
- * limits as for hb_fir1d (HB_ERR_UNSUPPORTED beyond them).  Columns whose window
- * reaches over the left or right image border are computed by the vector-ALU
- * kernel in a second launch on the same stream.
+ * limits as for hb_fir1d (HB_ERR_UNSUPPORTED beyond them).  One launch: strips whose
+ * windows reach over the left or right image border load their pixels with clamped
+ * column indices inside the same kernel.
  */
 hb_status hb_conv2d(const hb_half *in, float *out, int H, int W,
                     int64_t in_pitch, int64_t out_pitch,
@@ -213,14 +218,19 @@ hb_status hb_lanczos3_matrix(int n_in, int n_out, int32_t *start_host, hb_half *
  * leaves the fp16 range, or whose tile-to-tile state maps overflow, are
  * HB_ERR_UNSUPPORTED (stable filters never are).  All sums are fp32, and a rounding
  * error made at one sample passes through the filter like an input: the absolute
- * error is about 2^-24 * sum|h| * max|out| (h the impulse response).  That stays
- * within 1e-3 * max(1, |out|) for inputs in [-1, 1] while sum|h| is up to a few
- * hundred (a complex pole pair of radius 0.95, say); sharper resonances lose more.
+ * error is bounded by about 2^-24 * G * max|out|, G = sum over i < T of |h[i]| (h the
+ * impulse response).  The call computes G on the host and returns
+ * HB_ERR_UNSUPPORTED when G > 16384 (= 1e-3 * 2^24: beyond it that bound no longer
+ * stays within 1e-3 * max|out|); a complex pole pair of radius 0.95 has G of a few
+ * hundred, the running sum (alpha = 1, beta = 0) has G = T.  hb_iir2_abs_gain
+ * returns the G that the call would check (host only; -1 for arguments outside
+ * the ranges above).
  * `workspace`: device scratch of at
  * least hb_iir2_workspace_size(C, T) bytes, 256-byte aligned; contents undefined on
  * exit; concurrent calls need their own.
  */
 size_t hb_iir2_workspace_size(int C, int64_t T);
+double hb_iir2_abs_gain(float alpha, float beta, int64_t T);
 hb_status hb_iir2(const hb_half *in, float *out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
                   float alpha, float beta, void *workspace, size_t workspace_bytes, hb_stream stream);
 hb_status hb_iir2_valu(const hb_half *in, float *out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
@@ -260,6 +270,16 @@ hb_status hb_dct_denoise_valu(const hb_half *in, float *out, int C, int H, int W
  * hb_sat2d_workspace_size(H, W) bytes, 256-byte aligned; its contents on entry do
  * not matter and are undefined on exit.  Two calls that run concurrently need
  * two workspaces.
+ * Images of up to 1024 regions of 256 x 256 pixels whose workgroups are all resident
+ * at once (4096 x 4096 is 256 regions) run as ONE kernel that reads the image once:
+ * every workgroup forms the local table of its region in registers, publishes the
+ * region's row, column and total sums in the workspace, waits until all regions have
+ * published, adds the sums of the regions to its left and above, and stores.  The
+ * wait is bounded (hb_sat2d_set_wait_limit): a workgroup that reaches the bound marks
+ * its region and exits, and the workgroups that got through finish the marked regions
+ * from memory, so the kernel ends whatever the scheduling.  A small kernel ahead of it
+ * on the same stream clears the wait's counters.  Larger images take three launches
+ * (tile sums, scans of the carries, apply) and read the image twice.
  */
 size_t hb_sat2d_workspace_size(int H, int W);
 hb_status hb_sat2d(const hb_half *in, float *out, int H, int W,
@@ -345,7 +365,10 @@ hb_status hb_copy_f16_f32(const hb_half *in, float *out, int64_t n, hb_stream st
  * B (K x N) gathered through the operand-to-lane maps the kernels assume, and
  * scatters the accumulator to row-major D (M x N, fp32).  A test multiplies random
  * matrices and compares with a host product, which checks those maps.  A and B are
- * fp16 for which 0..2 and fp32 for which 3.
+ * fp16 for which 0..2 and fp32 for which 3.  which = 4 chains two products of
+ * different shape on one accumulator, back to back (an order the stage kernels never
+ * use): D = A1 B1 + A2 B2 with A = A1 (16 x 32) followed by A2 (16 x 16), B = B1
+ * (32 x 16) followed by B2 (16 x 16), each part dense row-major fp16, D 16 x 16.
  */
 hb_status hb_mfma_probe(int which, const void *A, const void *B, float *D, hb_stream stream);
 

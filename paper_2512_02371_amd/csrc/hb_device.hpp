@@ -37,11 +37,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // with the same slot order (see krow32 below), which leaves the sum unchanged.
 // ---------------------------------------------------------------------------
 
+// These wrappers are the only matrix products the kernels can issue (a test scans the sources for
+// builtins used anywhere else).  For 16 x 16 fp16 products there is ONE shape, K = 32: a
+// 16x16x16 product issued straight after a 16x16x32 on the same accumulator once gave a wrong
+// first tile, so an accumulator chain never mixes the two; operands with K = 16 are padded with
+// zeros.  The K = 16 instruction exists only inside the self-check kernel of util.hip.
 __device__ __forceinline__ floatx4 mfma16x16x32(half8 a, half8 b, floatx4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
-__device__ __forceinline__ floatx4 mfma16x16x16(half4 a, half4 b, floatx4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
 }
 __device__ __forceinline__ floatx4 mfma16x16x4f32(float a, float b, floatx4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);

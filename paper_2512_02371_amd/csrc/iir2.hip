@@ -348,6 +348,27 @@ static Mat2 mat2_pow(Mat2 m, int64_t n) {
     return r;
 }
 
+// sum of |h[i]|, i < T, of the filter's impulse response: the factor by which the filter can magnify a
+// rounding error made at one sample.  The recurrence runs until the response has died away (both
+// state values below 1e-12 of the sum so far), for at most kIirGainSamples samples; a response
+// still alive there is taken to stay at its recent size for the rest of the signal.
+constexpr int64_t kIirGainSamples = 1 << 16;
+constexpr double kIirMaxGain = 16384.0;                   // 2^-24 * gain <= 1e-3
+static double iir2_abs_gain(double al, double be, int64_t T) {
+    double h1 = 0.0, h2 = 0.0, sum = 0.0, recent = 0.0;
+    const int64_t n = T < kIirGainSamples ? T : kIirGainSamples;
+    for (int64_t i = 0; i < n; ++i) {
+        const double h = i == 0 ? 1.0 : al * h1 + be * h2;
+        h2 = h1;
+        h1 = h;
+        sum += fabs(h);
+        if (!(sum < 1.0e300)) return INFINITY;
+        recent = fabs(h1) > fabs(h2) ? fabs(h1) : fabs(h2);
+        if (i >= 2 && recent < 1.0e-12 * sum) return sum;
+    }
+    return sum + (double)(T - n) * recent;
+}
+
 static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,
                           float alpha, float beta, void* workspace, size_t workspace_bytes, hb_stream stream) {
     if (!in || !out) return HB_ERR_INVALID_ARG;
@@ -374,6 +395,7 @@ static hb_status iir2_run(bool valu, const hb_half* in, float* out, int C, int64
     a.alpha = alpha;
     a.beta = beta;
     const double al = alpha, be = beta;
+    if (!(iir2_abs_gain(al, be, T) <= kIirMaxGain)) return HB_ERR_UNSUPPORTED;
     // impulse response and the response to the initial state, 32 samples each
     double h[kIirBlock], ca[kIirBlock], cb[kIirBlock];
     for (int i = 0; i < kIirBlock; ++i) {
@@ -436,6 +458,11 @@ extern "C" size_t hb_iir2_workspace_size(int C, int64_t T) {
     if (C < 1 || T < 1) return 0;
     const size_t ntiles = (size_t)((T + hb::kIirTile - 1) / hb::kIirTile);
     return 2 * 2 * sizeof(float) * (size_t)C * ntiles;
+}
+
+extern "C" double hb_iir2_abs_gain(float alpha, float beta, int64_t T) {
+    if (T < 1 || !(fabsf(alpha) <= 4.f) || !(fabsf(beta) <= 4.f)) return -1.0;
+    return hb::iir2_abs_gain(alpha, beta, T);
 }
 
 extern "C" hb_status hb_iir2(const hb_half* in, float* out, int C, int64_t T, int64_t in_pitch, int64_t out_pitch,

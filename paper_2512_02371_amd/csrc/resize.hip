@@ -133,7 +133,7 @@ __global__ void __launch_bounds__(64 * kRzWaves) band_mfma_kernel(BandArgs p) {
         if (active) load_chunk(base, bufa);
 
         // coefficient block, B-operand layout: lane (c = o, g) holds B[8g + i][o] = coef[o][first + 32 kk + 8g + i - start[o]];
-        // wave wv builds chunks wv, wv + 4, ...
+        // wave wv builds chunks wv, wv + kRzWaves, ...
         for (int kk = wv; kk < nk; kk += kRzWaves) {
             half8 f;
 #pragma unroll

@@ -95,7 +95,7 @@ __global__ void __launch_bounds__(256) sat_sums_mfma_kernel(SatArgs p) {
         for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk)
-                X[rt][blk] = ldg8(src, off + 2u * (16u * rt * (uint32_t)p.in_pitch + 32u * blk));
+                X[rt][blk] = ldg8(src + (int64_t)(16 * rt) * p.in_pitch, off + 64u * blk);   // 64-bit base per 16 rows
     } else {
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)
@@ -241,7 +241,7 @@ __global__ void __launch_bounds__(256) sat_apply_mfma_kernel(SatArgs p) {
         for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk)
-                X[rt][blk] = ldg8(src, off + 2u * (16u * rt * (uint32_t)p.in_pitch + 32u * blk));
+                X[rt][blk] = ldg8(src + (int64_t)(16 * rt) * p.in_pitch, off + 64u * blk);   // 64-bit base per 16 rows
     } else {
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)

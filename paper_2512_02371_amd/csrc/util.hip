@@ -34,8 +34,14 @@ __global__ void __launch_bounds__(256) copy_f16_f32_kernel(const half_t* __restr
     }
 }
 
+// The K = 16 product lives here only: the stage kernels have no way to issue it.
+__device__ __forceinline__ floatx4 probe_mfma16x16x16(half4 a, half4 b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+}
+
 // One MFMA on dense row-major operands, gathered and scattered through the
-// operand-to-lane maps documented in hb_device.hpp.
+// operand-to-lane maps documented in hb_device.hpp; which = 4 chains a K = 32 and a K = 16
+// product on one accumulator, back to back (the order the stage kernels avoid).
 __global__ void __launch_bounds__(64) mfma_probe_kernel(int which, const void* Av, const void* Bv, float* D) {
     const int lane = threadIdx.x;
     if (which == 0) {          // 16x16x32 f16
@@ -52,7 +58,7 @@ __global__ void __launch_bounds__(64) mfma_probe_kernel(int which, const void* A
         half4 a, b;
         for (int i = 0; i < 4; ++i) { a[i] = A[c * 16 + 4 * g + i]; b[i] = B[(4 * g + i) * 16 + c]; }
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        acc = mfma16x16x16(a, b, acc);
+        acc = probe_mfma16x16x16(a, b, acc);
         for (int v = 0; v < 4; ++v) D[(4 * g + v) * 16 + c] = acc[v];
     } else if (which == 2) {   // 32x32x16 f16
         const half_t* A = (const half_t*)Av; const half_t* B = (const half_t*)Bv;
@@ -64,6 +70,19 @@ __global__ void __launch_bounds__(64) mfma_probe_kernel(int which, const void* A
         acc = mfma32x32x16(a, b, acc);
         for (int q = 0; q < 4; ++q)
             for (int r = 0; r < 4; ++r) D[(8 * q + 4 * h + r) * 32 + c] = acc[4 * q + r];
+    } else if (which == 4) {   // D = A32 B32 + A16 B16: A = [16 x 32 | 16 x 16], B = [32 x 16 | 16 x 16], each part dense
+        const half_t* A = (const half_t*)Av; const half_t* B = (const half_t*)Bv;
+        const int c = lane & 15, g = lane >> 4;
+        half8 a, b;
+        half4 a2, b2;
+        for (int i = 0; i < 8; ++i) { a[i] = A[c * 32 + 8 * g + i]; b[i] = B[(8 * g + i) * 16 + c]; }
+        for (int i = 0; i < 4; ++i) { a2[i] = A[512 + c * 16 + 4 * g + i]; b2[i] = B[512 + (4 * g + i) * 16 + c]; }
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_sched_barrier(0);
+        acc = mfma16x16x32(a, b, acc);
+        acc = probe_mfma16x16x16(a2, b2, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int v = 0; v < 4; ++v) D[(4 * g + v) * 16 + c] = acc[v];
     } else {                   // 16x16x4 f32
         const float* A = (const float*)Av; const float* B = (const float*)Bv;
         const int c = lane & 15, g = lane >> 4;
@@ -100,7 +119,7 @@ extern "C" hb_status hb_copy_f16_f32(const hb_half* in, float* out, int64_t n, h
 
 extern "C" hb_status hb_mfma_probe(int which, const void* A, const void* B, float* D, hb_stream stream) {
     using namespace hb;
-    if (!A || !B || !D || which < 0 || which > 3) return HB_ERR_INVALID_ARG;
+    if (!A || !B || !D || which < 0 || which > 4) return HB_ERR_INVALID_ARG;
     hipLaunchKernelGGL(mfma_probe_kernel, dim3(1), dim3(64), 0, reinterpret_cast<hipStream_t>(stream), which, A, B, D);
     return launch_status();
 }

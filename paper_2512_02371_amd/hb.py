@@ -31,7 +31,7 @@ SYMBOLS = [
     "hb_conv2d", "hb_conv2d_valu",
     "hb_down2", "hb_down2_valu", "hb_up2", "hb_up2_valu",
     "hb_resize_workspace_size", "hb_resize", "hb_resize_valu", "hb_lanczos3_band", "hb_lanczos3_matrix",
-    "hb_iir2_workspace_size", "hb_iir2", "hb_iir2_valu",
+    "hb_iir2_workspace_size", "hb_iir2_abs_gain", "hb_iir2", "hb_iir2_valu",
     "hb_dct_denoise_workspace_size", "hb_dct_denoise", "hb_dct_denoise_valu",
     "hb_sepblur", "hb_sepblur_valu",
     "hb_sat2d_workspace_size", "hb_sat2d", "hb_sat2d_valu", "hb_sat2d_noalloc", "hb_sat2d_set_wait_limit",
@@ -95,6 +95,8 @@ def load() -> ctypes.CDLL:
         getattr(L, name).restype = I
     L.hb_iir2_workspace_size.argtypes = [I, I64]
     L.hb_iir2_workspace_size.restype = ctypes.c_size_t
+    L.hb_iir2_abs_gain.argtypes = [ctypes.c_float, ctypes.c_float, I64]
+    L.hb_iir2_abs_gain.restype = ctypes.c_double
     dct = [vp, vp, I, I, I, I64, I64, I64, I64, ctypes.c_float, vp, ctypes.c_size_t, vp]
     for name in ("hb_dct_denoise", "hb_dct_denoise_valu"):
         getattr(L, name).argtypes = dct
@@ -234,6 +236,10 @@ def hb_dct_denoise_valu(inp, out, threshold, workspace):
 
 def hb_iir2_workspace_size(C, T):
     return int(load().hb_iir2_workspace_size(int(C), int(T)))
+
+
+def hb_iir2_abs_gain(alpha, beta, T):
+    return float(load().hb_iir2_abs_gain(float(alpha), float(beta), int(T)))
 
 
 def _iir2(name, inp, out, alpha, beta, workspace):

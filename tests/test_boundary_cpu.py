@@ -274,6 +274,11 @@ def test_iir2_argument_validation(lib, fn):
     assert call(a=float("nan")) == hb.HB_ERR_INVALID_ARG
     assert call(b=5.0) == hb.HB_ERR_INVALID_ARG
     assert call(a=3.0, b=2.0) == hb.HB_ERR_UNSUPPORTED          # impulse response leaves the fp16 range within 32 samples
+    # filters whose error magnification sum|h| exceeds 2^14 are refused: the running sum beyond 16384 samples,
+    # a pole pair almost on the unit circle; the same filters on short signals pass this check
+    big = dict(T=40000, ip=40000, op=40000, wsb=1 << 24)
+    assert call(a=1.0, b=0.0, **big) == hb.HB_ERR_UNSUPPORTED
+    assert call(a=1.99999, b=-0.99999, **big) == hb.HB_ERR_UNSUPPORTED
     assert call(ws=None) == hb.HB_ERR_WORKSPACE
     assert call(wsb=lib.hb_iir2_workspace_size(2, 5000) - 1) == hb.HB_ERR_WORKSPACE
     assert lib.hb_iir2_workspace_size(2, 5000) == 2 * 10 * 16     # 10 tiles of 512 samples, two states of two floats
@@ -307,7 +312,7 @@ def test_copy_and_probe_validation(lib):
     assert lib.hb_copy_f16_f32(None, FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(FAKE, FAKE, 0, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_copy_f16_f32(ctypes.c_void_p(0x1004), FAKE, 8, None) == hb.HB_ERR_INVALID_ARG
-    assert lib.hb_mfma_probe(4, FAKE, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
+    assert lib.hb_mfma_probe(5, FAKE, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
     assert lib.hb_mfma_probe(0, None, FAKE, FAKE, None) == hb.HB_ERR_INVALID_ARG
 
 
@@ -321,3 +326,37 @@ def test_size_limits_are_reported_not_wrapped(lib):
     # one conv image of 2^24 pixels or more (2 GiB of fp16 x 64 channels)
     assert lib.hb_conv3x3(FAKE, FAKE, FAKE, 1, 4096, 4096, 64, 64, None) == hb.HB_ERR_UNSUPPORTED
     assert lib.hb_conv3x3(FAKE, FAKE, FAKE, 1, 4096, 4095, 64, 32, None) == hb.HB_ERR_UNSUPPORTED
+
+
+def test_iir2_abs_gain_is_the_sum_of_the_impulse_response(lib):
+    """Against the definition: h from the recurrence in fp64, summed over T samples."""
+    for alpha, beta, T in [(1.6, -0.8, 5000), (1.2, -0.52, 100), (0.5, 0.3, 7), (-0.9, 0.0, 1000), (0.0, 0.0, 50),
+                           (1.0, 0.0, 12345), (1.9, -0.95, 100000)]:
+        al, be = float(np.float32(alpha)), float(np.float32(beta))
+        h = np.zeros(min(T, 200000))
+        for i in range(len(h)):
+            h[i] = 1.0 if i == 0 else al * h[i - 1] + (be * h[i - 2] if i >= 2 else 0.0)
+        want = np.abs(h).sum()
+        got = hb.hb_iir2_abs_gain(alpha, beta, T)
+        assert abs(got - want) <= 1e-9 * want, (alpha, beta, T, got, want)
+    assert hb.hb_iir2_abs_gain(1.0, 0.0, 1 << 30) == float(1 << 30)     # extrapolated past the summed samples
+    assert hb.hb_iir2_abs_gain(5.0, 0.0, 10) == -1.0
+    assert hb.hb_iir2_abs_gain(3.0, 2.0, 100000) == float("inf") or hb.hb_iir2_abs_gain(3.0, 2.0, 100000) > 1e100
+
+
+def test_matrix_builtins_appear_only_in_the_wrappers():
+    """The stage kernels issue matrix products through the wrappers of hb_device.hpp alone, and the
+    K = 16 fp16 shape exists only in the self-check kernel: a kernel cannot mix shapes on an accumulator."""
+    csrc = os.path.join(ROOT, "paper_2512_02371_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        text = open(os.path.join(csrc, name)).read()
+        text = re.sub(r"//[^\n]*", "", text)
+        uses = re.findall(r"__builtin_amdgcn_mfma_\w+", text)
+        if name == "hb_device.hpp":
+            assert sorted(set(uses)) == ["__builtin_amdgcn_mfma_f32_16x16x32_f16", "__builtin_amdgcn_mfma_f32_16x16x4f32",
+                                         "__builtin_amdgcn_mfma_f32_32x32x16_f16"], uses
+        elif name == "util.hip":
+            assert uses == ["__builtin_amdgcn_mfma_f32_16x16x16f16"], uses
+        else:
+            assert not uses, f"{name} issues {uses} directly"
+        assert "v_mfma" not in re.sub(r"/\*.*?\*/", "", text, flags=re.S), f"{name}: matrix instruction in inline assembly"

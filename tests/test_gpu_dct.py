@@ -2,9 +2,10 @@
 
 The hard threshold makes a bin whose magnitude is within rounding distance of the threshold
 flip between kept and cut; the oracle marks the pixels of every tile that has such a bin (margin
-2e-5, more than ten times the fp32 error of a bin) and those pixels are only required to lie
-between the two possible outcomes' scale, i.e. to be finite and within the input range; all other
-pixels meet the usual tolerance."""
+2e-5, more than ten times the fp32 error of a bin) and those pixels may differ from the oracle by what the
+near-threshold bins of their tiles can move them (a bound computed per pixel from the number of
+such bins, the transform's largest entry and the blend weights); all other pixels meet the usual
+tolerance."""
 import numpy as np
 import pytest
 
@@ -42,7 +43,33 @@ def run(fn, img, threshold, pitch_extra=0):
     return out.cpu().numpy(), obuf.cpu().numpy()
 
 
-def check(orc, got, img, threshold, what):
+def flip_bound(orc, plane_bits, thr):
+    """Per pixel, the most that bins flipping between kept and cut can move the output.  A bin of
+    magnitude |Y| <= thr + MARGIN reaches a pixel of its tile through D[u][i] D[v][j], at most
+    (sqrt(2)/4)^2 = 1/8 in magnitude, so a tile with n bins near the threshold moves its
+    reconstruction by at most n (thr + MARGIN) / 8 anywhere; the blend weighs tile t by
+    w2_t / sum_t w2_t^2.  (The forward transform is redone here only to COUNT the near bins.)"""
+    X = synth.f16_bits_to_f64(plane_bits)
+    H, W = X.shape
+    D, w = orc.dct16_matrix(), orc.sine_window16()
+    w2 = np.outer(w, w)
+    tiles = np.lib.stride_tricks.sliding_window_view(X, (16, 16))[::8, ::8]           # [ty, tx, 16, 16]
+    Y = np.einsum("ui,abij,vj->abuv", D, tiles * w2, D, optimize=True)
+    near = np.abs(np.abs(Y) - thr) < MARGIN
+    near[:, :, 0, 0] = False
+    n = near.sum(axis=(2, 3)).astype(np.float64)
+    num = np.zeros((H, W))
+    den = np.zeros((H, W))
+    for ty in range(n.shape[0]):
+        for tx in range(n.shape[1]):
+            ys, xs = slice(8 * ty, 8 * ty + 16), slice(8 * tx, 8 * tx + 16)
+            den[ys, xs] += w2 * w2
+            if n[ty, tx]:
+                num[ys, xs] += n[ty, tx] * w2
+    return (thr + MARGIN) / 8.0 * num / den
+
+
+def check(orc, got, img, threshold, what, max_masked=0.5):
     thr = float(np.float32(threshold))                 # the library receives fp32
     for c in range(img.shape[0]):
         ref, risky = orc.dct_denoise(img[c], thr, margin=MARGIN if thr > 0 else 0.0)   # nothing can flip at threshold 0
@@ -50,9 +77,15 @@ def check(orc, got, img, threshold, what):
         assert np.all(np.isfinite(g)), what
         e = scaled_err(g, ref)
         assert e[~risky].max(initial=0.0) <= TOL, f"{what} plane {c}: {e[~risky].max():.3e}"
-        # a flipped bin changes a pixel by at most threshold / 8 times the blend's 1 / w gain
-        assert np.all(np.abs(g[risky] - ref[risky]) <= 0.2 + threshold), what
-        assert risky.mean() < 0.5, "the margin should not swallow the test"
+        print(f"{what} plane {c}: {risky.mean():.4f} of the pixels lie in a tile with a bin within {MARGIN} of the "
+              f"threshold", flush=True)
+        assert risky.mean() < max_masked, "the margin should not swallow the test"
+        if risky.any():
+            # those pixels: within the usual tolerance plus what the flipped bins can move them
+            bound = flip_bound(orc, img[c], thr)
+            assert np.all((bound > 0) == risky), "the near-threshold tiles counted here are not the oracle's"
+            slack = np.abs(g - ref) - TOL * np.maximum(1.0, np.abs(ref)) - bound
+            assert slack[risky].max() <= 0.0, f"{what} plane {c}: {slack[risky].max():.3e} beyond the flip bound"
 
 
 @pytest.mark.parametrize("fn", ["hb_dct_denoise", "hb_dct_denoise_valu"])
@@ -103,4 +136,4 @@ def test_dct_denoise_full_size(orc):
     C, H, W = 3, 1024, 1024
     img = noisy_image(9880, C, H, W)
     got, _ = run("hb_dct_denoise", img, 0.05)
-    check(orc, got[1:2], img[1:2], 0.05, "3 x 1024 x 1024, plane 1")
+    check(orc, got[1:2], img[1:2], 0.05, "3 x 1024 x 1024, plane 1", max_masked=0.15)

@@ -26,6 +26,29 @@ def test_mfma_probe_matches_host_product(which):
     assert np.array_equal(dD.cpu().numpy().astype(np.float64), A @ B)
 
 
+def test_mfma_probe_two_shapes_chained_on_one_accumulator():
+    """A K = 16 product issued straight after a K = 32 product on the same accumulator: the order
+    that once produced a wrong tile inside an unrolled kernel and that the stage kernels cannot
+    express any more (the shared header offers one shape).  Exact small integers; if the pair still
+    misbehaves the case is reported as an expected failure, with the worst difference."""
+    import torch
+    from paper_2512_02371_amd import hb
+    rng = np.random.default_rng(104)
+    A1 = rng.integers(-8, 9, size=(16, 32)).astype(np.float64)
+    B1 = rng.integers(-8, 9, size=(32, 16)).astype(np.float64)
+    A2 = rng.integers(-8, 9, size=(16, 16)).astype(np.float64)
+    B2 = rng.integers(-8, 9, size=(16, 16)).astype(np.float64)
+    dA = torch.tensor(np.concatenate([A1.ravel(), A2.ravel()]), dtype=torch.float16, device="cuda:0")
+    dB = torch.tensor(np.concatenate([B1.ravel(), B2.ravel()]), dtype=torch.float16, device="cuda:0")
+    dD = torch.zeros((16, 16), dtype=torch.float32, device="cuda:0")
+    print("mfma probe which=4", flush=True)
+    hb.hb_mfma_probe(4, dA, dB, dD)
+    torch.cuda.synchronize()
+    got, want = dD.cpu().numpy().astype(np.float64), A1 @ B1 + A2 @ B2
+    if not np.array_equal(got, want):
+        pytest.xfail(f"chained 16x16x32 -> 16x16x16 on one accumulator: max difference {np.abs(got - want).max()}")
+
+
 @pytest.mark.parametrize("n", [8, 2048, 2049, 4096 * 3 + 5, 1 << 20])
 def test_copy_reference_converts_every_element(n):
     """hb_copy_f16_f32 (the bandwidth reference) is an exact fp16 -> fp32 conversion, tails included."""
