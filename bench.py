@@ -111,6 +111,11 @@ def main():
     ap.add_argument("--variant", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the supplementary runs")
+    ap.add_argument("--counter-run", action="store_true",
+                    help="for hardware-counter runs under rocprofv3: one batch of two launches wherever batches are timed")
+    ap.add_argument("--only-row", default=None,
+                    help="for counter runs: launch the calibration copy and ONE supplementary row (matrix-unit path), "
+                         "skip the five-stage step; prints that row")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every box of this pool has one. Use --gpus 1.",
@@ -135,6 +140,8 @@ def main():
 
     def batched(fn, nsets, per_batch=PER_BATCH, batches=BATCHES, warm=10):
         """ms per launch: `batches` times `per_batch` back-to-back launches between two HIP events."""
+        if args.counter_run:
+            per_batch, batches, warm = 2, 1, 1
         for i in range(warm):
             fn(i % nsets)
         torch.cuda.synchronize()
@@ -191,6 +198,10 @@ def main():
     # One plain copy of known size (32 MiB read, 64 MiB written), untimed: a counter run of this
     # program reads its own scale for FETCH_SIZE / WRITE_SIZE from this dispatch.
     hb.hb_copy_f16_f32(ins["sepblur"][0], outs["sepblur"][0])
+    if args.only_row:
+        sup = supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host, fir_taps, 0, 0.0, sfx, traffic_x)
+        print(json.dumps({"row": args.only_row, "result": sup.get(args.only_row)}))
+        return
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize()
@@ -271,8 +282,15 @@ def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, hos
     ns = len(lx)
     npx = 4096 * 4096
 
+    only = args.only_row
+
     def pair(name, mfn, vfn, nsets, nbytes, flops, px, mfma_peak=MFMA_F16_PEAK_TFLOPS, extra=None):
+        if only and name != only:
+            return
         m = batched(mfn, nsets, per_batch=20)
+        if only:
+            sup[name] = {"mfma_ms": m["median"]}
+            return
         v = batched(vfn, nsets, per_batch=5, batches=3, warm=2)
         row = {"mfma_ms": m["median"], "mfma_ms_min": m["min"], "mfma_ms_max": m["max"], "valu_ms": v["median"],
                "mfma_gpixels_per_s": px / m["median"] / 1e6, "valu_gpixels_per_s": px / v["median"] / 1e6,
@@ -284,6 +302,8 @@ def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, hos
 
     # the practical ceiling of a 2 B in + 4 B out stream: the tuned copy at both image sizes
     for size, bufs_in, bufs_out in ((4096, lx, lo), (8192, ins["pyr_level"], outs["pyr_level"])):
+        if only:
+            break
         n = size * size
         m = batched(lambda i: hb.hb_copy_f16_f32(bufs_in[i], bufs_out[i]), len(bufs_in))
         sup["copy_ceiling_%dx%d" % (size, size)] = {
@@ -292,36 +312,38 @@ def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, hos
 
     # the same step replayed from a HIP graph (the library allocates nothing, synchronises nothing and issues
     # no memset, so its launches can be captured)
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        for k in range(4):
-            step(k)
-    graph.replay()
-    torch.cuda.synchronize()
-    nrep = max(1, args.steps // 4)
-    t0 = time.perf_counter()
-    for _ in range(nrep):
+    if not only:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for k in range(4):
+                step(k)
         graph.replay()
-    torch.cuda.synchronize()
-    gms = (time.perf_counter() - t0) * 1e3 / (4 * nrep)
-    sup["five_stage_step_graph_replay"] = {"ms_per_step": gms, "gpixels_per_s": total_px / gms / 1e6,
-                                           "steps_per_graph": 4, "eager_over_graph": ms_per_step / gms}
-    del graph
+        torch.cuda.synchronize()
+        nrep = max(1, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(nrep):
+            graph.replay()
+        torch.cuda.synchronize()
+        gms = (time.perf_counter() - t0) * 1e3 / (4 * nrep)
+        sup["five_stage_step_graph_replay"] = {"ms_per_step": gms, "gpixels_per_s": total_px / gms / 1e6,
+                                               "steps_per_graph": 4, "eager_over_graph": ms_per_step / gms}
+        del graph
     del ins["pyr_level"], outs["pyr_level"], ins["conv3x3"], outs["conv3x3"]
     torch.cuda.empty_cache()
 
     # the FIR stage on 1024 of its 256 x 256 images stacked into one 262144 x 256 image, where its launch
     # latency no longer hides its bandwidth
     Hs = 256 * 1024
-    sx = [up(host["fir1d"]).repeat(1024, 1) for _ in range(3)]
-    so = [torch.empty((Hs, 256), dtype=torch.float32, device=dev) for _ in range(3)]
-    fir = getattr(hb, "hb_fir1d" + sfx)
-    m = batched(lambda i: fir(sx[i], so[i], fir_taps, 3), 3, per_batch=10)
-    sup["fir1d_stacked_262144x256"] = dict(
-        {"ms": m["median"], "ms_min": m["min"], "ms_max": m["max"], "gpixels_per_s": Hs * 256 / m["median"] / 1e6},
-        **roofline_object(m["median"], Hs * 256 * 6, Hs * 256 * 16, traffic=traffic_x.get("fir1d_stacked_262144x256")))
-    del sx, so
-    torch.cuda.empty_cache()
+    if not only or only == "fir1d_stacked_262144x256":
+        sx = [up(host["fir1d"]).repeat(1024, 1) for _ in range(3)]
+        so = [torch.empty((Hs, 256), dtype=torch.float32, device=dev) for _ in range(3)]
+        fir = getattr(hb, "hb_fir1d" + sfx)
+        m = batched(lambda i: fir(sx[i], so[i], fir_taps, 3), 3, per_batch=10)
+        sup["fir1d_stacked_262144x256"] = dict(
+            {"ms": m["median"], "ms_min": m["min"], "ms_max": m["max"], "gpixels_per_s": Hs * 256 / m["median"] / 1e6},
+            **roofline_object(m["median"], Hs * 256 * 6, Hs * 256 * 16, traffic=traffic_x.get("fir1d_stacked_262144x256")))
+        del sx, so
+        torch.cuda.empty_cache()
 
     # the large-tap regime of the paper's 1-D study (Sec. V-A)
     for ntaps in (64, 128, 256):
@@ -376,7 +398,8 @@ def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, hos
          lambda i: hb.hb_iir2(aud[i], aout[i], 1.6, -0.8, aws),
          lambda i: hb.hb_iir2_valu(aud[i], aout[i], 1.6, -0.8, aws),
          4, 6 * 2 * T, 4 * 2 * T, 2 * T)
-    sup["iir2_2x2097152"]["mfma_gsamples_per_s"] = 2 * T / sup["iir2_2x2097152"]["mfma_ms"] / 1e6
+    if "iir2_2x2097152" in sup:
+        sup["iir2_2x2097152"]["mfma_gsamples_per_s"] = 2 * T / sup["iir2_2x2097152"]["mfma_ms"] / 1e6
     del aud, aout
     # DCT-domain denoising (Sec. V-E): a one-megapixel three-channel image; fp32 products on the matrix units
     dimg = [torch.rand((3, 1024, 1024), device=dev).half() for _ in range(4)]
