@@ -78,6 +78,8 @@ __global__ void __launch_bounds__(kC2Threads) conv2d_mfma_kernel(Conv2dArgs p) {
     }
     __syncthreads();
 
+    // plain launch order: with every XCD on one contiguous run of the tasks the halo windows meet in one
+    // L2 (reads 1.25x the image instead of 1.57x) but the kernel measured 7 % slower at 4096 x 4096
     const int task = blockIdx.x * (kC2Threads / 64) + wv;
     if (task >= p.ntasks) return;
     const int sg = task / p.nstrips, ct = task - sg * p.nstrips;

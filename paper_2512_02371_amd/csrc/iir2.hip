@@ -315,15 +315,25 @@ __global__ void __launch_bounds__(256) iir2_blocks_valu_kernel(IirArgs p) {
         }
     }
     if (WRITE) {
+        // a lane's 32 outputs pass through a patch of LDS that belongs to its wave (pitch 33: the
+        // lanes' writes and the rows read back fall into distinct banks) and leave as runs of 64
+        // consecutive samples per store instruction, instead of 64 single samples 128 bytes apart
+        __shared__ float s_y[4][64 * (kIirBlock + 1)];
+        float* const yb = s_y[threadIdx.x >> 6];
         float* dst = p.out + (int64_t)ch * p.out_pitch;
         y1 = mine.a;
         y2 = mine.b;
         for (int i = 0; i < kIirBlock; ++i) {
-            if (t0 + i >= p.T) break;
-            const float y = fmaf(p.alpha, y1, fmaf(p.beta, y2, (float)sig[t0 + i]));
-            dst[t0 + i] = y;
+            const float xv = t0 + i < p.T ? (float)sig[t0 + i] : 0.f;
+            const float y = fmaf(p.alpha, y1, fmaf(p.beta, y2, xv));
+            yb[lane * (kIirBlock + 1) + i] = y;
             y2 = y1;
             y1 = y;
+        }
+        const int64_t w0 = (int64_t)tile0 * kIirTile;     // first sample of the wave's four tiles
+        for (int r = 0; r < kIirBlock; ++r) {
+            const int64_t t = w0 + 64 * r + lane;
+            if (t < p.T) dst[t] = yb[(2 * r + (lane >> 5)) * (kIirBlock + 1) + (lane & 31)];
         }
     }
 }

@@ -80,7 +80,9 @@ __global__ void __launch_bounds__(kC2Threads) down2_mfma_kernel(Rs2Args p) {
     }
     __syncthreads();
 
-    const int task = blockIdx.x * (kC2Threads / 64) + wv;
+    // every XCD takes one contiguous run of the tasks: neighbouring strips and row segments share their
+    // halo pixels in one L2 (measured reads 1.36x / 1.2x the input instead of 2.2x / 1.6x, same time)
+    const int task = xcd_contiguous(blockIdx.x, gridDim.x) * (kC2Threads / 64) + wv;
     if (task >= p.ntasks) return;
     const int sg = task / p.nstrips, ct = task - sg * p.nstrips;
     const int x0 = 16 * NW * ct;              // first output column of the strip
@@ -192,7 +194,9 @@ __global__ void __launch_bounds__(kC2Threads) up2_mfma_kernel(Rs2Args p) {
     }
     __syncthreads();
 
-    const int task = blockIdx.x * (kC2Threads / 64) + wv;
+    // every XCD takes one contiguous run of the tasks: neighbouring strips and row segments share their
+    // halo pixels in one L2 (measured reads 1.36x / 1.2x the input instead of 2.2x / 1.6x, same time)
+    const int task = xcd_contiguous(blockIdx.x, gridDim.x) * (kC2Threads / 64) + wv;
     if (task >= p.ntasks) return;
     const int sg = task / p.nstrips, ct = task - sg * p.nstrips;
     const int x0 = 16 * NW * ct;              // first output column of the strip
