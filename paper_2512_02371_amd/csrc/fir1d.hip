@@ -96,8 +96,9 @@ __global__ void __launch_bounds__(256) fir1d_mfma_kernel(FirArgs p) {
     };
     const int wmax = p.W - 32 * NK;           // last window start that stays inside the row
 
-    // (tasks in plain launch order: with the order that keeps neighbours on one XCD this kernel measured
-    // 10 % slower on tall images, 100 against 89 us on 262144 x 256)
+    // (tasks in plain launch order: with one contiguous eighth of the tasks per XCD this kernel measured
+    // 10 % slower on tall images, 100 against 89 us on 262144 x 256; groups of 2 to 8 neighbours per XCD
+    // measured within 2 % of the plain order there)
     const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int task = wave; task < p.ntasks; task += nwaves) {

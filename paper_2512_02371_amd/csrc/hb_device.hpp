@@ -186,6 +186,16 @@ __device__ __forceinline__ int xcd_contiguous(int wg, int nwg) {
     return (wg & 7) * per + (wg >> 3);
 }
 
+// The same idea at a finer grain: of every 8 G consecutive workgroup ids, XCD x (which receives
+// ids x, x + 8, ...) takes G consecutive positions.  Neighbours still meet in one L2, while the chip
+// as a whole sweeps through the tasks in launch order, as it does with the plain order.
+__device__ __forceinline__ int xcd_blocked(int wg, int nwg, int G) {
+    const int span = 8 * G, first = (wg / span) * span;
+    if (first + span > nwg) return wg;                    // tail workgroups keep their place
+    const int r = wg - first;
+    return first + (r & 7) * G + (r >> 3);
+}
+
 // Toeplitz fragment = eight consecutive entries of the zero-padded tap table that travels in the
 // kernel arguments (see TapsT): one 16-byte load at a 2-byte aligned address.
 __device__ __forceinline__ half8 tap_run(const uint16_t* tab, int t0) {

@@ -476,10 +476,11 @@ __global__ void __launch_bounds__(256, 2) pyr_mfma_kernel(PyrArgs p) {
     __shared__ __attribute__((aligned(16))) float s_patch[4][RowPatch<2 * NS>::kFloats];
     __shared__ __attribute__((aligned(16))) char s_stash[4][PyrStash<NS>::kBytes];
 
-    // (tasks in plain launch order: the waves in flight then sweep down the image as one band; with
-    // the order that keeps neighbouring tasks on one XCD, eight separate bands, 8192 x 8192 took 97
-    // instead of 92 us)
-    const int wave = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+    // (of every 32 workgroups an XCD takes four neighbours: the waves in flight still sweep down the
+    // image as one band, and neighbouring strips meet in one L2.  8192 x 8192: 91.4 us, plain launch
+    // order 93.9, one contiguous eighth of the tasks per XCD, i.e. eight separate bands, 97)
+    const int wgpos = xcd_blocked(blockIdx.x, gridDim.x, 4);
+    const int wave = __builtin_amdgcn_readfirstlane(wgpos * 4 + (threadIdx.x >> 6));
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     const int ntasks = p.count();
     for (int task = wave; task < ntasks; task += nwaves) {
