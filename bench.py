@@ -25,6 +25,7 @@ prints ONE JSON line:
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import re
@@ -198,6 +199,10 @@ def main():
     # One plain copy of known size (32 MiB read, 64 MiB written), untimed: a counter run of this
     # program reads its own scale for FETCH_SIZE / WRITE_SIZE from this dispatch.
     hb.hb_copy_f16_f32(ins["sepblur"][0], outs["sepblur"][0])
+    # no collector pauses between launches: a collection during a batch shows up as tens of milliseconds
+    # of GPU idle time in that batch
+    gc.collect()
+    gc.disable()
     if args.only_row:
         sup = supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host, fir_taps, 0, 0.0, sfx, traffic_x)
         print(json.dumps({"row": args.only_row, "result": sup.get(args.only_row)}))

@@ -34,17 +34,6 @@
 #define HB_SEP_WAVES 4096     // at most this many wave tasks per launch: one resident round, no straggler round
 #endif
 
-#ifdef HB_SEP_TIMING
-__device__ unsigned long long g_sep_stamp[16384][4];      // measurement builds only
-extern "C" int hb_debug_sep_stamps(void* host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_sep_stamp), bytes);
-}
-#define SEP_STAMP(task, i) do { if ((threadIdx.x & 63) == 0 && (task) < 16384) g_sep_stamp[task][i] = wall_clock64(); } while (0)
-static __device__ int g_dbg_task_unused;
-#define g_dbg_task dbg_task_local
-#else
-#define SEP_STAMP(task, i) do { } while (0)
-#endif
 
 namespace hb {
 
@@ -207,35 +196,18 @@ __device__ __forceinline__ void sep_fragments(const SepArgs& p, int c, int g, ha
 // per lane and rows beyond the image are not stored.
 template <int NT, int NS, bool STREAM>
 __device__ __forceinline__ void sep_task_short(const SepArgs& p, float* patch,
-                                               int x0, int Y0, int xw, int c, int g, int dbg_task_local = 0) {
+                                               int x0, int Y0, int xw, int c, int g) {
     constexpr int NW = HB_SEP_TILES, NL = NS + NT - 1, NK = (NT + 1) / 2;
-#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 4)
-    const half_t* src = p.in + x0;
-#else
     const half_t* src = p.in + (x0 - xw);                 // uniform; lanes add row * pitch + 8g
-#endif
     float* dst = p.out + x0;
     half8 px[NL][NW];
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
-#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 2)
-        if (q >= NS) continue;
-#endif
         const int yr = clampi(Y0 - p.ay + 16 * q + c, 0, p.H - 1);
         const uint32_t off = ((uint32_t)yr * (uint32_t)p.in_pitch + 8u * g) * 2u;
 #pragma unroll
         for (int w = 0; w < NW; ++w) px[q][w] = ldg8(src, off + 32u * w);
-#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 1)
-#pragma unroll
-        for (int w = 1; w < NW; ++w) px[q][w] = px[q][0];
-#endif
     }
-#if defined(HB_SEP_EXP) && (HB_SEP_EXP & 2)
-#pragma unroll
-    for (int q = NS; q < NL; ++q)
-#pragma unroll
-        for (int w = 0; w < NW; ++w) px[q][w] = px[NS - 1][w];
-#endif
     // The tap tables are read only now: a wave that waited for them first would put a memory round
     // trip in front of its pixel requests.
     __builtin_amdgcn_sched_barrier(0);
@@ -250,9 +222,6 @@ __device__ __forceinline__ void sep_task_short(const SepArgs& p, float* patch,
             const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
             h[q][w] = to_half4(mfma16x16x32(px[q][w], coefx, zero));
         }
-#ifdef HB_SEP_TIMING
-        if (q == 0 || q == NL - 1) { asm volatile("" :: "v"(h[q][0]) : "memory"); SEP_STAMP(g_dbg_task, q == 0 ? 1 : 2); }
-#endif
         if (q < NT - 1) continue;
         const int s = q - (NT - 1);                       // output step completed by this tile
         floatx4 acc[NW];
@@ -308,16 +277,9 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
         const int x0 = 16 * NW * ct;
         const int Y0 = seg * p.steps * 16;
         const int nsteps = min(p.steps, (p.H - Y0 + 15) / 16);
-#ifdef HB_SEP_TIMING
-        const int dbg_task_local = task;
-        SEP_STAMP(task, 0);
-#else
-        const int dbg_task_local = 0;
-#endif
         if constexpr (NS > 0) {
             if (p.grid.interior(seg, ct)) {   // builds its fragments itself, AFTER its pixel loads are on their way
-                sep_task_short<NT, NS, STREAM>(p, s_patch[threadIdx.x >> 6], x0, Y0, xw, c, g, dbg_task_local);
-                SEP_STAMP(task, 3);
+                sep_task_short<NT, NS, STREAM>(p, s_patch[threadIdx.x >> 6], x0, Y0, xw, c, g);
                 continue;
             }
         }
@@ -325,7 +287,6 @@ __global__ void __launch_bounds__(256) sepblur_mfma_kernel(SepArgs p) {
         sep_fragments<NKX, NK>(p, c, g, coefx, coefy);
         if (p.grid.interior(seg, ct)) sep_task<NKX, NT, NW, true, STREAM>(p, p.foldx, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
         else sep_task<NKX, NT, NW, false, STREAM>(p, p.foldx, s_patch[threadIdx.x >> 6], coefx, coefy, x0, Y0, nsteps, xw, c, g);
-        SEP_STAMP(task, 3);
     }
 }
 
