@@ -89,6 +89,19 @@ def half_to_double(bits: int) -> float:
     return float(_load().hbo_half_to_double(int(bits)))
 
 
+_half_table = None
+
+
+def halves_to_doubles(bits):
+    """fp16 bit patterns -> float64 array, through the oracle's own binary16 decoder (a table of
+    all 65536 patterns, decoded once by hbo_half_to_double)."""
+    global _half_table
+    if _half_table is None:
+        f = _load().hbo_half_to_double
+        _half_table = np.array([f(b) for b in range(65536)], dtype=np.float64)
+    return _half_table[np.ascontiguousarray(bits, dtype=np.uint16)]
+
+
 def fir1d(img, taps, anchor):
     """out[y][x] = sum_r k[r] in[y][clampW(x + r - anchor)]  (Sec. V-A 1-D form)."""
     img, pi = _u16(img)
@@ -167,8 +180,7 @@ def dct_denoise(img, threshold, margin=0.0):
     out = sum_tiles(w rec) / sum_tiles(w^2).  Tile origins are (8 ty, 8 tx), 0 <= ty < H/8 - 1.
     Also returns a mask of the pixels touched by a tile with a bin within `margin` of the threshold
     (a hard threshold makes those bins, and only those, sensitive to rounding)."""
-    img, _ = _u16(img)
-    X = img.view(np.float16).astype(np.float64)
+    X = halves_to_doubles(img)
     H, W = X.shape
     assert H % 8 == 0 and W % 8 == 0 and H >= 16 and W >= 16
     D, w = dct16_matrix(), sine_window16()

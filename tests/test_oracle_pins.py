@@ -51,6 +51,9 @@ def test_half_decoder_matches_numpy_on_all_bit_patterns(orc):
     assert np.array_equal(np.isnan(mine), nan)
     assert np.array_equal(mine[~nan], ref[~nan])
     assert np.array_equal(np.signbit(mine[~nan]), np.signbit(ref[~nan]))
+    # the array form (used where the oracle's arithmetic is numpy) is the same decoder
+    arr = orc.halves_to_doubles(bits.reshape(256, 256))
+    assert arr.shape == (256, 256) and np.array_equal(arr.ravel()[~nan], ref[~nan]) and np.isnan(arr.ravel()[nan]).all()
 
 
 # --------------------------------------------------------------------------
