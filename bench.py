@@ -204,7 +204,8 @@ def main():
     gc.collect()
     gc.disable()
     if args.only_row:
-        sup = supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host, fir_taps, 0, 0.0, sfx, traffic_x)
+        sup = supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host, fir_taps, 0, 0.0, sfx, traffic_x,
+                            calls, nsets)
         print(json.dumps({"row": args.only_row, "result": sup.get(args.only_row)}))
         return
     for k in range(args.warmup):
@@ -271,14 +272,14 @@ def main():
 
     if not args.no_extra:
         out["supplementary"] = supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host,
-                                             fir_taps, total_px, ms_per_step, sfx, traffic_x)
+                                             fir_taps, total_px, ms_per_step, sfx, traffic_x, calls, nsets)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(host, fir_taps, gau_taps, total_px)
     print(json.dumps(out))
 
 
 def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, host, fir_taps, total_px,
-                  ms_per_step, sfx, traffic_x):
+                  ms_per_step, sfx, traffic_x, calls=None, nsets=None):
     """Outside the timed step: the copy ceiling, the stacked FIR, the step from a graph, and the paper's other
     case studies (matrix-unit kernel and vector-ALU twin), each with a roofline object of its ALGORITHMIC work
     (input + output bytes once, the definition's multiply-adds; Sec. V-A's accounting)."""
@@ -317,6 +318,36 @@ def supplementary(args, hb, synth, torch, dev, up, batched, step, ins, outs, hos
 
     # the same step replayed from a HIP graph (the library allocates nothing, synchronises nothing and issues
     # no memset, so its launches can be captured)
+    # the same step with its independent stages on TWO streams (the pyramid on one, the other four on the other;
+    # no stage waits for another, each stream keeps its order): the tail of one kernel overlaps the start of the
+    # next.  Not the headline figure: kernels that share the chip cannot be timed one by one, so `value`,
+    # `stages` and `roofline` come from the single-stream step.  (Three or more streams put the two longest
+    # kernels on the chip together and measured 2-3x SLOWER.)
+    if not only and calls is not None:
+        s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+        others = [st for st in STAGES if st != "pyr_level"]
+
+        def step2(k):
+            with torch.cuda.stream(s_a):
+                calls["pyr_level"](k % nsets["pyr_level"])
+            with torch.cuda.stream(s_b):
+                for st in others:
+                    calls[st](k % nsets[st])
+        for k in range(args.warmup):
+            step2(k)
+        torch.cuda.synchronize()
+        ms2 = []
+        for b in range(BATCHES):
+            t0 = time.perf_counter()
+            for k in range(args.steps):
+                step2(b * args.steps + k)
+            torch.cuda.synchronize()
+            ms2.append((time.perf_counter() - t0) * 1e3 / args.steps)
+        st2 = stats(ms2)
+        sup["five_stage_step_two_streams"] = {
+            "ms_per_step": st2["median"], "ms_min": st2["min"], "ms_max": st2["max"],
+            "gpixels_per_s": total_px / st2["median"] / 1e6, "one_stream_over_two": ms_per_step / st2["median"],
+            "streams": "pyr_level | fir1d, sepblur, sat2d, conv3x3", "batches": BATCHES, "steps_per_batch": args.steps}
     if not only:
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
