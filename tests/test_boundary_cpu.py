@@ -360,3 +360,25 @@ def test_matrix_builtins_appear_only_in_the_wrappers():
         else:
             assert not uses, f"{name} issues {uses} directly"
         assert "v_mfma" not in re.sub(r"/\*.*?\*/", "", text, flags=re.S), f"{name}: matrix instruction in inline assembly"
+
+
+def test_sat2d_noalloc_and_wait_limit_validation(lib):
+    """The allocation-free entry point checks its arguments and its size limit before it looks the
+    array's address up (no GPU needed for these paths); the wait limit is a plain process-wide value."""
+    f = lib.hb_sat2d_noalloc
+    assert f(None, FAKE, 64, 64, 64, 64, None) == hb.HB_ERR_INVALID_ARG
+    assert f(FAKE, None, 64, 64, 64, 64, None) == hb.HB_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, 0, 64, 64, 64, None) == hb.HB_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, 64, 64, 63, 64, None) == hb.HB_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, 64, 64, 64, 10, None) == hb.HB_ERR_INVALID_ARG
+    # 4096 x 4096 fits the array, 8192 x 8192 does not
+    assert lib.hb_sat2d_workspace_size(4096, 4096) <= hb.HB_SAT2D_NOALLOC_SCRATCH_BYTES
+    assert lib.hb_sat2d_workspace_size(8192, 8192) > hb.HB_SAT2D_NOALLOC_SCRATCH_BYTES
+    assert f(FAKE, FAKE, 8192, 8192, 8192, 8192, None) == hb.HB_ERR_UNSUPPORTED
+    prev = lib.hb_sat2d_set_wait_limit(123)
+    try:
+        assert lib.hb_sat2d_set_wait_limit(-5) == 123          # returns the previous limit
+        assert lib.hb_sat2d_set_wait_limit(0) == 0             # negative: "give up at once" is stored as 0
+        assert lib.hb_sat2d_set_wait_limit(7) == 16384         # 0 restored the default
+    finally:
+        lib.hb_sat2d_set_wait_limit(prev if prev > 0 else 0)
