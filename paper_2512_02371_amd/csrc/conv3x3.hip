@@ -125,22 +125,19 @@ __device__ __forceinline__ void cv_request_row(const ConvArgs& p, const CvRowOff
 #define HB_CONV_AHEAD 1
 #endif
 constexpr int kCvAhead = HB_CONV_AHEAD;
-__device__ __forceinline__ void cv_rows(const char* ring, const int (&row)[4], const half8 (&wf)[36], int c32, int h,
+// Lane part of the LDS byte address of group grp = 3 kc + kx: pixel c32 + kx, channel piece 2 kc + h,
+// which sits in slot (2 kc) ^ (h ^ s) of the pixel (s = the pixel's permutation).  The twelve values
+// are formed once per kernel: every instruction between two products costs the matrix pipe issue time.
+__device__ __forceinline__ int cv_lane_part(int grp, int c32, int h) {
+    const int kc = grp / 3, kx = grp - 3 * kc;
+    const int px = c32 + kx;
+    return px * 128 + ((32 * kc) ^ (16 * (h ^ ((px >> 1) & 7))));
+}
+__device__ __forceinline__ void cv_rows(const char* ring, const int (&row)[4], const half8 (&wf)[36], const int (&L)[12],
                                         floatx16 (&acc)[2]) {
-    // byte offset of pixel c32 + kx inside a row and the piece permutation there, per tap shift kx;
-    // group 3 kc + kx reads channel piece 2 kc + h, which sits in slot (2 kc) ^ (h ^ s)
-    c32 = cv_fresh(c32);
-    int apx[3], sw[3];
-#pragma unroll
-    for (int kx = 0; kx < 3; ++kx) {
-        const int px = c32 + kx;
-        apx[kx] = px * 128;
-        sw[kx] = 16 * (h ^ ((px >> 1) & 7));
-    }
     half8 b[kCvAhead + 1][4];
     auto read_group = [&](int grp, half8 (&dst)[4]) {
-        const int kc = grp / 3, kx = grp - 3 * kc;
-        const int a = apx[kx] + ((32 * kc) ^ sw[kx]);
+        const int a = L[grp];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) dst[rr] = *reinterpret_cast<const half8*>(ring + (a + row[rr]));
     };
@@ -252,6 +249,9 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
     }
     __syncthreads();
 
+    int L[12];
+#pragma unroll
+    for (int grp = 0; grp < 12; ++grp) L[grp] = cv_lane_part(grp, c32, h);
     int rb = 0;                                           // ring row of the tile's first row: 8 k mod 26
     for (int k = 0; k < len; ++k) {
         // the rows of tile k + 2 take the ring rows that tile k - 1 has released
@@ -274,7 +274,7 @@ __global__ void __launch_bounds__(kCvThreads) conv3x3_mfma_kernel(ConvArgs p) {
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
-        cv_rows(s_ring, row, wf, c32, h, acc);
+        cv_rows(s_ring, row, wf, L, acc);
         __builtin_amdgcn_sched_barrier(0);
         // accumulators -> stage: lane (c32, h) holds channels 32 j + 8 q + 4 h + (0..3) of pixel c32
 #pragma unroll
